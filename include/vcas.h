@@ -1,0 +1,194 @@
+/*
+ * vcas.h -- C ABI of the MI355X (gfx950) library for the sampled backward pass
+ * of a transformer linear layer Z = X W^T under VCAS, "variance-controlled
+ * adaptive sampling" (Wang, Chen, Zhu, ICLR 2024).
+ *
+ * Notation follows the paper (Sec. 4): batch N, tokens per sample T, rows
+ * R = N*T, G = grad of Z [R, K_out], X = layer input [R, K_in],
+ * W [K_out, K_in], data keep ratio rho, token keep ratio nu, data keep
+ * probabilities p[N], token keep probabilities q[R].
+ *
+ * Conventions that hold for every call:
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *    Structs (vcas_shape, vcas_rng, vcas_plan) are read on the host.
+ *  - Tensors are dense row-major.  dtype VCAS_F32: float; VCAS_BF16: 16-bit
+ *    bfloat16 bit patterns.  K_in and K_out must be multiples of 8 (one 16-byte
+ *    vector of bf16; fp32 needs only a multiple of 4 but the same rule is kept),
+ *    and tensor base addresses 16-byte aligned.
+ *  - The caller owns every buffer.  The library allocates nothing; calls that
+ *    need scratch take a `workspace` of at least vcas_workspace_bytes(shape)
+ *    bytes that was passed once to vcas_workspace_init after allocation.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream); calls return without synchronising.  Kept counts stay on
+ *    the device.  Two calls that share a workspace must be ordered (same stream).
+ *  - Errors are reported by the return value and detected on the host before
+ *    anything is launched (null pointer, non-positive size, bad dtype, keep
+ *    ratio outside (0,1], K not a multiple of 8).  Nothing throws or exits.
+ *  - Results are a pure function of the arguments: the same inputs, seed,
+ *    layer and draw give the same bits on every call and launch geometry.
+ */
+#ifndef VCAS_H
+#define VCAS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VCAS_OK = 0,
+    VCAS_EINVAL = 1,     /* size / ratio / alignment out of range */
+    VCAS_ENULL = 2,      /* required pointer is null */
+    VCAS_EDTYPE = 3,     /* dtype is neither VCAS_F32 nor VCAS_BF16 */
+    VCAS_EWORKSPACE = 4, /* workspace missing */
+    VCAS_EHIP = 5        /* a HIP launch failed; hipGetLastError has the cause */
+} vcas_status;
+
+typedef enum { VCAS_F32 = 0, VCAS_BF16 = 1 } vcas_dtype;
+
+typedef struct {
+    int32_t N, T, K_in, K_out;
+    int32_t dtype; /* vcas_dtype of G, X, W and dX */
+} vcas_shape;
+
+/* Randomness of one layer and one draw.  Row r of sampler s (0 = SampleA over
+ * samples, 1 = SampleW over tokens) is decided by the Philox4x32-10 block with
+ * counter (r, layer, s, draw) and key (seed low word, seed high word): the top
+ * 24 bits of output word 0, scaled to [0,1), are compared with the keep
+ * probability.  (The paper writes Bern(p; eps) without naming a generator.) */
+typedef struct {
+    uint64_t seed;
+    uint32_t layer;
+    uint32_t draw;
+} vcas_rng;
+
+/* Everything the sampling steps decide for one layer; all device pointers,
+ * all required, caller-allocated. */
+typedef struct {
+    float *gsq;     /* [R]  ||g_t||^2                                   */
+    float *gnorm;   /* [N]  ||G_i||_F                                   */
+    float *p;       /* [N]  data keep probabilities, sum = min(N rho, #nonzero) */
+    uint8_t *maskA; /* [N]  1 = sample kept                             */
+    int32_t *idxA;  /* [N]  kept samples, ascending; first *cntA valid  */
+    int32_t *cntA;  /* [1]                                              */
+    float *xsq;     /* [R]  ||x_t||^2 for rows of kept samples, else 0  */
+    float *score;   /* [R]  leverage score ||ghat_t|| ||x_t||           */
+    float *q;       /* [R]  token keep probabilities                    */
+    uint8_t *maskW; /* [R]  1 = token kept                              */
+    int32_t *idxW;  /* [R]  kept tokens, ascending; first *cntW valid   */
+    int32_t *cntW;  /* [1]                                              */
+    float *scaleW;  /* [R]  1/(p_i q_t) for kept tokens, else 0         */
+} vcas_plan;
+
+const char *vcas_status_string(vcas_status s);
+
+/* Bytes of scratch the calls below need for this shape (host query; 0 on a
+ * bad shape). */
+size_t vcas_workspace_bytes(const vcas_shape *shape);
+
+/* Must be called once on a freshly allocated workspace (and again after a
+ * failed launch) before it is used: clears the split-K arrival counters, which
+ * the kernels afterwards leave at zero themselves.  `bytes` is the buffer's
+ * size and must be at least vcas_workspace_bytes(shape). */
+vcas_status vcas_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/*
+ * Squared row norms, the ||.||_2^2 factors of Eq. 3 and the ||G_i||_F of
+ * Sec. 4.1.  G [R,K_out] and/or X [R,K_in] (either may be null, not both).
+ *   gsq[t]   = sum_k G[t,k]^2            (required if G is given)
+ *   gnorm[i] = sqrt(sum_{t in i} gsq[t]) (optional, needs G)
+ *   xsq[t]   = sum_k X[t,k]^2, or 0 if sample_mask is given and the row's
+ *              sample has mask 0        (required if X is given)
+ * fp32, each row summed in a fixed order that does not depend on the launch:
+ * 16-byte group j of the row goes to accumulator j mod 64, accumulators fold
+ * with fused multiply-add in ascending k and are combined pairwise at
+ * distances 32,16,8,4,2,1; gnorm likewise over the T values of a sample.
+ */
+vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X,
+                           const uint8_t *sample_mask, float *gsq, float *xsq, float *gnorm,
+                           void *stream);
+
+/*
+ * Keep probabilities proportional to score[n] (Sec. 4.1: p_i ~ ||G_i||_F with
+ * sum N rho; Sec. 4.2: q_t ~ leverage score with sum N T rho nu), capped at
+ * one: prob_i = min(1, c score_i) with c such that sum prob = min(budget,
+ * number of positive scores); zero (or negative) scores get 0.  Scores must be
+ * finite.  Sums are taken in fp64 in a fixed order; prob is fp32.
+ */
+vcas_status vcas_keep_probs(const float *score, int32_t n, double budget, float *prob, void *stream);
+
+/*
+ * Bernoulli masks and the kept-row list (Sec. 4.1 / 4.2: m = Bern(p)/p; the
+ * division is applied later as a scale).  mask[r] = [u_r < prob[r]] with u_r
+ * from vcas_rng and stream_id (0 = SampleA, 1 = SampleW); idx = kept r in
+ * ascending order (idx has room for n entries; entries past *count are left
+ * untouched); *count = number kept.
+ */
+vcas_status vcas_sample_compact(const float *prob, int32_t n, const vcas_rng *rng, uint32_t stream_id,
+                                uint8_t *mask, int32_t *idx, int32_t *count, void *stream);
+
+/* Leverage scores of Sec. 4.2 on the already data-sampled gradient:
+ * score[t] = maskA[i] * ((1/p[i]) * sqrt(gsq[t])) * sqrt(xsq[t]), fp32. */
+vcas_status vcas_leverage_scores(const vcas_shape *shape, const float *gsq, const float *xsq,
+                                 const float *p, const uint8_t *maskA, float *score, void *stream);
+
+/* scaleW[t] = maskW[t] ? 1 / (p[i] * q[t]) : 0, the product of the two masks'
+ * 1/probability factors that a kept token carries into the weight gradient. */
+vcas_status vcas_row_scale(const vcas_shape *shape, const float *p, const float *q,
+                           const uint8_t *maskW, float *scaleW, void *stream);
+
+/*
+ * Sampled activation gradient (Eq. 1, upper line; SampleA only):
+ *   dX[r,:] = (1/p[i]) * G[r,:] W   for the T rows r of every kept sample i,
+ *   dX[r,:] = 0                     for rows of dropped samples.
+ * idxA/cntA: kept samples ascending and their count (device).  dX [R,K_in] in
+ * the layer dtype is written completely.  bf16: MFMA with fp32 accumulation;
+ * fp32: fp32 MFMA.
+ */
+vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const void *W, const float *p,
+                               const int32_t *idxA, const int32_t *cntA, void *dX, void *stream);
+
+/*
+ * Sampled weight gradient (Sec. 4.2, grad_W = Gtilde^T X):
+ *   dW[o,k] = sum over the *cntW rows t = idxW[.] of row_scale[t] G[t,o] X[t,k].
+ * dW [K_out,K_in] fp32 is overwritten.  Needs the workspace (split-K partial
+ * tiles, combined in a fixed order, so the result is deterministic).
+ */
+vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X,
+                               const float *row_scale, const int32_t *idxW, const int32_t *cntW,
+                               float *dW, void *workspace, void *stream);
+
+/*
+ * The whole path for one layer and one draw, in the paper's order: row norms
+ * of G, p, SampleA mask, dX; row norms of X on kept samples, leverage scores,
+ * q, SampleW mask, scale, dW.  Fills every field of *plan.  With
+ * token_sampling = 0 SampleW is skipped (Alg. 1's "SampleA only" backward):
+ * q = maskW = the data mask repeated over tokens.  dX may be null (skip the
+ * activation gradient), dW may be null.
+ */
+vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W,
+                                 double rho, double nu, const vcas_rng *rng, int32_t token_sampling,
+                                 const vcas_plan *plan, void *dX, float *dW, void *workspace,
+                                 void *stream);
+
+/*
+ * Variance probe for the adaptive keep ratios (Sec. 4.1 variance, Eq. 3, and
+ * the Monte-Carlo lines of Alg. 1) over M mask draws, draw j using
+ * rng.draw = base->draw + j.  out[4] (device, fp64):
+ *   out[0] = sum_i (1-p_i)/p_i ||G_i||_F^2
+ *   out[1] = mean_j of Eq. 3, sum_t (1-q_t)/q_t score_t^2, under draw j's data mask
+ *   out[2] = mean_j ||dW(SampleA only, draw j) - dW exact||_F^2
+ *   out[3] = mean_j ||dW(SampleA and SampleW, draw j) - dW exact||_F^2
+ * dW exact is this library's dW at keep ratio one.  `plan` is scratch for the
+ * draws (left holding the last one).
+ */
+vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho,
+                                double nu, const vcas_rng *base, int32_t M, const vcas_plan *plan,
+                                double *out, void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VCAS_H */

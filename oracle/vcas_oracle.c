@@ -189,19 +189,28 @@ void orc_sample_norms(const float *gsq, int N, int T, float *gnorm)
 
 /* --------------------------- keep probabilities (Sec. 4.1, Sec. 4.2) */
 
-/* fp64 sum in the written-down "1024-slot" order: slot = i mod 1024,
- * ascending inside a slot, then halving tree (j, j+512), (j, j+256), ... */
+/* fp64 sum in the written-down "1024-slot" order: slot = i mod 1024, ascending
+ * inside a slot; each run of 64 consecutive slots is halved pairwise
+ * (j, j+32), (j, j+16), ... (j, j+1); the 16 run sums are then halved pairwise
+ * (j, j+8), ... (j, j+1). */
 static double slot_sum(const double *v, int n)
 {
-    double part[1024];
+    double part[1024], run[16];
     for (int s = 0; s < 1024; ++s)
         part[s] = 0.0;
     for (int i = 0; i < n; ++i)
         part[i % 1024] += v[i];
-    for (int half = 512; half >= 1; half >>= 1)
+    for (int r = 0; r < 16; ++r) {
+        double *g = part + 64 * r;
+        for (int half = 32; half >= 1; half >>= 1)
+            for (int j = 0; j < half; ++j)
+                g[j] = g[j] + g[j + half];
+        run[r] = g[0];
+    }
+    for (int half = 8; half >= 1; half >>= 1)
         for (int j = 0; j < half; ++j)
-            part[j] = part[j] + part[j + half];
-    return part[0];
+            run[j] = run[j] + run[j + half];
+    return run[0];
 }
 
 /*

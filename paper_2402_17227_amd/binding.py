@@ -1,0 +1,188 @@
+"""ctypes binding of libvcas.so: same names as the C ABI (include/vcas.h),
+argument marshalling only.  PyTorch supplies device memory and the stream;
+every step of the path runs in the library's kernels.  There is no CPU
+fallback: a missing library or a failing call raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch  # first: libvcas.so then binds to the HIP runtime torch has loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvcas.so")
+
+VCAS_F32, VCAS_BF16 = 0, 1
+STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: "VCAS_EWORKSPACE", 5: "VCAS_EHIP"}
+
+EXPORTS = [
+    "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
+    "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
+    "vcas_linear_backward", "vcas_variance_probe",
+]
+
+
+class VcasError(RuntimeError):
+    pass
+
+
+class Shape(C.Structure):
+    _fields_ = [("N", C.c_int32), ("T", C.c_int32), ("K_in", C.c_int32), ("K_out", C.c_int32), ("dtype", C.c_int32)]
+
+
+class Rng(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("layer", C.c_uint32), ("draw", C.c_uint32)]
+
+
+class PlanPtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("gsq", "gnorm", "p", "maskA", "idxA", "cntA", "xsq", "score", "q",
+                                          "maskW", "idxW", "cntW", "scaleW")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libvcas.so (build it first with paper_2402_17227_amd.build.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise VcasError(f"{LIB_PATH} is missing: run `python -m paper_2402_17227_amd.build` first")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.vcas_status_string.restype = C.c_char_p
+        _lib.vcas_workspace_bytes.restype = C.c_size_t
+        _lib.vcas_workspace_bytes.argtypes = [C.POINTER(Shape)]
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise VcasError(f"{what}: {STATUS.get(status, status)} ({lib().vcas_status_string(status).decode()})")
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def shape_of(N: int, T: int, K_in: int, K_out: int, dtype: int) -> Shape:
+    return Shape(N, T, K_in, K_out, dtype)
+
+
+def dtype_of(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return VCAS_BF16
+    if t.dtype == torch.float32:
+        return VCAS_F32
+    raise VcasError(f"unsupported dtype {t.dtype}")
+
+
+@dataclass
+class Plan:
+    """Device buffers for everything the sampling steps decide (vcas_plan)."""
+    gsq: torch.Tensor
+    gnorm: torch.Tensor
+    p: torch.Tensor
+    maskA: torch.Tensor
+    idxA: torch.Tensor
+    cntA: torch.Tensor
+    xsq: torch.Tensor
+    score: torch.Tensor
+    q: torch.Tensor
+    maskW: torch.Tensor
+    idxW: torch.Tensor
+    cntW: torch.Tensor
+    scaleW: torch.Tensor
+
+    @staticmethod
+    def allocate(N: int, T: int, device="cuda") -> "Plan":
+        R = N * T
+        f = dict(dtype=torch.float32, device=device)
+        return Plan(gsq=torch.empty(R, **f), gnorm=torch.empty(N, **f), p=torch.empty(N, **f),
+                    maskA=torch.empty(N, dtype=torch.uint8, device=device),
+                    idxA=torch.empty(N, dtype=torch.int32, device=device),
+                    cntA=torch.zeros(1, dtype=torch.int32, device=device),
+                    xsq=torch.empty(R, **f), score=torch.empty(R, **f), q=torch.empty(R, **f),
+                    maskW=torch.empty(R, dtype=torch.uint8, device=device),
+                    idxW=torch.empty(R, dtype=torch.int32, device=device),
+                    cntW=torch.zeros(1, dtype=torch.int32, device=device), scaleW=torch.empty(R, **f))
+
+    def ptrs(self) -> PlanPtrs:
+        return PlanPtrs(*[t.data_ptr() for t in (self.gsq, self.gnorm, self.p, self.maskA, self.idxA, self.cntA,
+                                                  self.xsq, self.score, self.q, self.maskW, self.idxW, self.cntW,
+                                                  self.scaleW)])
+
+
+def vcas_workspace_bytes(shape: Shape) -> int:
+    return int(lib().vcas_workspace_bytes(C.byref(shape)))
+
+
+def vcas_workspace_init(workspace: torch.Tensor):
+    _check(lib().vcas_workspace_init(_ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                                     _stream()), "vcas_workspace_init")
+
+
+def make_workspace(shape: Shape, device="cuda") -> torch.Tensor:
+    nbytes = vcas_workspace_bytes(shape)
+    if nbytes == 0:
+        raise VcasError("bad shape")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    vcas_workspace_init(ws)
+    return ws
+
+
+def vcas_row_norms(shape: Shape, G, X, sample_mask, gsq, xsq, gnorm):
+    _check(lib().vcas_row_norms(C.byref(shape), _ptr(G), _ptr(X), _ptr(sample_mask), _ptr(gsq), _ptr(xsq),
+                                _ptr(gnorm), _stream()), "vcas_row_norms")
+
+
+def vcas_keep_probs(score, n: int, budget: float, prob):
+    _check(lib().vcas_keep_probs(_ptr(score), C.c_int32(n), C.c_double(budget), _ptr(prob), _stream()),
+           "vcas_keep_probs")
+
+
+def vcas_sample_compact(prob, n: int, rng: Rng, stream_id: int, mask, idx, count):
+    _check(lib().vcas_sample_compact(_ptr(prob), C.c_int32(n), C.byref(rng), C.c_uint32(stream_id), _ptr(mask),
+                                     _ptr(idx), _ptr(count), _stream()), "vcas_sample_compact")
+
+
+def vcas_leverage_scores(shape: Shape, gsq, xsq, p, maskA, score):
+    _check(lib().vcas_leverage_scores(C.byref(shape), _ptr(gsq), _ptr(xsq), _ptr(p), _ptr(maskA), _ptr(score),
+                                      _stream()), "vcas_leverage_scores")
+
+
+def vcas_row_scale(shape: Shape, p, q, maskW, scaleW):
+    _check(lib().vcas_row_scale(C.byref(shape), _ptr(p), _ptr(q), _ptr(maskW), _ptr(scaleW), _stream()),
+           "vcas_row_scale")
+
+
+def vcas_sampled_dgrad(shape: Shape, G, W, p, idxA, cntA, dX):
+    _check(lib().vcas_sampled_dgrad(C.byref(shape), _ptr(G), _ptr(W), _ptr(p), _ptr(idxA), _ptr(cntA), _ptr(dX),
+                                    _stream()), "vcas_sampled_dgrad")
+
+
+def vcas_sampled_wgrad(shape: Shape, G, X, row_scale, idxW, cntW, dW, workspace):
+    _check(lib().vcas_sampled_wgrad(C.byref(shape), _ptr(G), _ptr(X), _ptr(row_scale), _ptr(idxW), _ptr(cntW),
+                                    _ptr(dW), _ptr(workspace), _stream()), "vcas_sampled_wgrad")
+
+
+def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan,
+                         dX, dW, workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_linear_backward(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.c_double(nu),
+                                      C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
+                                      _ptr(dW), _ptr(workspace), _stream()), "vcas_linear_backward")
+
+
+def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M: int, plan: Plan, out, workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_variance_probe(C.byref(shape), _ptr(G), _ptr(X), C.c_double(rho), C.c_double(nu),
+                                     C.byref(base), C.c_int32(M), C.byref(ptrs), _ptr(out), _ptr(workspace),
+                                     _stream()), "vcas_variance_probe")

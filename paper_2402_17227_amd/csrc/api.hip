@@ -1,0 +1,332 @@
+// C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
+// launches on the caller's stream.  See include/vcas.h for the contract.
+#include "common.hpp"
+
+namespace vcas {
+
+// norms.hip
+vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
+                      hipStream_t st);
+vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st);
+// sampling.hip
+vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st);
+vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32_t stream_id, uint8_t *mask,
+                           int32_t *idx, int32_t *count, hipStream_t st);
+vcas_status compact_only(const uint8_t *mask, int n, int32_t *idx, int32_t *count, hipStream_t st);
+vcas_status leverage_scores(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, int64_t R,
+                            int T, float *score, hipStream_t st);
+vcas_status row_scale(const float *p, const float *q, const uint8_t *maskW, int64_t R, int T, float *scale,
+                      hipStream_t st);
+vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q, uint8_t *maskW, hipStream_t st);
+// gemm_bf16.hip / gemm_f32.hip
+int wgrad_tiles_bf16(int K_out, int K_in);
+int wgrad_tiles_f32(int K_out, int K_in);
+vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
+                       const int32_t *cntA, void *dX, hipStream_t st);
+vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
+                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int32_t *counters,
+                       int splits, hipStream_t st);
+vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
+                      const int32_t *cntA, void *dX, hipStream_t st);
+vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
+                      const int32_t *cntW, float *dW, float *partials, int32_t *counters, int splits, hipStream_t st);
+
+// Split-K slices of the weight gradient: enough workgroups to cover the chip
+// about twice, at most kMaxSplit, and never so many that a slice at full
+// length R would have fewer than 4 contraction steps.
+int wgrad_split(const vcas_shape *s)
+{
+    const bool bf = s->dtype == VCAS_BF16;
+    const int tiles = bf ? wgrad_tiles_bf16(s->K_out, s->K_in) : wgrad_tiles_f32(s->K_out, s->K_in);
+    const int64_t R = (int64_t)s->N * s->T;
+    const int64_t steps = (R + (bf ? 63 : 15)) / (bf ? 64 : 16);
+    int64_t want = (512 + tiles - 1) / tiles;
+    int64_t cap = steps / (bf ? 4 : 8);
+    if (want > cap) want = cap;
+    if (want > kMaxSplit) want = kMaxSplit;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// ---- variance probe reductions (fp64) ---------------------------------------
+
+// out[slot] (+)= weight * sum_i (1-p_i)/p_i * n_i^2 over p_i > 0; one block.
+__global__ __launch_bounds__(256) void var_closed_kernel(const float *__restrict__ prob, const float *__restrict__ val,
+                                                         int64_t n, int square_val, double weight, int accumulate,
+                                                         double *__restrict__ out)
+{
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) {
+        const double pr = prob[i];
+        if (pr > 0.0) {
+            const double v = val[i];
+            acc += (1.0 - pr) / pr * (square_val ? v * v : v);
+        }
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int h = 128; h >= 1; h >>= 1) {
+        if ((int)threadIdx.x < h) sh[threadIdx.x] += sh[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = (accumulate ? *out : 0.0) + weight * sh[0];
+}
+
+// per-block partial sums of (a-b)^2, then a one-block pass adds them in order
+__global__ __launch_bounds__(256) void sq_diff_partial_kernel(const float *__restrict__ a, const float *__restrict__ b,
+                                                              int64_t n, double *__restrict__ partial)
+{
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const double d = (double)a[i] - (double)b[i];
+        acc += d * d;
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int h = 128; h >= 1; h >>= 1) {
+        if ((int)threadIdx.x < h) sh[threadIdx.x] += sh[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = sh[0];
+}
+
+__global__ __launch_bounds__(64) void sq_diff_final_kernel(const double *__restrict__ partial, int blocks,
+                                                           double weight, double *__restrict__ out)
+{
+    if (threadIdx.x != 0) return;
+    double s = 0.0;
+    for (int i = 0; i < blocks; ++i) s += partial[i];
+    *out += weight * s;
+}
+
+static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
+                                  const int32_t *idxA, const int32_t *cntA, void *dX, hipStream_t st)
+{
+    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, st)
+                                : dgrad_f32(s, G, W, p, idxA, cntA, dX, st);
+}
+
+static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
+                                  const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
+                                  hipStream_t st)
+{
+    const WorkspaceLayout w = workspace_layout(&s);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    int32_t *counters = reinterpret_cast<int32_t *>(base + w.counters);
+    float *partials = reinterpret_cast<float *>(base + w.partials);
+    const int splits = wgrad_split(&s);
+    return s.dtype == VCAS_BF16 ? wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, counters, splits, st)
+                                : wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, counters, splits, st);
+}
+
+static bool plan_complete(const vcas_plan *pl)
+{
+    return pl && pl->gsq && pl->gnorm && pl->p && pl->maskA && pl->idxA && pl->cntA && pl->xsq && pl->score &&
+           pl->q && pl->maskW && pl->idxW && pl->cntW && pl->scaleW;
+}
+
+static bool ratio_ok(double r) { return r > 0.0 && r <= 1.0; }
+
+#define VCAS_TRY(expr)                      \
+    do {                                    \
+        vcas_status st__ = (expr);          \
+        if (st__ != VCAS_OK) return st__;   \
+    } while (0)
+
+static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
+                                        double nu, const vcas_rng &rng, int token_sampling, const vcas_plan &pl,
+                                        void *dX, float *dW, void *workspace, hipStream_t st)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
+    VCAS_TRY(sample_norms(pl.gsq, s.N, s.T, pl.gnorm, st));
+    VCAS_TRY(keep_probs(pl.gnorm, s.N, (double)s.N * rho, pl.p, st));
+    VCAS_TRY(sample_compact(pl.p, s.N, rng, 0u, pl.maskA, pl.idxA, pl.cntA, st));
+    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
+    VCAS_TRY(row_sumsq(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, st));
+    VCAS_TRY(leverage_scores(pl.gsq, pl.xsq, pl.p, pl.maskA, R, s.T, pl.score, st));
+    if (token_sampling) {
+        VCAS_TRY(keep_probs(pl.score, (int)R, (double)R * rho * nu, pl.q, st));
+        VCAS_TRY(sample_compact(pl.q, (int)R, rng, 1u, pl.maskW, pl.idxW, pl.cntW, st));
+    } else {
+        VCAS_TRY(broadcast_data_mask(pl.maskA, R, s.T, pl.q, pl.maskW, st));
+        VCAS_TRY(compact_only(pl.maskW, (int)R, pl.idxW, pl.cntW, st));
+    }
+    VCAS_TRY(row_scale(pl.p, pl.q, pl.maskW, R, s.T, pl.scaleW, st));
+    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+    return VCAS_OK;
+}
+
+}  // namespace vcas
+
+using namespace vcas;
+
+extern "C" {
+
+const char *vcas_status_string(vcas_status s)
+{
+    switch (s) {
+    case VCAS_OK: return "ok";
+    case VCAS_EINVAL: return "invalid size, ratio or alignment";
+    case VCAS_ENULL: return "required pointer is null";
+    case VCAS_EDTYPE: return "unknown dtype";
+    case VCAS_EWORKSPACE: return "workspace missing";
+    case VCAS_EHIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+size_t vcas_workspace_bytes(const vcas_shape *shape)
+{
+    if (check_shape(shape) != VCAS_OK) return 0;
+    return workspace_layout(shape).total;
+}
+
+vcas_status vcas_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (bytes < kCounterBytes) return VCAS_EINVAL;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((kCounterInts + 255) / 256)), dim3(256), 0, as_stream(stream),
+                       static_cast<uint32_t *>(workspace), kCounterInts);
+    return launch_status();
+}
+
+vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X, const uint8_t *sample_mask,
+                           float *gsq, float *xsq, float *gnorm, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!G && !X) return VCAS_ENULL;
+    if (G && !gsq) return VCAS_ENULL;
+    if (X && !xsq) return VCAS_ENULL;
+    if (gnorm && !G) return VCAS_ENULL;
+    if ((G && !aligned16(G)) || (X && !aligned16(X))) return VCAS_EINVAL;
+    const int64_t R = (int64_t)shape->N * shape->T;
+    hipStream_t st = as_stream(stream);
+    if (G) {
+        VCAS_TRY(row_sumsq(G, shape->dtype, R, shape->K_out, shape->T, nullptr, gsq, st));
+        if (gnorm) VCAS_TRY(sample_norms(gsq, shape->N, shape->T, gnorm, st));
+    }
+    if (X) VCAS_TRY(row_sumsq(X, shape->dtype, R, shape->K_in, shape->T, sample_mask, xsq, st));
+    return VCAS_OK;
+}
+
+vcas_status vcas_keep_probs(const float *score, int32_t n, double budget, float *prob, void *stream)
+{
+    if (n < 0 || !(budget >= 0.0)) return VCAS_EINVAL;
+    if (n == 0) return VCAS_OK;
+    if (!score || !prob) return VCAS_ENULL;
+    return keep_probs(score, n, budget, prob, as_stream(stream));
+}
+
+vcas_status vcas_sample_compact(const float *prob, int32_t n, const vcas_rng *rng, uint32_t stream_id, uint8_t *mask,
+                                int32_t *idx, int32_t *count, void *stream)
+{
+    if (n < 0) return VCAS_EINVAL;
+    if (!rng || !count) return VCAS_ENULL;
+    if (n > 0 && (!prob || !mask || !idx)) return VCAS_ENULL;
+    return sample_compact(prob, n, *rng, stream_id, mask, idx, count, as_stream(stream));
+}
+
+vcas_status vcas_leverage_scores(const vcas_shape *shape, const float *gsq, const float *xsq, const float *p,
+                                 const uint8_t *maskA, float *score, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!gsq || !xsq || !p || !maskA || !score) return VCAS_ENULL;
+    return leverage_scores(gsq, xsq, p, maskA, (int64_t)shape->N * shape->T, shape->T, score, as_stream(stream));
+}
+
+vcas_status vcas_row_scale(const vcas_shape *shape, const float *p, const float *q, const uint8_t *maskW,
+                           float *scaleW, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!p || !q || !maskW || !scaleW) return VCAS_ENULL;
+    return row_scale(p, q, maskW, (int64_t)shape->N * shape->T, shape->T, scaleW, as_stream(stream));
+}
+
+vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const void *W, const float *p,
+                               const int32_t *idxA, const int32_t *cntA, void *dX, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!G || !W || !p || !idxA || !cntA || !dX) return VCAS_ENULL;
+    if (!aligned16(G) || !aligned16(W) || !aligned16(dX)) return VCAS_EINVAL;
+    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, as_stream(stream));
+}
+
+vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X, const float *row_scale_,
+                               const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!aligned16(G) || !aligned16(X) || !aligned16(dW) || !aligned16(workspace)) return VCAS_EINVAL;
+    return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, as_stream(stream));
+}
+
+vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
+                                 double nu, const vcas_rng *rng, int32_t token_sampling, const vcas_plan *plan,
+                                 void *dX, float *dW, void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (dX && !W) return VCAS_ENULL;
+    if (dW && !workspace) return VCAS_EWORKSPACE;
+    if (!ratio_ok(rho) || !ratio_ok(nu)) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || (dW && !aligned16(dW)) ||
+        (workspace && !aligned16(workspace)))
+        return VCAS_EINVAL;
+    return linear_backward_impl(*shape, G, X, W, rho, nu, *rng, token_sampling, *plan, dX, dW, workspace,
+                                as_stream(stream));
+}
+
+vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,
+                                const vcas_rng *base, int32_t M, const vcas_plan *plan, double *out, void *workspace,
+                                void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!G || !X || !base || !out || !plan_complete(plan)) return VCAS_ENULL;
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!ratio_ok(rho) || !ratio_ok(nu) || M <= 0) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(X) || !aligned16(workspace)) return VCAS_EINVAL;
+    const vcas_shape &s = *shape;
+    hipStream_t st = as_stream(stream);
+    const WorkspaceLayout w = workspace_layout(&s);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    float *exact = reinterpret_cast<float *>(ws + w.probe_exact);
+    float *draw = reinterpret_cast<float *>(ws + w.probe_draw);
+    double *partial = reinterpret_cast<double *>(ws + w.probe_acc);  // 32 doubles
+    const int64_t R = (int64_t)s.N * s.T, nW = (int64_t)s.K_out * s.K_in;
+    const int blocks = 32;
+    const double wgt = 1.0 / (double)M;
+
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t *>(out), (size_t)8);
+    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    vcas_rng rng = *base;
+    VCAS_TRY(linear_backward_impl(s, G, X, nullptr, 1.0, 1.0, rng, 1, *plan, nullptr, exact, workspace, st));
+    for (int j = 0; j < M; ++j) {
+        rng.draw = base->draw + (uint32_t)j;
+        // SampleA only
+        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 0, *plan, nullptr, draw, workspace, st));
+        hipLaunchKernelGGL(sq_diff_partial_kernel, dim3(blocks), dim3(256), 0, st, draw, exact, nW, partial);
+        hipLaunchKernelGGL(sq_diff_final_kernel, dim3(1), dim3(64), 0, st, partial, blocks, wgt, out + 2);
+        // SampleA and SampleW
+        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 1, *plan, nullptr, draw, workspace, st));
+        hipLaunchKernelGGL(sq_diff_partial_kernel, dim3(blocks), dim3(256), 0, st, draw, exact, nW, partial);
+        hipLaunchKernelGGL(sq_diff_final_kernel, dim3(1), dim3(64), 0, st, partial, blocks, wgt, out + 3);
+        if (j == 0)
+            hipLaunchKernelGGL(var_closed_kernel, dim3(1), dim3(256), 0, st, plan->p, plan->gnorm, (int64_t)s.N, 1,
+                               1.0, 0, out + 0);
+        hipLaunchKernelGGL(var_closed_kernel, dim3(1), dim3(256), 0, st, plan->q, plan->score, R, 1, wgt, 1, out + 1);
+        if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    }
+    return VCAS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+// Shared host/device helpers of the VCAS gfx950 library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vcas.h"
+
+namespace vcas {
+
+constexpr int kWave = 64;
+
+// ---- launch bookkeeping -----------------------------------------------------
+
+inline vcas_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? VCAS_OK : VCAS_EHIP;
+}
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline vcas_status check_shape(const vcas_shape *s)
+{
+    if (!s) return VCAS_ENULL;
+    if (s->dtype != VCAS_F32 && s->dtype != VCAS_BF16) return VCAS_EDTYPE;
+    if (s->N <= 0 || s->T <= 0 || s->K_in <= 0 || s->K_out <= 0) return VCAS_EINVAL;
+    if ((s->K_in % 8) != 0 || (s->K_out % 8) != 0) return VCAS_EINVAL;
+    if ((int64_t)s->N * s->T > (int64_t)1 << 30) return VCAS_EINVAL;
+    return VCAS_OK;
+}
+
+inline int elem_bytes(int dtype) { return dtype == VCAS_BF16 ? 2 : 4; }
+
+// ---- workspace layout -------------------------------------------------------
+// [0, kCounterBytes)          split-K arrival counters (int32), zero between calls
+// [kCounterBytes, +partials)  split-K partial tiles of the weight gradient (fp32)
+// then two K_out*K_in fp32 matrices and 8 doubles for the variance probe
+
+constexpr size_t kCounterInts = 16384;
+constexpr size_t kCounterBytes = kCounterInts * sizeof(int32_t);
+constexpr int kMaxSplit = 16;
+
+struct WorkspaceLayout {
+    size_t counters, partials, probe_exact, probe_draw, probe_acc, total;
+};
+
+int wgrad_split(const vcas_shape *s);   // host: number of split-K slices for this shape
+
+inline WorkspaceLayout workspace_layout(const vcas_shape *s)
+{
+    WorkspaceLayout w;
+    size_t mat = (size_t)s->K_out * s->K_in * sizeof(float);
+    w.counters = 0;
+    w.partials = kCounterBytes;
+    w.probe_exact = w.partials + mat * (size_t)wgrad_split(s);
+    w.probe_draw = w.probe_exact + mat;
+    w.probe_acc = w.probe_draw + mat;
+    w.total = w.probe_acc + 256;
+    return w;
+}
+
+// ---- device helpers ---------------------------------------------------------
+
+// bf16 halves of a packed pair; element k (even) is the low half.
+__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
+
+// Sum over the 64 lanes by pairwise exchange at distances 32,16,8,4,2,1.
+// Every lane ends with the same value.
+__device__ __forceinline__ float wave_exchange_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = v + __shfl_xor(v, d, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double wave_exchange_sum(double v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = v + __shfl_xor(v, d, kWave);
+    return v;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11, Sec. 3.3); returns output word 0.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                        uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t h0 = __umulhi(M0, c0), l0 = M0 * c0;
+        uint32_t h1 = __umulhi(M1, c2), l1 = M1 * c2;
+        uint32_t n0 = h1 ^ c1 ^ k0;
+        uint32_t n2 = h0 ^ c3 ^ k1;
+        c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+// Uniform in [0,1) that decides row `row` of sampler `stream_id`.
+__device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t layer, uint32_t stream_id, uint32_t draw,
+                                                uint32_t row)
+{
+    uint32_t w = philox4x32_10_word0(row, layer, stream_id, draw, (uint32_t)seed, (uint32_t)(seed >> 32));
+    return (float)(w >> 8) * 0x1.0p-24f;
+}
+
+}  // namespace vcas

@@ -1,0 +1,116 @@
+// Row-norm kernels: squared 2-norms of the rows of G and X (the factors of
+// Eq. 3 and the per-sample Frobenius norms of Sec. 4.1 of the VCAS paper).
+// HBM-bound: every element is read once, one fp32 per row is written.
+//
+// Summation order (fixed, independent of the launch): 16-byte group j of a row
+// belongs to lane j mod 64; a lane folds its elements in ascending k with
+// acc = fma(v, v, acc); lanes are combined by exchange steps 32,16,8,4,2,1.
+#include "common.hpp"
+
+namespace vcas {
+
+template <bool BF16>
+__device__ __forceinline__ float fold16(const uint4 &c, float acc)
+{
+    if constexpr (BF16) {
+        acc = __builtin_fmaf(bf16_lo(c.x), bf16_lo(c.x), acc);
+        acc = __builtin_fmaf(bf16_hi(c.x), bf16_hi(c.x), acc);
+        acc = __builtin_fmaf(bf16_lo(c.y), bf16_lo(c.y), acc);
+        acc = __builtin_fmaf(bf16_hi(c.y), bf16_hi(c.y), acc);
+        acc = __builtin_fmaf(bf16_lo(c.z), bf16_lo(c.z), acc);
+        acc = __builtin_fmaf(bf16_hi(c.z), bf16_hi(c.z), acc);
+        acc = __builtin_fmaf(bf16_lo(c.w), bf16_lo(c.w), acc);
+        acc = __builtin_fmaf(bf16_hi(c.w), bf16_hi(c.w), acc);
+    } else {
+        float a = __uint_as_float(c.x), b = __uint_as_float(c.y), d = __uint_as_float(c.z), e = __uint_as_float(c.w);
+        acc = __builtin_fmaf(a, a, acc);
+        acc = __builtin_fmaf(b, b, acc);
+        acc = __builtin_fmaf(d, d, acc);
+        acc = __builtin_fmaf(e, e, acc);
+    }
+    return acc;
+}
+
+// One wavefront per row; CH 16-byte groups per lane are in flight at once.
+// Rows of samples whose sample_keep byte is 0 are not read and get 0.
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
+                                                        int T, const uint8_t *__restrict__ sample_keep,
+                                                        float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t row = wave; row < R; row += nwaves) {
+        if (sample_keep && sample_keep[row / T] == 0) {
+            if (lane == 0) out[row] = 0.0f;
+            continue;
+        }
+        const uint4 *p = A + row * groups_per_row;
+        float acc = 0.0f;
+        for (int base = 0; base < groups_per_row; base += 64 * CH) {
+            uint4 v[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                int g = base + lane + 64 * j;
+                v[j] = g < groups_per_row ? p[g] : make_uint4(0u, 0u, 0u, 0u);
+            }
+            // a zero group leaves acc unchanged (fma(0,0,acc) == acc for acc >= +0)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) acc = fold16<BF16>(v[j], acc);
+        }
+        acc = wave_exchange_sum(acc);
+        if (lane == 0) out[row] = acc;
+    }
+}
+
+// ||G_i||_F: value t of a sample belongs to lane t mod 64, plain fp32 adds in
+// ascending t, exchange steps, correctly rounded sqrt.  One wavefront per sample.
+__global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restrict__ gsq, int N, int T,
+                                                          float *__restrict__ gnorm)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= N) return;
+    const float *p = gsq + (int64_t)i * T;
+    float acc = 0.0f;
+    for (int t = lane; t < T; t += 64) acc = acc + p[t];
+    acc = wave_exchange_sum(acc);
+    if (lane == 0) gnorm[i] = __fsqrt_rn(acc);
+}
+
+template <bool BF16>
+static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, const uint8_t *keep, float *out,
+                                    hipStream_t st)
+{
+    const int groups = K / (BF16 ? 8 : 4);
+    const int need = (groups + 63) / 64;
+    int64_t blocks64 = (R + 3) / 4;
+    const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
+    const uint4 *a = static_cast<const uint4 *>(A);
+#define VCAS_LAUNCH_CH(C) \
+    hipLaunchKernelGGL((row_sumsq_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, R, groups, T, keep, out)
+    if (need <= 1) VCAS_LAUNCH_CH(1);
+    else if (need <= 2) VCAS_LAUNCH_CH(2);
+    else if (need <= 3) VCAS_LAUNCH_CH(3);
+    else if (need <= 4) VCAS_LAUNCH_CH(4);
+    else if (need <= 6) VCAS_LAUNCH_CH(6);
+    else VCAS_LAUNCH_CH(8);
+#undef VCAS_LAUNCH_CH
+    return launch_status();
+}
+
+vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
+                      hipStream_t st)
+{
+    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, st)
+                              : launch_row_sumsq<false>(A, R, K, T, keep, out, st);
+}
+
+vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st)
+{
+    hipLaunchKernelGGL(sample_norm_kernel, dim3((N + 3) / 4), dim3(256), 0, st, gsq, N, T, gnorm);
+    return launch_status();
+}
+
+}  // namespace vcas

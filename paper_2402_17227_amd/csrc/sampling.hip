@@ -1,0 +1,258 @@
+// Sampling kernels of the VCAS backward pass: capped-proportional keep
+// probabilities (Sec. 4.1 p_i ~ ||G_i||_F, Sec. 4.2 q_t ~ leverage score),
+// Philox Bernoulli masks, kept-row compaction, and the two small elementwise
+// steps (leverage scores, per-row scale).  All vectors are at most R floats,
+// so these kernels are latency-bound, not bandwidth-bound.
+#include "common.hpp"
+
+namespace vcas {
+
+// ---- block-wide sums over 1024 threads in a fixed order ---------------------
+// Thread tid is "slot" tid.  Each 64-slot group is combined by exchange steps
+// 32..1, then the 16 group sums by exchange steps 8,4,2,1.  Every thread
+// returns the total.  `buf` is 16 values of LDS; calls must alternate buffers
+// or be separated by a barrier.
+
+__device__ __forceinline__ double block_sum_1024(double v, double *buf)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_exchange_sum(v);
+    if (lane == 0) buf[wave] = v;
+    __syncthreads();
+    double t = buf[lane & 15];
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) t = t + __shfl_xor(t, d, kWave);
+    return t;
+}
+
+__device__ __forceinline__ int block_sum_1024(int v, int *buf)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    if (lane == 0) buf[wave] = v;
+    __syncthreads();
+    int t = buf[lane & 15];
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) t += __shfl_xor(t, d, kWave);
+    return t;
+}
+
+// prob_i = min(1, c * score_i), sum prob = min(budget, #positive scores).
+// c is found by rounds: every not-yet-fixed entry that the current c pushes to
+// >= 1 is fixed at one, then c is recomputed from what is left, until a round
+// fixes nothing.  Sums in fp64, slot = i mod 1024, ascending i inside a slot.
+// While running, prob[i] == 1 marks "fixed at one" (each element is only ever
+// touched by its own thread).  Single block of 1024 threads.
+__device__ void keep_probs_block(const float *__restrict__ score, int n, double budget, float *__restrict__ prob)
+{
+    __shared__ double sd[2][16];
+    __shared__ int si[2][16];
+    const int tid = threadIdx.x;
+
+    double part = 0.0;
+    int cnt = 0;
+    for (int i = tid; i < n; i += 1024) {
+        float a = score[i];
+        if (a > 0.0f) {
+            part += (double)a;
+            ++cnt;
+        }
+        prob[i] = 0.0f;
+    }
+    double S = block_sum_1024(part, sd[0]);
+    const int nonzero = block_sum_1024(cnt, si[0]);
+
+    if (budget >= (double)nonzero) {
+        for (int i = tid; i < n; i += 1024) prob[i] = score[i] > 0.0f ? 1.0f : 0.0f;
+        return;
+    }
+
+    int ncap = 0;
+    double c = 0.0;
+    int flip = 1;
+    for (;;) {
+        const double rem = budget - (double)ncap;
+        if (!(S > 0.0) || !(rem > 0.0)) {
+            c = 0.0;
+            break;
+        }
+        c = rem / S;
+        part = 0.0;
+        cnt = 0;
+        for (int i = tid; i < n; i += 1024) {
+            float a = score[i];
+            if (a > 0.0f && prob[i] != 1.0f) {
+                if (c * (double)a >= 1.0) {
+                    prob[i] = 1.0f;
+                    ++cnt;
+                } else {
+                    part += (double)a;
+                }
+            }
+        }
+        const double S_next = block_sum_1024(part, sd[flip]);
+        const int newly = block_sum_1024(cnt, si[flip]);
+        flip ^= 1;
+        if (newly == 0) break;
+        ncap += newly;
+        S = S_next;
+    }
+    for (int i = tid; i < n; i += 1024) {
+        float a = score[i];
+        if (prob[i] == 1.0f) continue;
+        float p = 0.0f;
+        if (a > 0.0f) {
+            p = (float)(c * (double)a);
+            p = p < 1.0f ? p : 1.0f;
+        }
+        prob[i] = p;
+    }
+}
+
+__global__ __launch_bounds__(1024) void keep_probs_kernel(const float *__restrict__ score, int n, double budget,
+                                                          float *__restrict__ prob)
+{
+    keep_probs_block(score, n, budget, prob);
+}
+
+// mask[r] = [u_r < prob[r]]
+__global__ __launch_bounds__(256) void bernoulli_mask_kernel(const float *__restrict__ prob, int n, uint64_t seed,
+                                                             uint32_t layer, uint32_t stream_id, uint32_t draw,
+                                                             uint8_t *__restrict__ mask)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= n) return;
+    const float u = philox_uniform(seed, layer, stream_id, draw, (uint32_t)r);
+    mask[r] = u < prob[r] ? 1 : 0;
+}
+
+// Ascending list of the r with mask[r] != 0, and their count.  Single block of
+// 1024 threads; thread tid owns the contiguous slice [tid*per, (tid+1)*per).
+// Slice counts are scanned across the block (wave scan, then the 16 wave
+// totals through LDS).
+__device__ void compact_block(const uint8_t *__restrict__ mask, int n, int32_t *__restrict__ idx,
+                              int32_t *__restrict__ count)
+{
+    __shared__ int wave_total[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (n + 1023) / 1024;
+    const int lo = min(n, tid * per), hi = min(n, lo + per);
+    int mine = 0;
+    for (int r = lo; r < hi; ++r) mine += mask[r] != 0;
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_total[wave] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        int t = wave_total[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    int pos = before + incl - mine;
+    for (int r = lo; r < hi; ++r)
+        if (mask[r] != 0) idx[pos++] = r;
+    if (tid == 0) *count = total;
+}
+
+__global__ __launch_bounds__(1024) void compact_kernel(const uint8_t *__restrict__ mask, int n,
+                                                       int32_t *__restrict__ idx, int32_t *__restrict__ count)
+{
+    compact_block(mask, n, idx, count);
+}
+
+// score[t] = maskA[i] * ((1/p[i]) * sqrt(gsq[t])) * sqrt(xsq[t])
+__global__ __launch_bounds__(256) void leverage_kernel(const float *__restrict__ gsq, const float *__restrict__ xsq,
+                                                       const float *__restrict__ p, const uint8_t *__restrict__ maskA,
+                                                       int64_t R, int T, float *__restrict__ score)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= R) return;
+    const int i = (int)(t / T);
+    float s = 0.0f;
+    if (maskA[i]) {
+        const float inv = __fdiv_rn(1.0f, p[i]);
+        const float a = __fmul_rn(inv, __fsqrt_rn(gsq[t]));
+        s = __fmul_rn(a, __fsqrt_rn(xsq[t]));
+    }
+    score[t] = s;
+}
+
+// scaleW[t] = maskW[t] ? 1/(p[i] q[t]) : 0
+__global__ __launch_bounds__(256) void row_scale_kernel(const float *__restrict__ p, const float *__restrict__ q,
+                                                        const uint8_t *__restrict__ maskW, int64_t R, int T,
+                                                        float *__restrict__ scale)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= R) return;
+    const int i = (int)(t / T);
+    scale[t] = maskW[t] ? __fdiv_rn(1.0f, __fmul_rn(p[i], q[t])) : 0.0f;
+}
+
+// "SampleA only" token plan: every token of a kept sample is kept with q = 1.
+__global__ __launch_bounds__(256) void broadcast_data_mask_kernel(const uint8_t *__restrict__ maskA, int64_t R, int T,
+                                                                  float *__restrict__ q, uint8_t *__restrict__ maskW)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= R) return;
+    const uint8_t m = maskA[t / T] ? 1 : 0;
+    q[t] = m ? 1.0f : 0.0f;
+    maskW[t] = m;
+}
+
+// ---- host launchers ---------------------------------------------------------
+
+vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st)
+{
+    hipLaunchKernelGGL(keep_probs_kernel, dim3(1), dim3(1024), 0, st, score, n, budget, prob);
+    return launch_status();
+}
+
+vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32_t stream_id, uint8_t *mask,
+                           int32_t *idx, int32_t *count, hipStream_t st)
+{
+    if (n > 0) {
+        hipLaunchKernelGGL(bernoulli_mask_kernel, dim3((n + 255) / 256), dim3(256), 0, st, prob, n, rng.seed,
+                           rng.layer, stream_id, rng.draw, mask);
+        if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    }
+    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, mask, n, idx, count);
+    return launch_status();
+}
+
+vcas_status compact_only(const uint8_t *mask, int n, int32_t *idx, int32_t *count, hipStream_t st)
+{
+    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, mask, n, idx, count);
+    return launch_status();
+}
+
+vcas_status leverage_scores(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, int64_t R,
+                            int T, float *score, hipStream_t st)
+{
+    hipLaunchKernelGGL(leverage_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, gsq, xsq, p, maskA, R, T,
+                       score);
+    return launch_status();
+}
+
+vcas_status row_scale(const float *p, const float *q, const uint8_t *maskW, int64_t R, int T, float *scale,
+                      hipStream_t st)
+{
+    hipLaunchKernelGGL(row_scale_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, p, q, maskW, R, T,
+                       scale);
+    return launch_status();
+}
+
+vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q, uint8_t *maskW, hipStream_t st)
+{
+    hipLaunchKernelGGL(broadcast_data_mask_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, maskA, R, T,
+                       q, maskW);
+    return launch_status();
+}
+
+}  // namespace vcas

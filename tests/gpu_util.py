@@ -1,0 +1,67 @@
+"""Helpers shared by the GPU parity tests, the smoke check and the benchmark:
+move seeded inputs to the device, run the library, bring results back."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads
+from paper_2402_17227_amd import binding as vb
+
+
+def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """numpy (fp32, or bf16 bit patterns as uint16) -> device tensor of the layer dtype."""
+    if dtype == workloads.BF16:
+        return torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def from_device(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> numpy float64 (values) for comparison."""
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_l2(got, ref) -> float:
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    den = float(np.sqrt((ref**2).sum()))
+    num = float(np.sqrt(((got - ref) ** 2).sum()))
+    return num / den if den > 0 else num
+
+
+def run_layer_gpu(spec, G, X, W, draw: int = 0, token_sampling: bool = True, want_dX=True, want_dW=True):
+    """One call of vcas_linear_backward.  Returns (plan as numpy dict, dX fp64, dW fp64)."""
+    shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+    g, x, w = to_device(G, spec.dtype), to_device(X, spec.dtype), to_device(W, spec.dtype)
+    plan = vb.Plan.allocate(spec.N, spec.T)
+    ws = vb.make_workspace(shape)
+    dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda") if want_dX else None
+    dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda") if want_dW else None
+    rng = vb.Rng(spec.seed, spec.layer, draw)
+    vb.vcas_linear_backward(shape, g, x, w, spec.rho, spec.nu, rng, token_sampling, plan, dX, dW, ws)
+    torch.cuda.synchronize()
+    return plan_to_numpy(plan), (from_device(dX) if want_dX else None), (from_device(dW) if want_dW else None)
+
+
+def plan_to_numpy(plan: "vb.Plan") -> dict:
+    d = {k: getattr(plan, k).cpu().numpy() for k in ("gsq", "gnorm", "p", "maskA", "xsq", "score", "q", "maskW", "scaleW")}
+    cntA = int(plan.cntA.item())
+    cntW = int(plan.cntW.item())
+    d["cntA"], d["cntW"] = cntA, cntW
+    d["idxA"] = plan.idxA.cpu().numpy()[:cntA]
+    d["idxW"] = plan.idxW.cpu().numpy()[:cntW]
+    return d
+
+
+def compare_plan(got: dict, want) -> None:
+    """Bit-exact comparison of every sampling decision with the oracle's plan."""
+    for name in ("gsq", "gnorm", "p", "xsq", "score", "q", "scaleW"):
+        a, b = got[name], getattr(want, name)
+        assert a.dtype == np.float32 and b.dtype == np.float32
+        same = a.view(np.uint32) == b.view(np.uint32)
+        assert same.all(), f"{name}: {int((~same).sum())} of {a.size} differ, first at {int(np.argmin(same))}: " \
+                           f"{a[np.argmin(same)]!r} vs {b[np.argmin(same)]!r}"
+    for name in ("maskA", "maskW"):
+        assert np.array_equal(got[name], getattr(want, name)), name
+    assert got["cntA"] == want.idxA.size and got["cntW"] == want.idxW.size
+    assert np.array_equal(got["idxA"], want.idxA) and np.array_equal(got["idxW"], want.idxW)

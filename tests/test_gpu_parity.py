@@ -1,0 +1,284 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Bit-exact for norms, probabilities, masks, index
+lists and scales; rel-L2 <= 1e-5 (fp32) / 1e-2 (bf16 in, fp32 accumulate) for
+dX and dW."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from workloads import BF16, F32
+
+pytestmark = pytest.mark.gpu
+
+TOL = {F32: 1e-5, BF16: 1e-2}
+
+
+@pytest.fixture(scope="module")
+def vb():
+    from paper_2402_17227_amd import binding
+    binding.lib()
+    return binding
+
+
+def _bits(a):
+    return np.ascontiguousarray(a, np.float32).view(np.uint32)
+
+
+def _dev(a, dtype=None):
+    from tests.gpu_util import to_device
+    if dtype is None:
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return to_device(a, dtype)
+
+
+# ------------------------------------------------------------ single calls
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N,T,K", [(3, 7, 8), (4, 33, 136), (8, 128, 768), (2, 197, 1024), (3, 50, 3072),
+                                   (2, 64, 4096), (1, 70, 8200)])
+def test_row_norms_bit_exact(vb, dtype, N, T, K):
+    rng = np.random.default_rng(N * 1000 + K)
+    R = N * T
+    a = (rng.standard_normal((R, K)) * np.exp(rng.standard_normal((R, 1)))).astype(np.float32)
+    A = workloads.f32_to_bf16_bits(a) if dtype == BF16 else a
+    keep = (rng.random(N) < 0.6).astype(np.uint8)
+    shape = vb.shape_of(N, T, K, K, dtype)
+    gsq = torch.empty(R, device="cuda")
+    xsq = torch.empty(R, device="cuda")
+    gnorm = torch.empty(N, device="cuda")
+    d = _dev(A, dtype)
+    vb.vcas_row_norms(shape, d, d, _dev(keep), gsq, xsq, gnorm)
+    torch.cuda.synchronize()
+    want_g = oracle.row_sumsq(A, dtype)
+    assert np.array_equal(_bits(gsq.cpu().numpy()), _bits(want_g))
+    assert np.array_equal(_bits(xsq.cpu().numpy()), _bits(oracle.row_sumsq(A, dtype, T, keep)))
+    assert np.array_equal(_bits(gnorm.cpu().numpy()), _bits(oracle.sample_norms(want_g, N, T)))
+
+
+@pytest.mark.parametrize("n,rho,sigma,zero_frac", [(1, 0.5, 1.0, 0.0), (8, 0.5, 1.0, 0.0), (64, 0.3, 1.5, 0.1),
+                                                   (1000, 0.9, 2.0, 0.0), (4096, 0.25, 1.0, 0.05),
+                                                   (16384, 0.2, 1.2, 0.3), (12608, 0.15, 0.7, 0.7),
+                                                   (70000, 0.05, 1.0, 0.0), (50, 1.0, 1.0, 0.2)])
+def test_keep_probs_bit_exact(vb, n, rho, sigma, zero_frac):
+    rng = np.random.default_rng(n)
+    a = np.exp(sigma * rng.standard_normal(n)).astype(np.float32)
+    a[rng.random(n) < zero_frac] = 0.0
+    prob = torch.full((n,), -1.0, device="cuda")
+    vb.vcas_keep_probs(_dev(a), n, n * rho, prob)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(prob.cpu().numpy()), _bits(oracle.keep_probs(a, n * rho)))
+
+
+def test_keep_probs_degenerate_inputs(vb):
+    for a, budget in [(np.zeros(100, np.float32), 10.0), (np.full(77, 2.5, np.float32), 77 * 0.35),
+                      (np.array([1e6, 1, 2, 3, 4], np.float32), 2.0), (np.array([10, 6, 1, 1, 1, 1], np.float32), 3.0),
+                      (np.array([3.0], np.float32), 0.0)]:
+        prob = torch.full((a.size,), -1.0, device="cuda")
+        vb.vcas_keep_probs(_dev(a), a.size, budget, prob)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(prob.cpu().numpy()), _bits(oracle.keep_probs(a, budget)))
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 1000, 4096, 16384, 100003])
+@pytest.mark.parametrize("stream_id", [0, 1])
+def test_sample_compact_bit_exact(vb, n, stream_id):
+    rng = np.random.default_rng(n + stream_id)
+    prob = rng.random(n).astype(np.float32)
+    prob[rng.random(n) < 0.1] = 1.0
+    prob[rng.random(n) < 0.1] = 0.0
+    seed, layer, draw = 0x0123456789ABCDEF + n, 41, 7
+    mask = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+    idx = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    vb.vcas_sample_compact(_dev(prob), n, vb.Rng(seed, layer, draw), stream_id, mask, idx, cnt)
+    torch.cuda.synchronize()
+    want_mask, want_idx = oracle.sample_mask(prob, seed, layer, stream_id, draw)
+    assert np.array_equal(mask.cpu().numpy(), want_mask)
+    assert int(cnt.item()) == want_idx.size
+    got_idx = idx.cpu().numpy()
+    assert np.array_equal(got_idx[:want_idx.size], want_idx)
+    assert np.all(got_idx[want_idx.size:] == -7)          # entries past the count are left alone
+
+
+def test_philox_known_answer_on_device(vb):
+    # Row 5 of (layer 3, stream 1, draw 0, seed 0) is the fourth published-format known answer:
+    # word 0 = dd3c661d, so u = 0xdd3c66 / 2^24.  Thresholds one ulp apart on either side pin it.
+    u = np.float32(0xDD3C66 / 2.0**24)
+    for thr, want in [(np.nextafter(u, np.float32(1)), 1), (u, 0)]:
+        prob = np.zeros(8, np.float32)
+        prob[5] = thr
+        mask = torch.empty(8, dtype=torch.uint8, device="cuda")
+        idx = torch.empty(8, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        vb.vcas_sample_compact(_dev(prob), 8, vb.Rng(0, 3, 0), 1, mask, idx, cnt)
+        torch.cuda.synchronize()
+        assert int(mask[5].item()) == want and int(cnt.item()) == want
+
+
+def test_leverage_scores_and_row_scale_bit_exact(vb):
+    # wide dynamic range: exercises the correctly rounded sqrt and divide
+    rng = np.random.default_rng(17)
+    N, T = 37, 113
+    R = N * T
+    gsq = np.exp(8 * rng.standard_normal(R)).astype(np.float32)
+    xsq = np.exp(8 * rng.standard_normal(R)).astype(np.float32)
+    gsq[:50] = 0
+    p = rng.uniform(1e-4, 1, N).astype(np.float32)
+    p[:5] = 1.0
+    maskA = (rng.random(N) < 0.7).astype(np.uint8)
+    shape = vb.shape_of(N, T, 8, 8, F32)
+    score = torch.empty(R, device="cuda")
+    vb.vcas_leverage_scores(shape, _dev(gsq), _dev(xsq), _dev(p), _dev(maskA), score)
+    q = rng.uniform(1e-5, 1, R).astype(np.float32)
+    maskW = (rng.random(R) < 0.5).astype(np.uint8)
+    scale = torch.empty(R, device="cuda")
+    vb.vcas_row_scale(shape, _dev(p), _dev(q), _dev(maskW), scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(score.cpu().numpy()), _bits(oracle.leverage_scores(gsq, xsq, p, maskA, N, T)))
+    assert np.array_equal(_bits(scale.cpu().numpy()), _bits(oracle.row_scale(p, q, maskW, N, T)))
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N,T,kin,kout,keep", [(4, 40, 136, 264, [1, 0, 1, 1]), (3, 197, 320, 200, [0, 1, 0]),
+                                               (6, 64, 128, 128, [1, 1, 1, 1, 1, 1]), (5, 30, 64, 72, [0, 0, 0, 0, 0]),
+                                               (9, 130, 768, 256, [0, 1, 1, 0, 0, 0, 1, 0, 1])])
+def test_dgrad_with_given_mask(vb, dtype, N, T, kin, kout, keep):
+    rng = np.random.default_rng(kin + kout)
+    R = N * T
+    g = rng.standard_normal((R, kout)).astype(np.float32)
+    w = (rng.standard_normal((kout, kin)) * 0.05).astype(np.float32)
+    G, W = (workloads.f32_to_bf16_bits(a) if dtype == BF16 else a for a in (g, w))
+    p = rng.uniform(0.2, 1, N).astype(np.float32)
+    maskA = np.array(keep, np.uint8)
+    idxA = np.nonzero(maskA)[0].astype(np.int32)
+    idx_buf = np.full(N, -1, np.int32)
+    idx_buf[:idxA.size] = idxA
+    shape = vb.shape_of(N, T, kin, kout, dtype)
+    dX = torch.full((R, kin), float("nan"), dtype=torch.bfloat16 if dtype == BF16 else torch.float32, device="cuda")
+    vb.vcas_sampled_dgrad(shape, _dev(G, dtype), _dev(W, dtype), _dev(p), _dev(idx_buf),
+                          _dev(np.array([idxA.size], np.int32)), dX)
+    torch.cuda.synchronize()
+    from tests.gpu_util import from_device, rel_l2
+    got = from_device(dX)
+    want = oracle.dgrad(G, W, dtype, N, T, p, maskA)
+    assert np.isfinite(got).all()
+    assert np.all(got[np.repeat(maskA == 0, T)] == 0)
+    if idxA.size:
+        assert rel_l2(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("R,kin,kout,frac", [(300, 136, 264, 0.5), (1000, 128, 128, 1.0), (70, 64, 72, 0.0),
+                                             (5000, 256, 384, 0.3), (4096, 768, 768, 0.05), (130, 768, 256, 0.7)])
+def test_wgrad_with_given_rows(vb, dtype, R, kin, kout, frac):
+    rng = np.random.default_rng(R + kin)
+    g = rng.standard_normal((R, kout)).astype(np.float32)
+    x = rng.standard_normal((R, kin)).astype(np.float32)
+    G, X = (workloads.f32_to_bf16_bits(a) if dtype == BF16 else a for a in (g, x))
+    keep = rng.random(R) < frac
+    scale = np.where(keep, rng.uniform(1, 8, R), 0).astype(np.float32)
+    idx = np.nonzero(keep)[0].astype(np.int32)
+    idx_buf = np.full(R, -1, np.int32)
+    idx_buf[:idx.size] = idx
+    shape = vb.shape_of(1, R, kin, kout, dtype)
+    ws = vb.make_workspace(shape)
+    from tests.gpu_util import from_device, rel_l2
+    want = oracle.wgrad(G, X, dtype, scale)
+    for rep in range(2):                                   # second call: counters were left at zero
+        dW = torch.full((kout, kin), float("nan"), device="cuda")
+        vb.vcas_sampled_wgrad(shape, _dev(G, dtype), _dev(X, dtype), _dev(scale), _dev(idx_buf),
+                              _dev(np.array([idx.size], np.int32)), dW, ws)
+        torch.cuda.synchronize()
+        got = from_device(dW)
+        assert np.isfinite(got).all()
+        if idx.size == 0:
+            assert np.all(got == 0)
+        else:
+            assert rel_l2(got, want) <= TOL[dtype]
+
+
+# ---------------------------------------------------------- the whole path
+
+@pytest.mark.parametrize("spec", workloads.small_cases(), ids=lambda s: f"{s.name}-{'bf16' if s.dtype else 'f32'}")
+def test_linear_backward_small_cases(vb, spec):
+    from tests.gpu_util import run_layer_gpu, compare_plan, rel_l2
+    G, X, W = workloads.make_layer(spec)
+    got_plan, dX, dW = run_layer_gpu(spec, G, X, W, draw=3)
+    want_plan, want_dX, want_dW = oracle.linear_backward(G, X, W, spec.dtype, spec.N, spec.T, spec.rho, spec.nu,
+                                                         spec.seed, spec.layer, 3)
+    compare_plan(got_plan, want_plan)
+    assert np.isfinite(dX).all() and np.isfinite(dW).all()
+    assert np.all(dX[np.repeat(want_plan.maskA == 0, spec.T)] == 0)
+    if want_plan.idxA.size:
+        assert rel_l2(dX, want_dX) <= TOL[spec.dtype]
+    if want_plan.idxW.size:
+        assert rel_l2(dW, want_dW) <= TOL[spec.dtype]
+    else:
+        assert np.all(dW == 0)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_keep_ratio_one_is_the_dense_backward(vb, dtype):
+    from tests.gpu_util import run_layer_gpu, rel_l2
+    spec = workloads.LayerSpec("dense", dtype, 7, 45, 200, 136, 1.0, 1.0, layer=9, seed=3, gen_seed=8, token_sigma=0.5)
+    G, X, W = workloads.make_layer(spec)
+    plan, dX, dW = run_layer_gpu(spec, G, X, W)
+    assert plan["cntA"] == spec.N and plan["cntW"] == spec.R
+    assert np.all(plan["p"] == 1) and np.all(plan["q"] == 1) and np.all(plan["scaleW"] == 1)
+    g, x, w = (oracle.to_f64(a, dtype) for a in (G, X, W))
+    assert rel_l2(dX, g @ w) <= TOL[dtype]
+    assert rel_l2(dW, g.T @ x) <= TOL[dtype]
+
+
+def test_all_zero_gradient_keeps_nothing(vb):
+    from tests.gpu_util import run_layer_gpu
+    spec = workloads.LayerSpec("zero", BF16, 4, 20, 64, 72, 0.5, 0.5, layer=1, seed=1, gen_seed=1)
+    G, X, W = workloads.make_layer(spec)
+    G[:] = 0
+    plan, dX, dW = run_layer_gpu(spec, G, X, W)
+    assert plan["cntA"] == 0 and plan["cntW"] == 0
+    assert np.all(dX == 0) and np.all(dW == 0)
+
+
+def test_sample_a_only_backward(vb):
+    from tests.gpu_util import run_layer_gpu, compare_plan, rel_l2
+    spec = workloads.LayerSpec("aonly", BF16, 9, 33, 136, 200, 0.5, 0.5, layer=6, seed=21, gen_seed=5, token_sigma=0.5)
+    G, X, W = workloads.make_layer(spec)
+    got_plan, dX, dW = run_layer_gpu(spec, G, X, W, draw=1, token_sampling=False)
+    want_plan, want_dX, want_dW = oracle.linear_backward(G, X, W, spec.dtype, spec.N, spec.T, spec.rho, spec.nu,
+                                                         spec.seed, spec.layer, 1, token_sampling=False)
+    compare_plan(got_plan, want_plan)
+    assert rel_l2(dX, want_dX) <= 1e-2 and rel_l2(dW, want_dW) <= 1e-2
+
+
+def test_results_are_reproducible(vb):
+    from tests.gpu_util import run_layer_gpu
+    spec = workloads.LayerSpec("repro", BF16, 8, 128, 768, 768, 0.5, 0.5, layer=2, seed=5, gen_seed=6, token_sigma=0.5)
+    G, X, W = workloads.make_layer(spec)
+    a = run_layer_gpu(spec, G, X, W)
+    b = run_layer_gpu(spec, G, X, W)
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    assert np.array_equal(a[0]["idxW"], b[0]["idxW"])
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_variance_probe_matches_oracle(vb, dtype):
+    spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)
+    G, X, W = workloads.make_layer(spec)
+    M = 4
+    shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, dtype)
+    from tests.gpu_util import to_device
+    plan = vb.Plan.allocate(spec.N, spec.T)
+    ws = vb.make_workspace(shape)
+    out = torch.full((4,), float("nan"), dtype=torch.float64, device="cuda")
+    vb.vcas_variance_probe(shape, to_device(G, dtype), to_device(X, dtype), spec.rho, spec.nu,
+                           vb.Rng(spec.seed, spec.layer, 10), M, plan, out, ws)
+    torch.cuda.synchronize()
+    want = oracle.variance_probe(G, X, dtype, spec.N, spec.T, spec.rho, spec.nu, spec.seed, spec.layer, 10, M)
+    got = out.cpu().numpy()
+    # [0], [1]: same fp32 inputs, fp64 sums.  [2], [3]: squared differences of dW, whose own error is
+    # bounded by the GEMM tolerance; the differences are sampling noise, far above rounding.
+    np.testing.assert_allclose(got[:2], want[:2], rtol=1e-9)
+    np.testing.assert_allclose(got[2:], want[2:], rtol=1e-4 if dtype == F32 else 3e-2)

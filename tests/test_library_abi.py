@@ -1,0 +1,74 @@
+"""CPU-side checks of the boundary: the library builds, loads, exports every
+symbol that include/vcas.h declares, and rejects bad arguments on the host
+before anything is launched (no GPU needed for any of this)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def vb():
+    from paper_2402_17227_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(force=True)
+    return binding
+
+
+def test_every_declared_symbol_is_exported(vb):
+    header = open(os.path.join(ROOT, "include", "vcas.h")).read()
+    declared = set(re.findall(r"\b(vcas_[a-z_]+)\s*\(", header))
+    declared -= {"vcas_status", "vcas_dtype"}
+    assert declared == set(vb.EXPORTS)
+    lib = vb.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_workspace_bytes_and_status_strings(vb):
+    good = vb.shape_of(8, 128, 768, 768, vb.VCAS_F32)
+    assert vb.vcas_workspace_bytes(good) > 768 * 768 * 4
+    assert vb.vcas_workspace_bytes(vb.shape_of(8, 128, 770, 768, vb.VCAS_F32)) == 0   # K not a multiple of 8
+    assert vb.vcas_workspace_bytes(vb.shape_of(0, 128, 768, 768, vb.VCAS_F32)) == 0
+    assert vb.vcas_workspace_bytes(vb.shape_of(8, 128, 768, 768, 7)) == 0
+    assert vb.lib().vcas_status_string(0) == b"ok"
+    assert b"null" in vb.lib().vcas_status_string(2)
+
+
+def test_bad_arguments_are_rejected_on_the_host(vb):
+    lib = vb.lib()
+    null = C.c_void_p(0)
+    fake = C.c_void_p(0x1000)          # never dereferenced: every call below fails its host checks first
+    good = vb.shape_of(8, 128, 768, 768, vb.VCAS_BF16)
+    rng = vb.Rng(0, 0, 0)
+    assert lib.vcas_row_norms(C.byref(good), null, null, null, null, null, null, null) == 2
+    assert lib.vcas_row_norms(C.byref(vb.shape_of(8, 128, 768, 768, 5)), fake, null, null, fake, null, null, null) == 3
+    assert lib.vcas_row_norms(C.byref(vb.shape_of(8, -1, 768, 768, 0)), fake, null, null, fake, null, null, null) == 1
+    assert lib.vcas_row_norms(C.byref(good), C.c_void_p(0x1004), null, null, fake, null, null, null) == 1  # alignment
+    assert lib.vcas_keep_probs(null, C.c_int32(5), C.c_double(1.0), null, null) == 2
+    assert lib.vcas_keep_probs(fake, C.c_int32(-5), C.c_double(1.0), fake, null) == 1
+    assert lib.vcas_keep_probs(fake, C.c_int32(5), C.c_double(float("nan")), fake, null) == 1
+    assert lib.vcas_sample_compact(fake, C.c_int32(4), None, C.c_uint32(0), fake, fake, fake, null) == 2
+    assert lib.vcas_sampled_dgrad(C.byref(good), fake, fake, fake, fake, null, fake, null) == 2
+    assert lib.vcas_sampled_wgrad(C.byref(good), fake, fake, fake, fake, fake, fake, null, null) == 4
+    plan = vb.PlanPtrs(*([0x1000] * 13))
+    assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(1.5), C.c_double(0.5), C.byref(rng),
+                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null) == 1
+    assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(0.5), C.c_double(0.0), C.byref(rng),
+                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null) == 1
+    bad_plan = vb.PlanPtrs(*([0x1000] * 12 + [0]))
+    assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
+                                    C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null) == 2
+    assert lib.vcas_variance_probe(C.byref(good), fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
+                                   C.c_int32(0), C.byref(plan), fake, fake, null) == 1
+    assert lib.vcas_workspace_init(null, C.c_size_t(1 << 20), null) == 4
+
+
+def test_binding_refuses_to_run_without_the_library(vb, monkeypatch, tmp_path):
+    monkeypatch.setattr(vb, "_lib", None)
+    monkeypatch.setattr(vb, "LIB_PATH", str(tmp_path / "libvcas.so"))
+    with pytest.raises(vb.VcasError):
+        vb.lib()
