@@ -257,7 +257,7 @@ __global__ __launch_bounds__(WM *WN * 64) void dgrad_bf16_kernel(const uint16_t 
         if (m < M) {
             const int s = idxA[m / T];
             dst = s * T + (int)(m % T);
-            sc = __fdiv_rn(1.0f, p[s]);
+            sc = 1.0f / (p[s]);
         }
         row_of[r] = dst;
         scale_of[r] = sc;

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
         if (m < M) {
             const int s = idxA[m / T];
             dst = s * T + (int)(m % T);
-            sc = __fdiv_rn(1.0f, p[s]);
+            sc = 1.0f / (p[s]);
         }
         row_of[tid] = dst;
         scale_of[tid] = sc;

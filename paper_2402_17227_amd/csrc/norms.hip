@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restric
     float acc = 0.0f;
     for (int t = lane; t < T; t += 64) acc = acc + p[t];
     acc = wave_exchange_sum(acc);
-    if (lane == 0) gnorm[i] = __fsqrt_rn(acc);
+    if (lane == 0) gnorm[i] = __builtin_sqrtf(acc);
 }
 
 template <bool BF16>

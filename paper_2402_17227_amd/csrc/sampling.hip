@@ -177,9 +177,9 @@ __global__ __launch_bounds__(256) void leverage_kernel(const float *__restrict__
     const int i = (int)(t / T);
     float s = 0.0f;
     if (maskA[i]) {
-        const float inv = __fdiv_rn(1.0f, p[i]);
-        const float a = __fmul_rn(inv, __fsqrt_rn(gsq[t]));
-        s = __fmul_rn(a, __fsqrt_rn(xsq[t]));
+        const float inv = 1.0f / (p[i]);
+        const float a = inv * __builtin_sqrtf(gsq[t]);
+        s = a * __builtin_sqrtf(xsq[t]);
     }
     score[t] = s;
 }
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void row_scale_kernel(const float *__restrict_
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= R) return;
     const int i = (int)(t / T);
-    scale[t] = maskW[t] ? __fdiv_rn(1.0f, __fmul_rn(p[i], q[t])) : 0.0f;
+    scale[t] = maskW[t] ? 1.0f / (p[i] * q[t]) : 0.0f;
 }
 
 // "SampleA only" token plan: every token of a kept sample is kept with q = 1.
