@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the VCAS sampled linear-layer backward on one MI355X.
+
+One "step" is one pass of the whole hot path (row norms -> keep probabilities
+-> Philox masks -> compaction -> sampled dX and dW) over every linear layer of
+the BERT-base-shaped stack (72 layers, B=32, L=128, bf16), each layer with its
+own synthetic G, X, W resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "sampled linear-BP ms & effective TFLOP/s vs dense BP (bf16), % of roofline"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+
+
+class Layer:
+    """Device-resident tensors and scratch of one linear layer."""
+
+    def __init__(self, spec, vb, to_device, make_layer):
+        import torch
+        G, X, W = make_layer(spec)
+        self.spec = spec
+        self.shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+        self.G, self.X, self.W = (to_device(a, spec.dtype) for a in (G, X, W))
+        self.plan = vb.Plan.allocate(spec.N, spec.T)
+        self.ws = vb.make_workspace(self.shape)
+        self.dX = torch.empty((spec.R, spec.K_in), dtype=self.G.dtype, device="cuda")
+        self.dW = torch.empty((spec.K_out, spec.K_in), dtype=torch.float32, device="cuda")
+        self.dense_flops = 4.0 * spec.R * spec.K_in * spec.K_out
+
+
+def cpu_baseline(specs, make_layer):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    picked = [s for s in specs if any(f".b{b}." in s.name for b in _sample_blocks(specs))] or specs[:1]
+    flops = 0.0
+    secs = 0.0
+    for s in picked:
+        G, X, W = make_layer(s)
+        t0 = time.perf_counter()
+        oracle.linear_backward(G, X, W, s.dtype, s.N, s.T, s.rho, s.nu, s.seed, s.layer, 0)
+        secs += time.perf_counter() - t0
+        flops += 4.0 * s.R * s.K_in * s.K_out
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s (effective, dense-equivalent)",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(picked)} of {len(specs)} layers (blocks {sorted(_sample_blocks(specs))}), "
+                      f"{secs:.1f} s of oracle time"}
+
+
+def _sample_blocks(specs):
+    blocks = sorted({int(s.name.split(".b")[1].split(".")[0]) for s in specs if ".b" in s.name})
+    if not blocks:
+        return set()
+    return {blocks[0], blocks[len(blocks) // 2], blocks[-1]}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_base")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import workloads
+    from paper_2402_17227_amd import binding as vb
+    from tests.gpu_util import to_device
+
+    vb.lib()                                    # fails loudly if libvcas.so was not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    specs = workloads.config(args.workload)
+    layers = [Layer(s, vb, to_device, workloads.make_layer) for s in specs]
+    torch.cuda.synchronize()
+    dense_flops = sum(l.dense_flops for l in layers)
+
+    def step(draw, rho=None, nu=None):
+        for l in layers:
+            s = l.spec
+            vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, s.rho if rho is None else rho,
+                                    s.nu if nu is None else nu, vb.Rng(s.seed, s.layer, draw), True, l.plan,
+                                    l.dX, l.dW, l.ws)
+
+    # ---- timed region: K steps of the whole path --------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    kept_rows = sum(int(l.plan.cntA.item()) * l.spec.T * 2.0 * l.spec.K_in * l.spec.K_out for l in layers)
+    kept_toks = sum(int(l.plan.cntW.item()) * 2.0 * l.spec.K_in * l.spec.K_out for l in layers)
+    kept_fraction = (kept_rows + kept_toks) / dense_flops
+
+    # ---- per-kernel durations of the two GEMMs, HIP events on the launch stream ----
+    # Replays each layer's dgrad / wgrad entry point on the plan the last step left,
+    # one event pair per launch, same shapes, inputs and launch configuration.
+    def kernel_times(call):
+        evs = []
+        for _ in range(max(3, min(args.steps, 10))):
+            for l in layers:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                call(l)
+                b.record()
+                evs.append((a, b))
+        torch.cuda.synchronize()
+        t = [a.elapsed_time(b) for a, b in evs]
+        return sum(t) / len(t), sum(t) / (len(t) / len(layers))
+
+    dg_avg, dg_total = kernel_times(lambda l: vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.plan.p, l.plan.idxA,
+                                                                    l.plan.cntA, l.dX))
+    wg_avg, wg_total = kernel_times(lambda l: vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.plan.scaleW, l.plan.idxW,
+                                                                    l.plan.cntW, l.dW, l.ws))
+    if dg_total >= wg_total:
+        name, avg_ms, flops = "dgrad_bf16_kernel", dg_avg, kept_rows / len(layers)
+    else:
+        name, avg_ms, flops = "wgrad_bf16_kernel", wg_avg, kept_toks / len(layers)
+    bf16 = specs[0].dtype == workloads.BF16
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    achieved = flops / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                "frac": achieved / peak, "traffic": None, "avg_launch_us": avg_ms * 1e3,
+                "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
+
+    # ---- dense yardsticks at the same shapes -------------------------------------
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+
+    def dense_own():        # this library's two GEMMs at keep ratio one, sampling passes skipped
+        for l in layers:
+            vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.ones_p, l.iota_N, l.full_N, l.dX)
+            vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.ones_R, l.iota_R, l.full_R, l.dW, l.ws)
+
+    def dense_torch():
+        for l in layers:
+            torch.matmul(l.G, l.W, out=l.dX)
+            torch.matmul(l.G.t(), l.X)
+
+    for l in layers:
+        s = l.spec
+        l.ones_p = torch.ones(s.N, device="cuda")
+        l.iota_N = torch.arange(s.N, dtype=torch.int32, device="cuda")
+        l.full_N = torch.full((1,), s.N, dtype=torch.int32, device="cuda")
+        l.ones_R = torch.ones(s.R, device="cuda")
+        l.iota_R = torch.arange(s.R, dtype=torch.int32, device="cuda")
+        l.full_R = torch.full((1,), s.R, dtype=torch.int32, device="cuda")
+    reps = max(3, min(args.steps, 10))
+    dense_own_ms = timed(dense_own, reps)
+    dense_torch_ms = timed(dense_torch, reps)
+
+    out = {
+        "metric": METRIC,
+        "value": dense_flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s (effective: dense-equivalent 4*R*K_in*K_out per layer / sampled-path time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
+                   "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
+        "kept_flop_fraction": kept_fraction,
+        "dense_ms_per_step": {"this_library_keep_ratio_1_gemms_only": dense_own_ms, "torch_matmul": dense_torch_ms},
+        "speedup_vs_dense": {"this_library": dense_own_ms / ms_per_step, "torch_matmul": dense_torch_ms / ms_per_step},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, workloads.make_layer)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
