@@ -1,5 +1,7 @@
 // C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
 // launches on the caller's stream.  See include/vcas.h for the contract.
+#include <stdlib.h>
+
 #include "common.hpp"
 
 namespace vcas {
@@ -24,26 +26,27 @@ int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int32_t *counters,
-                       int splits, hipStream_t st);
+                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
+                       hipStream_t st);
 vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                       const int32_t *cntA, void *dX, hipStream_t st);
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
-                      const int32_t *cntW, float *dW, float *partials, int32_t *counters, int splits, hipStream_t st);
+                      const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st);
 
 // Split-K slices of the weight gradient: enough workgroups to cover the chip
-// about twice, at most kMaxSplit, and never so many that a slice at full
-// length R would have fewer than 4 contraction steps.
+// once, at most 8 (the last-arriving workgroup of a tile reads every partial,
+// so that tail grows with the split count), and never so many that a slice at
+// full length R would have fewer than 4 contraction steps.
 int wgrad_split(const vcas_shape *s)
 {
     const bool bf = s->dtype == VCAS_BF16;
     const int tiles = bf ? wgrad_tiles_bf16(s->K_out, s->K_in) : wgrad_tiles_f32(s->K_out, s->K_in);
     const int64_t R = (int64_t)s->N * s->T;
     const int64_t steps = (R + (bf ? 63 : 15)) / (bf ? 64 : 16);
-    int64_t want = (512 + tiles - 1) / tiles;
-    int64_t cap = steps / (bf ? 4 : 8);
+    int64_t want = (256 + tiles - 1) / tiles;
+    int64_t cap = steps / (bf ? 2 : 8);
     if (want > cap) want = cap;
-    if (want > kMaxSplit) want = kMaxSplit;
+    if (want > 8) want = 8;
     if (want < 1) want = 1;
     return (int)want;
 }
@@ -120,11 +123,12 @@ static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void
 {
     const WorkspaceLayout w = workspace_layout(&s);
     unsigned char *base = static_cast<unsigned char *>(workspace);
-    int32_t *counters = reinterpret_cast<int32_t *>(base + w.counters);
     float *partials = reinterpret_cast<float *>(base + w.partials);
-    const int splits = wgrad_split(&s);
-    return s.dtype == VCAS_BF16 ? wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, counters, splits, st)
-                                : wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, counters, splits, st);
+    int splits = wgrad_split(&s);
+    static const char *force = getenv("VCAS_WGRAD_SPLIT");
+    if (force && atoi(force) < splits) splits = atoi(force);
+    return s.dtype == VCAS_BF16 ? wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, splits, st)
+                                : wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, splits, st);
 }
 
 static bool plan_complete(const vcas_plan *pl)

@@ -19,6 +19,8 @@
 // wgrad multiplies the G block by the per-token scale on the way (the scale
 // lies on the contraction axis and cannot go into the epilogue); dgrad's
 // per-row 1/p goes into the epilogue.
+#include <stdlib.h>
+
 #include "common.hpp"
 
 namespace vcas {
@@ -42,6 +44,27 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 }
 
 // ---------------------------------------------------------------- loaders
+//
+// All global reads are raw buffer loads: a 128-bit resource descriptor in
+// SGPRs (base, size), a per-thread byte offset in one VGPR that does not change
+// over the contraction loop, and the loop's advance in an SGPR.  Reads past the
+// end of the tensor return zero, so a masked-out row is just an offset beyond
+// the end (kOutside) and ragged tails need no branches or address arithmetic.
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+constexpr uint32_t kOutside = 0x80000000u;   // tensors are < 2 GiB (checked on the host)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset)
+{
+    // soffset is wave-uniform by construction; say so, or the compiler loops over its values
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, __builtin_amdgcn_readfirstlane((int)soffset), 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // Operand whose rows are contiguous along the contraction (G in dgrad).
 // ROWS x 64 tile; thread owns 16-byte slot (tid % 8) of rows tid/8 + j*NT/8.
@@ -49,19 +72,15 @@ template <int ROWS, int NT>
 struct DirectLoader {
     static constexpr int PER = ROWS * 8 / NT;
     static_assert(ROWS * 8 % NT == 0 && NT % 8 == 0, "tile/thread mismatch");
-    const uint16_t *row_ptr[PER];  // null: row outside the problem
-    uint4 regs[PER];
+    typedef uint4 Regs[PER];
+    uint32_t voff[PER];   // byte offset of (row, slot) at contraction index 0, or kOutside
 
-    __device__ __forceinline__ void load(int k0, int K)
+    __device__ __forceinline__ void load(Regs &regs, __amdgpu_buffer_rsrc_t rsrc, uint32_t k_bytes) const
     {
-        const int k = k0 + (threadIdx.x & 7) * 8;
 #pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            regs[j] = make_uint4(0u, 0u, 0u, 0u);
-            if (row_ptr[j] != nullptr && k < K) regs[j] = *reinterpret_cast<const uint4 *>(row_ptr[j] + k);
-        }
+        for (int j = 0; j < PER; ++j) regs[j] = buffer_load16(rsrc, voff[j], k_bytes);
     }
-    __device__ __forceinline__ void store(unsigned char *tile) const
+    __device__ __forceinline__ static void store(const Regs &regs, unsigned char *tile)
     {
         const int slot = threadIdx.x & 7;
 #pragma unroll
@@ -79,23 +98,19 @@ struct TransLoader {
     static constexpr int CH = COLS / 8;
     static constexpr int PER = 16 * CH / NT;
     static_assert(16 * CH % NT == 0 && PER >= 1, "tile/thread mismatch");
-    uint4 regs[PER][4];
+    typedef uint4 Regs[PER][4];
 
     __device__ __forceinline__ static int chunk(int j) { return (threadIdx.x + j * NT) % CH; }
     __device__ __forceinline__ static int kquad(int j) { return (threadIdx.x + j * NT) / CH; }
 
-    // addr(j, i) -> pointer to the 8 columns of k-row kquad(j)*4+i, or null
-    template <typename Addr>
-    __device__ __forceinline__ void load(Addr addr)
+    // voff(j, i) -> byte offset of the 8 columns of k-row kquad(j)*4+i (or kOutside)
+    template <typename Off>
+    __device__ __forceinline__ static void load(Regs &regs, __amdgpu_buffer_rsrc_t rsrc, Off voff, uint32_t soffset)
     {
 #pragma unroll
         for (int j = 0; j < PER; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint16_t *p = addr(j, i);
-                regs[j][i] = make_uint4(0u, 0u, 0u, 0u);
-                if (p != nullptr) regs[j][i] = *reinterpret_cast<const uint4 *>(p);
-            }
+            for (int i = 0; i < 4; ++i) regs[j][i] = buffer_load16(rsrc, voff(j, i), soffset);
     }
 
     __device__ __forceinline__ static void put(unsigned char *tile, int j, int c, uint32_t d0, uint32_t d1)
@@ -106,7 +121,7 @@ struct TransLoader {
     }
 
     // plain transpose
-    __device__ __forceinline__ void store(unsigned char *tile) const
+    __device__ __forceinline__ static void store(const Regs &regs, unsigned char *tile)
     {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
@@ -125,22 +140,20 @@ struct TransLoader {
         }
     }
 
-    // transpose with k-row i multiplied by s[j][i] (fp32 multiply, one bf16 rounding)
-    __device__ __forceinline__ void store_scaled(unsigned char *tile, const float (*s)[4]) const
+    // transpose with k-row i multiplied by s[i] (fp32 multiply, one bf16 rounding); PER == 1
+    __device__ __forceinline__ static void store_scaled(const Regs &regs, unsigned char *tile, const float (&s)[4])
     {
+        static_assert(PER == 1, "scaled store handles one unit per thread");
+        const uint32_t *r0 = reinterpret_cast<const uint32_t *>(&regs[0][0]);
+        const uint32_t *r1 = reinterpret_cast<const uint32_t *>(&regs[0][1]);
+        const uint32_t *r2 = reinterpret_cast<const uint32_t *>(&regs[0][2]);
+        const uint32_t *r3 = reinterpret_cast<const uint32_t *>(&regs[0][3]);
 #pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const uint32_t *r0 = reinterpret_cast<const uint32_t *>(&regs[j][0]);
-            const uint32_t *r1 = reinterpret_cast<const uint32_t *>(&regs[j][1]);
-            const uint32_t *r2 = reinterpret_cast<const uint32_t *>(&regs[j][2]);
-            const uint32_t *r3 = reinterpret_cast<const uint32_t *>(&regs[j][3]);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                put(tile, j, 2 * d, pack_bf16(bf16_lo(r0[d]) * s[j][0], bf16_lo(r1[d]) * s[j][1]),
-                    pack_bf16(bf16_lo(r2[d]) * s[j][2], bf16_lo(r3[d]) * s[j][3]));
-                put(tile, j, 2 * d + 1, pack_bf16(bf16_hi(r0[d]) * s[j][0], bf16_hi(r1[d]) * s[j][1]),
-                    pack_bf16(bf16_hi(r2[d]) * s[j][2], bf16_hi(r3[d]) * s[j][3]));
-            }
+        for (int d = 0; d < 4; ++d) {
+            put(tile, 0, 2 * d, pack_bf16(bf16_lo(r0[d]) * s[0], bf16_lo(r1[d]) * s[1]),
+                pack_bf16(bf16_lo(r2[d]) * s[2], bf16_lo(r3[d]) * s[3]));
+            put(tile, 0, 2 * d + 1, pack_bf16(bf16_hi(r0[d]) * s[0], bf16_hi(r1[d]) * s[1]),
+                pack_bf16(bf16_hi(r2[d]) * s[2], bf16_hi(r3[d]) * s[3]));
         }
     }
 };
@@ -197,17 +210,66 @@ __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
 
 // ------------------------------------------------------------------ dgrad
 
+// Software pipeline shared by both kernels.  Two register sets and two LDS
+// buffers: while step s is on the matrix cores, the loads of step s+1 are
+// landing in one register set and the loads of step s+2 are being issued into
+// the other, so a global load has about one and a half steps to arrive.
+//   load(set, s)   issue the global loads of step s into register set `set`
+//   stage(set, b)  write register set `set` (transposed / scaled) to LDS buffer b
+//   compute(b)     MFMA over LDS buffer b
+template <typename Load, typename Stage, typename Compute>
+__device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Compute compute)
+{
+    if (steps <= 0) return;
+    load(0, 0);
+    if (steps > 1) load(1, 1);
+    stage(0, 0);
+    __syncthreads();
+    // Steady state without conditions inside (so that the waits on the older register set
+    // stay partial waits): LDS buffer 0 holds step s, register set 1 holds step s+1.
+    int s = 0;
+    for (; s + 3 < steps; s += 2) {
+        // the scheduling fences keep the loads at the top of each phase: hoisting the MFMAs
+        // above them (to save registers) would take the prefetch distance away
+        load(0, s + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(0);
+        __builtin_amdgcn_sched_barrier(0);
+        stage(1, 1);
+        __syncthreads();
+        load(1, s + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage(0, 0);
+        __syncthreads();
+    }
+    const int left = steps - s;   // 1, 2 or 3
+    if (left == 3) load(0, s + 2);
+    compute(0);
+    if (left >= 2) {
+        stage(1, 1);
+        __syncthreads();
+        compute(1);
+        if (left == 3) {
+            stage(0, 0);
+            __syncthreads();
+            compute(0);
+        }
+    }
+}
+
 // grid: 1-D, tiles_n * (ceil(R/BM) + 1) + 8 workgroups.  The first ceil8(compute
 // tiles) ids compute (spread over the XCDs in contiguous runs), the following
 // ones write the zero rows of dropped samples, the rest exit.
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void dgrad_bf16_kernel(const uint16_t *__restrict__ G,
+template <int BM, int BN, int WM, int WN, int OCC>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint16_t *__restrict__ G,
                                                                   const uint16_t *__restrict__ W,
                                                                   const float *__restrict__ p,
                                                                   const int32_t *__restrict__ idxA,
                                                                   const int32_t *__restrict__ cntA,
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
-                                                                  int K_out, int tiles_n)
+                                                                  int K_out, int tiles_n, int dbg)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -256,28 +318,38 @@ __global__ __launch_bounds__(WM *WN * 64) void dgrad_bf16_kernel(const uint16_t 
         float sc = 0.0f;
         if (m < M) {
             const int s = idxA[m / T];
-            dst = s * T + (int)(m % T);
-            sc = 1.0f / (p[s]);
+            if (s >= 0 && s < N) {
+                dst = s * T + (int)(m % T);
+                sc = 1.0f / p[s];
+            }
         }
         row_of[r] = dst;
         scale_of[r] = sc;
     }
     __syncthreads();
 
-    DirectLoader<BM, NT> la;
+    typedef DirectLoader<BM, NT> LA;
+    typedef TransLoader<BN, NT> LB;
+    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
+    const __amdgpu_buffer_rsrc_t rsrcW = make_rsrc(W, (uint32_t)((int64_t)K_out * K_in * 2));
+    LA la;
 #pragma unroll
-    for (int j = 0; j < la.PER; ++j) {
+    for (int j = 0; j < LA::PER; ++j) {
         const int32_t src = row_of[(threadIdx.x >> 3) + j * (NT / 8)];
-        la.row_ptr[j] = src >= 0 ? G + (int64_t)src * K_out : nullptr;
+        la.voff[j] = src >= 0 ? (uint32_t)src * (uint32_t)K_out * 2u + (threadIdx.x & 7) * 16u : kOutside;
     }
-    TransLoader<BN, NT> lb;
-    auto w_addr = [&](int k0) {
-        return [=](int j, int i) -> const uint16_t * {
-            const int k = k0 + lb.kquad(j) * 4 + i;
-            const int col = n0 + lb.chunk(j) * 8;
-            return (k < K_out && col < K_in) ? W + (int64_t)k * K_in + col : nullptr;
-        };
-    };
+    // W rows k0 + kquad*4 + i at this thread's 8 columns; rows past K_out fall off the end of W and read
+    // as zero, which also cancels whatever G holds there (only the last step can be ragged)
+    uint32_t w_off[LB::PER][4];
+#pragma unroll
+    for (int j = 0; j < LB::PER; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int col = n0 + LB::chunk(j) * 8;
+            w_off[j][i] = col < K_in ? ((uint32_t)(LB::kquad(j) * 4 + i) * (uint32_t)K_in + col) * 2u : kOutside;
+        }
+    typename LA::Regs ra[2];
+    typename LB::Regs rb[2];
 
     const int wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
@@ -289,48 +361,113 @@ __global__ __launch_bounds__(WM *WN * 64) void dgrad_bf16_kernel(const uint16_t 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int steps = (K_out + BK - 1) / BK;
-    la.load(0, K_out);
-    lb.load(w_addr(0));
-    la.store(tA(0));
-    lb.store(tB(0));
-    __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int cur = s & 1;
-        if (s + 1 < steps) {
-            la.load((s + 1) * BK, K_out);
-            lb.load(w_addr((s + 1) * BK));
+    auto load = [&](int set, int s) {
+        if (dbg & 1) return;
+        const uint32_t kb = (uint32_t)s * BK * 2u;                       // bytes along a G row
+        const uint32_t wb = (uint32_t)s * BK * (uint32_t)K_in * 2u;      // bytes down the rows of W
+        auto w_voff = [&](int j, int i) { return w_off[j][i]; };
+        if (set == 0) {
+            la.load(ra[0], rsrcG, kb);
+            LB::load(rb[0], rsrcW, w_voff, wb);
+        } else {
+            la.load(ra[1], rsrcG, kb);
+            LB::load(rb[1], rsrcW, w_voff, wb);
         }
-        mma_tile<TM, TN>(tA(cur), tB(cur), wm0, wn0, acc);
-        if (s + 1 < steps) {
-            la.store(tA(cur ^ 1));
-            lb.store(tB(cur ^ 1));
+    };
+    auto stage = [&](int set, int buf) {
+        if (dbg & 2) return;
+        if (set == 0) {
+            LA::store(ra[0], tA(buf));
+            LB::store(rb[0], tB(buf));
+        } else {
+            LA::store(ra[1], tA(buf));
+            LB::store(rb[1], tB(buf));
         }
-        __syncthreads();
-    }
+    };
+    auto compute_step = [&](int buf) { if (dbg & 4) return; mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
+    pipeline((K_out + BK - 1) / BK, load, stage, compute_step);
 
+    // Epilogue: scale by 1/p, round to bf16, pair neighbouring columns (lanes l, l^1)
+    // so that every lane stores one 32-bit word: even lanes rows of even v, odd lanes odd v.
     const int lane = threadIdx.x & 63;
+    const bool odd = lane & 1;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = wm0 + i * 32 + acc_row(v);
+        for (int v = 0; v < 16; v += 2) {
+            const int r_even = wm0 + i * 32 + acc_row(v);
+            const int r = r_even + (odd ? 1 : 0);
             const int32_t dst = row_of[r];
-            if (dst < 0) continue;
-            const float sc = scale_of[r];
-            uint16_t *out = dX + (int64_t)dst * K_in;
+            const float sc_e = scale_of[r_even], sc_o = scale_of[r_even + 1];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn0 + j * 32 + (lane & 31);
-                if (col < K_in) {
-                    __bf16 b = (__bf16)(acc[i][j][v] * sc);
-                    out[col] = *reinterpret_cast<uint16_t *>(&b);
-                }
+                const float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
+                const float send = odd ? mine_e : mine_o;
+                const float recv = __shfl_xor(send, 1, kWave);
+                const uint32_t word = odd ? pack_bf16(recv, mine_o) : pack_bf16(mine_e, recv);
+                const int col = n0 + wn0 + j * 32 + (lane & 30);
+                if (dst >= 0 && col < K_in)
+                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = word;
             }
         }
 }
 
 // ------------------------------------------------------------------ wgrad
+
+// How many of the launched split-K slices do work for a given number of
+// contraction steps, and how many steps each takes.  Used by the GEMM and by
+// the reduction so that both agree.
+__host__ __device__ inline int wgrad_active_splits(int steps_all, int splits, int min_steps, int &per)
+{
+    int active = splits < steps_all / min_steps ? splits : steps_all / min_steps;
+    if (active < 1) active = 1;
+    per = (steps_all + active - 1) / active;
+    if (per < 1) per = 1;
+    active = (steps_all + per - 1) / per;
+    return active < 1 ? 1 : active;
+}
+
+// dW = partial[0] + partial[1] + ... in that order; does nothing when only one
+// split was active (the GEMM wrote dW itself).  `step` is the GEMM's
+// contraction step in tokens.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partials,
+                                                            const int32_t *__restrict__ cntW, float *__restrict__ dW,
+                                                            int64_t R, int64_t elems, int splits, int min_steps,
+                                                            int step)
+{
+    const int64_t cnt = min((int64_t)max(*cntW, 0), R);
+    int per;
+    const int active = wgrad_active_splits((int)((cnt + step - 1) / step), splits, min_steps, per);
+    if (active == 1) return;
+    for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (int64_t)gridDim.x * 1024) {
+        float4 t[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            t[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < active) t[s] = *reinterpret_cast<const float4 *>(partials + s * elems + i);
+        }
+        float4 sum = t[0];
+#pragma unroll
+        for (int s = 1; s < 8; ++s) {
+            sum.x += t[s].x;
+            sum.y += t[s].y;
+            sum.z += t[s].z;
+            sum.w += t[s].w;
+        }
+        *reinterpret_cast<float4 *>(dW + i) = sum;
+    }
+}
+
+vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW, int64_t R, int64_t elems, int splits,
+                          int min_steps, int step, hipStream_t st)
+{
+    if (splits <= 1) return VCAS_OK;
+    int64_t blocks = (elems / 4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partials, cntW, dW, R, elems,
+                       splits, min_steps, step);
+    return launch_status();
+}
 
 struct TokenQuad {
     int32_t tok[4];
@@ -340,18 +477,20 @@ struct TokenQuad {
 // grid: 1-D, splits * tiles workgroups (rounded up to a multiple of 8), split-
 // major, so that the workgroups one XCD gets (a contiguous run after the remap)
 // contract the same tokens and share those G and X rows in its L2.  Split s of
-// a tile contracts a contiguous run of 64-token steps.  With more than
-// one active split the partial tiles go to `partials` [split][K_out][K_in] and
-// the workgroup that arrives last at the tile's counter adds them up in split
-// order and writes dW, so the sum order is fixed.
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void wgrad_bf16_kernel(const uint16_t *__restrict__ G,
+// a tile contracts a contiguous run of 64-token steps.  The number of active
+// splits is derived from the device-side count (wgrad_active_splits).  With one
+// active split the tile goes straight to dW; otherwise the partial tiles go to
+// `partials` [split][K_out][K_in] and splitk_reduce_kernel adds them in split
+// order, so the sum order is fixed.  (An in-kernel "last workgroup reduces"
+// scheme was measured first: its device-scope fences write back the XCD's L2
+// and cost more than the second launch.)
+template <int BM, int BN, int WM, int WN, int OCC>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint16_t *__restrict__ G,
                                                                   const uint16_t *__restrict__ X,
                                                                   const float *__restrict__ row_scale,
                                                                   const int32_t *__restrict__ idxW,
                                                                   const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                                  float *__restrict__ partials,
-                                                                  int32_t *__restrict__ counters, int64_t R, int K_in,
+                                                                  float *__restrict__ partials, int64_t R, int K_in,
                                                                   int K_out, int tiles_n, int tiles, int splits,
                                                                   int min_steps)
 {
@@ -360,8 +499,6 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_bf16_kernel(const uint16_t 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     auto tA = [&](int buf) { return smem + buf * (BM * 128); };
     auto tB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
-    __shared__ int last_flag;
-
     const int total = tiles * splits;
     const int id = xcd_remap(blockIdx.x, total);
     if (id >= total) return;
@@ -370,26 +507,31 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_bf16_kernel(const uint16_t 
 
     const int64_t cnt = min((int64_t)max(*cntW, 0), R);
     const int steps_all = (int)((cnt + BK - 1) / BK);
-    int active = min(splits, max(1, steps_all / min_steps));
-    const int per = max(1, (steps_all + active - 1) / active);
-    active = max(1, (steps_all + per - 1) / per);
+    int per;
+    const int active = wgrad_active_splits(steps_all, splits, min_steps, per);
     if (split >= active) return;
     const int s_begin = split * per, s_end = min(steps_all, s_begin + per);
 
-    TransLoader<BM, NT> la;
-    TransLoader<BN, NT> lb;
-    static_assert(TransLoader<BM, NT>::PER == 1 && TransLoader<BN, NT>::PER == 1, "one unit per thread assumed");
-    const int kqa = la.kquad(0), kqb = lb.kquad(0);
-    const int cola = o0 + la.chunk(0) * 8, colb = c0 + lb.chunk(0) * 8;
+    typedef TransLoader<BM, NT> LA;
+    typedef TransLoader<BN, NT> LB;
+    static_assert(LA::PER == 1 && LB::PER == 1 && BM == BN, "one unit per thread, square tile assumed");
+    const int kq = LA::kquad(0);
+    const int cola = o0 + LA::chunk(0) * 8, colb = c0 + LB::chunk(0) * 8;
+    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
+    const __amdgpu_buffer_rsrc_t rsrcX = make_rsrc(X, (uint32_t)(R * K_in * 2));
+    typename LA::Regs ra[2];
+    typename LB::Regs rb[2];
+    float scale_of_set[2][4];   // per-token scales of the step held in the register set of the same index
+    TokenQuad ahead;     // fetched one step before its data loads are issued
 
-    auto fetch_quad = [&](int step, int kq) {
+    auto fetch_quad = [&](int step) {
         TokenQuad t;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t k = (int64_t)step * BK + kq * 4 + i;
+            const int64_t k = (int64_t)(s_begin + step) * BK + kq * 4 + i;
             t.tok[i] = -1;
             t.sc[i] = 0.0f;
-            if (step < s_end && k < cnt) {
+            if (s_begin + step < s_end && k < cnt) {
                 const int32_t r = idxW[k];
                 if (r >= 0 && r < R) {
                     t.tok[i] = r;
@@ -410,45 +552,40 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_bf16_kernel(const uint16_t 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    if (s_begin < s_end) {
-        TokenQuad qa = fetch_quad(s_begin, kqa), qb = fetch_quad(s_begin, kqb);
-        TokenQuad na, nb;
-        auto load_both = [&]() {
-            la.load([&](int, int i) -> const uint16_t * {
-                return (qa.tok[i] >= 0 && cola < K_out) ? G + (int64_t)qa.tok[i] * K_out + cola : nullptr;
-            });
-            lb.load([&](int, int i) -> const uint16_t * {
-                return (qb.tok[i] >= 0 && colb < K_in) ? X + (int64_t)qb.tok[i] * K_in + colb : nullptr;
-            });
+    ahead = fetch_quad(0);
+    auto load = [&](int set, int s) {
+        // `ahead` holds the quad of step s (steps are loaded in order); fetch the next one
+        const TokenQuad q = ahead;
+        ahead = fetch_quad(s + 1);
+        auto g_voff = [&](int, int i) {
+            return (q.tok[i] >= 0 && cola < K_out) ? ((uint32_t)q.tok[i] * (uint32_t)K_out + cola) * 2u : kOutside;
         };
-        load_both();
-        na = fetch_quad(s_begin + 1, kqa);
-        nb = fetch_quad(s_begin + 1, kqb);
-        {
-            const float sc[1][4] = {{qa.sc[0], qa.sc[1], qa.sc[2], qa.sc[3]}};
-            la.store_scaled(tA(0), sc);
-            lb.store(tB(0));
+        auto x_voff = [&](int, int i) {
+            return (q.tok[i] >= 0 && colb < K_in) ? ((uint32_t)q.tok[i] * (uint32_t)K_in + colb) * 2u : kOutside;
+        };
+        if (set == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) scale_of_set[0][i] = q.sc[i];
+            LA::load(ra[0], rsrcG, g_voff, 0u);
+            LB::load(rb[0], rsrcX, x_voff, 0u);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) scale_of_set[1][i] = q.sc[i];
+            LA::load(ra[1], rsrcG, g_voff, 0u);
+            LB::load(rb[1], rsrcX, x_voff, 0u);
         }
-        __syncthreads();
-        for (int s = s_begin; s < s_end; ++s) {
-            const int cur = (s - s_begin) & 1;
-            const bool more = s + 1 < s_end;
-            if (more) {
-                qa = na;
-                qb = nb;
-                load_both();
-                na = fetch_quad(s + 2, kqa);
-                nb = fetch_quad(s + 2, kqb);
-            }
-            mma_tile<TM, TN>(tA(cur), tB(cur), wm0, wn0, acc);
-            if (more) {
-                const float sc[1][4] = {{qa.sc[0], qa.sc[1], qa.sc[2], qa.sc[3]}};
-                la.store_scaled(tA(cur ^ 1), sc);
-                lb.store(tB(cur ^ 1));
-            }
-            __syncthreads();
+    };
+    auto stage = [&](int set, int buf) {
+        if (set == 0) {
+            LA::store_scaled(ra[0], tA(buf), scale_of_set[0]);
+            LB::store(rb[0], tB(buf));
+        } else {
+            LA::store_scaled(ra[1], tA(buf), scale_of_set[1]);
+            LB::store(rb[1], tB(buf));
         }
-    }
+    };
+    auto compute_step = [&](int buf) { mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
+    pipeline(s_end - s_begin, load, stage, compute_step);
 
     const int lane = threadIdx.x & 63;
     float *dst = active == 1 ? dW : partials + (int64_t)split * K_out * K_in;
@@ -464,35 +601,6 @@ __global__ __launch_bounds__(WM *WN * 64) void wgrad_bf16_kernel(const uint16_t 
                 if (c < K_in) dst[(int64_t)o * K_in + c] = acc[i][j][v];
             }
         }
-    if (active == 1) return;
-
-    // arrival: the last split of this tile reduces
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int prev = atomicAdd(&counters[tile], 1);
-        const int last = prev == active - 1;
-        if (last) counters[tile] = 0;
-        last_flag = last;
-    }
-    __syncthreads();
-    if (!last_flag) return;
-    __threadfence();
-    constexpr int CH = BN / 4;
-    for (int u = threadIdx.x; u < BM * CH; u += NT) {
-        const int o = o0 + u / CH, c = c0 + (u % CH) * 4;
-        if (o >= K_out || c >= K_in) continue;
-        const int64_t off = (int64_t)o * K_in + c;
-        float4 sum = *reinterpret_cast<const float4 *>(partials + off);
-        for (int s = 1; s < active; ++s) {
-            const float4 t = *reinterpret_cast<const float4 *>(partials + (int64_t)s * K_out * K_in + off);
-            sum.x += t.x;
-            sum.y += t.y;
-            sum.z += t.z;
-            sum.w += t.w;
-        }
-        *reinterpret_cast<float4 *>(dW + off) = sum;
-    }
 }
 
 // ---------------------------------------------------------- host launchers
@@ -506,40 +614,69 @@ static bool allow_lds(Kern kern, size_t bytes)
                                (int)bytes) == hipSuccess;
 }
 
-vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, hipStream_t st)
+template <int BM, int BN, int WM, int WN, int OCC>
+static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
+                                const int32_t *idxA, const int32_t *cntA, void *dX, hipStream_t st)
 {
-    constexpr int BM = 128, BN = 128, WM = 2, WN = 2;
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
     const int64_t grid = tiles_n * ((R + BM - 1) / BM + 1) + 8;
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
     const size_t lds = 2 * (BM + BN) * 128 + BM * 8;
-    auto kern = dgrad_bf16_kernel<BM, BN, WM, WN>;
-    if (!allow_lds(kern, lds)) return VCAS_EHIP;
+    static const int dbg = getenv("VCAS_DBG") ? atoi(getenv("VCAS_DBG")) : 0;
+    auto kern = dgrad_bf16_kernel<BM, BN, WM, WN, OCC>;
+    static bool allowed = false;   // once per instantiation
+    if (!allowed) {
+        if (!allow_lds(kern, lds)) return VCAS_EHIP;
+        allowed = true;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                        static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                       s.K_out, tiles_n);
+                       s.K_out, tiles_n, dbg);
     return launch_status();
 }
 
-vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int32_t *counters,
-                       int splits, hipStream_t st)
+static int tile_choice(const char *name)
 {
-    constexpr int BM = 128, BN = 128, WM = 2, WN = 2;
+    const char *e = getenv(name);
+    return e ? atoi(e) : 0;
+}
+
+vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
+                       const int32_t *cntA, void *dX, hipStream_t st)
+{
+    static const int choice = tile_choice("VCAS_DGRAD_TILE");
+    switch (choice) {
+    case 1: return launch_dgrad<256, 256, 2, 2, 1>(s, G, W, p, idxA, cntA, dX, st);
+    case 2: return launch_dgrad<256, 256, 2, 4, 2>(s, G, W, p, idxA, cntA, dX, st);
+    case 3: return launch_dgrad<256, 128, 2, 2, 1>(s, G, W, p, idxA, cntA, dX, st);
+    case 4: return launch_dgrad<128, 256, 2, 2, 1>(s, G, W, p, idxA, cntA, dX, st);
+    default: return launch_dgrad<128, 128, 2, 2, 2>(s, G, W, p, idxA, cntA, dX, st);
+    }
+}
+
+vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
+                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
+                       hipStream_t st)
+{
+    constexpr int BM = 128, BN = 128, WM = 2, WN = 2, MIN_STEPS = 2;
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
     const int tiles = ((s.K_out + BM - 1) / BM) * tiles_n;
-    if (tiles > (int)kCounterInts) splits = 1;
+    if (splits > 8) splits = 8;
     const size_t lds = 2 * (BM + BN) * 128;
-    auto kern = wgrad_bf16_kernel<BM, BN, WM, WN>;
-    if (!allow_lds(kern, lds)) return VCAS_EHIP;
+    auto kern = wgrad_bf16_kernel<BM, BN, WM, WN, 2>;
+    static bool allowed = false;
+    if (!allowed) {
+        if (!allow_lds(kern, lds)) return VCAS_EHIP;
+        allowed = true;
+    }
     const int grid = (tiles * splits + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
-                       static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, counters, R, s.K_in,
-                       s.K_out, tiles_n, tiles, splits, 4);
-    return launch_status();
+                       static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out,
+                       tiles_n, tiles, splits, MIN_STEPS);
+    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
 }
 
 }  // namespace vcas

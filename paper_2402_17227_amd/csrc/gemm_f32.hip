@@ -10,6 +10,21 @@ namespace vcas {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+// gemm_bf16.hip
+vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW, int64_t R, int64_t elems, int splits,
+                          int min_steps, int step, hipStream_t st);
+
+// same rule as the bf16 kernels use (kept in step with it by the shared reduction kernel's tests)
+__host__ __device__ inline int wgrad_active_splits(int steps_all, int splits, int min_steps, int &per)
+{
+    int active = splits < steps_all / min_steps ? splits : steps_all / min_steps;
+    if (active < 1) active = 1;
+    per = (steps_all + active - 1) / active;
+    if (per < 1) per = 1;
+    active = (steps_all + per - 1) / per;
+    return active < 1 ? 1 : active;
+}
+
 namespace f32gemm {
 
 constexpr int BM = 64, BN = 64, BKF = 16, PITCH = 68, NT = 256;
@@ -153,19 +168,17 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
 }
 
 // grid: splits * tiles workgroups rounded up to 8, split-major; see the bf16
-// kernel for the split-K protocol (same counters and partial buffers).
+// kernel for the split-K protocol (same partial buffers and reduction kernel).
 __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict__ G, const float *__restrict__ X,
                                                         const float *__restrict__ row_scale,
                                                         const int32_t *__restrict__ idxW,
                                                         const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                        float *__restrict__ partials, int32_t *__restrict__ counters,
-                                                        int64_t R, int K_in, int K_out, int tiles_n, int tiles,
+                                                        float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles,
                                                         int splits, int min_steps)
 {
     using namespace f32gemm;
     __shared__ __attribute__((aligned(16))) float As[2][TILE_FLOATS];
     __shared__ __attribute__((aligned(16))) float Bs[2][TILE_FLOATS];
-    __shared__ int last_flag;
 
     const int total = tiles * splits;
     const int id = xcd_remap(blockIdx.x, total);
@@ -176,9 +189,8 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict_
 
     const int64_t cnt = min((int64_t)max(*cntW, 0), R);
     const int steps_all = (int)((cnt + BKF - 1) / BKF);
-    int active = min(splits, max(1, steps_all / min_steps));
-    const int per = max(1, (steps_all + active - 1) / active);
-    active = max(1, (steps_all + per - 1) / per);
+    int per;
+    const int active = wgrad_active_splits(steps_all, splits, min_steps, per);
     if (split >= active) return;
     const int s_begin = split * per, s_end = min(steps_all, s_begin + per);
 
@@ -245,33 +257,6 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict_
         const int o = o0 + wm0 + acc_row(v);
         if (o < K_out && c < K_in) dst[(int64_t)o * K_in + c] = acc[v];
     }
-    if (active == 1) return;
-
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int prev = atomicAdd(&counters[tile], 1);
-        const int last = prev == active - 1;
-        if (last) counters[tile] = 0;
-        last_flag = last;
-    }
-    __syncthreads();
-    if (!last_flag) return;
-    __threadfence();
-    for (int u = tid; u < BM * (BN / 4); u += NT) {
-        const int o = o0 + u / (BN / 4), cc = c0 + (u % (BN / 4)) * 4;
-        if (o >= K_out || cc >= K_in) continue;
-        const int64_t off = (int64_t)o * K_in + cc;
-        float4 sum = *reinterpret_cast<const float4 *>(partials + off);
-        for (int s = 1; s < active; ++s) {
-            const float4 t = *reinterpret_cast<const float4 *>(partials + (int64_t)s * K_out * K_in + off);
-            sum.x += t.x;
-            sum.y += t.y;
-            sum.z += t.z;
-            sum.w += t.w;
-        }
-        *reinterpret_cast<float4 *>(dW + off) = sum;
-    }
 }
 
 int wgrad_tiles_f32(int K_out, int K_in) { return ((K_out + 63) / 64) * ((K_in + 63) / 64); }
@@ -290,17 +275,19 @@ vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const f
 }
 
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
-                      const int32_t *cntW, float *dW, float *partials, int32_t *counters, int splits, hipStream_t st)
+                      const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st)
 {
+    constexpr int MIN_STEPS = 8;
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + 63) / 64;
     const int tiles = ((s.K_out + 63) / 64) * tiles_n;
-    if (tiles > (int)kCounterInts) splits = 1;
+    if (splits > 8) splits = 8;
     const int grid = (tiles * splits + 7) / 8 * 8;
     hipLaunchKernelGGL(wgrad_f32_kernel, dim3(grid), dim3(256), 0, st, static_cast<const float *>(G),
-                       static_cast<const float *>(X), row_scale, idxW, cntW, dW, partials, counters, R, s.K_in,
-                       s.K_out, tiles_n, tiles, splits, 8);
-    return launch_status();
+                       static_cast<const float *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
+                       tiles, splits, MIN_STEPS);
+    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, f32gemm::BKF, st);
 }
 
 }  // namespace vcas
