@@ -20,6 +20,12 @@ vcas_status leverage_scores(const float *gsq, const float *xsq, const float *p, 
 vcas_status row_scale(const float *p, const float *q, const uint8_t *maskW, int64_t R, int T, float *scale,
                       hipStream_t st);
 vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q, uint8_t *maskW, hipStream_t st);
+vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
+                      uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st);
+vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
+vcas_status sampler_w(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, const float *u, int N,
+                      int T, double budget, int token_sampling, float *score, float *q, uint8_t *maskW, float *scaleW,
+                      int32_t *idxW, int32_t *cntW, hipStream_t st);
 // gemm_bf16.hip / gemm_f32.hip
 int wgrad_tiles_bf16(int K_out, int K_in);
 int wgrad_tiles_f32(int K_out, int K_in);
@@ -150,21 +156,14 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
                                         void *dX, float *dW, void *workspace, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
+    float *u = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + workspace_layout(&s).uniforms);
     VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
-    VCAS_TRY(sample_norms(pl.gsq, s.N, s.T, pl.gnorm, st));
-    VCAS_TRY(keep_probs(pl.gnorm, s.N, (double)s.N * rho, pl.p, st));
-    VCAS_TRY(sample_compact(pl.p, s.N, rng, 0u, pl.maskA, pl.idxA, pl.cntA, st));
+    VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
+    if (token_sampling) VCAS_TRY(uniforms(R, rng, 1u, u, st));
     VCAS_TRY(row_sumsq(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, st));
-    VCAS_TRY(leverage_scores(pl.gsq, pl.xsq, pl.p, pl.maskA, R, s.T, pl.score, st));
-    if (token_sampling) {
-        VCAS_TRY(keep_probs(pl.score, (int)R, (double)R * rho * nu, pl.q, st));
-        VCAS_TRY(sample_compact(pl.q, (int)R, rng, 1u, pl.maskW, pl.idxW, pl.cntW, st));
-    } else {
-        VCAS_TRY(broadcast_data_mask(pl.maskA, R, s.T, pl.q, pl.maskW, st));
-        VCAS_TRY(compact_only(pl.maskW, (int)R, pl.idxW, pl.cntW, st));
-    }
-    VCAS_TRY(row_scale(pl.p, pl.q, pl.maskW, R, s.T, pl.scaleW, st));
+    VCAS_TRY(sampler_w(pl.gsq, pl.xsq, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu, token_sampling, pl.score,
+                       pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
     if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
     return VCAS_OK;
 }
@@ -281,7 +280,7 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
     VCAS_TRY(check_shape(shape));
     if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
     if (dX && !W) return VCAS_ENULL;
-    if (dW && !workspace) return VCAS_EWORKSPACE;
+    if (!workspace) return VCAS_EWORKSPACE;
     if (!ratio_ok(rho) || !ratio_ok(nu)) return VCAS_EINVAL;
     if (!aligned16(G) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || (dW && !aligned16(dW)) ||
         (workspace && !aligned16(workspace)))

@@ -36,14 +36,15 @@ inline int elem_bytes(int dtype) { return dtype == VCAS_BF16 ? 2 : 4; }
 // ---- workspace layout -------------------------------------------------------
 // [0, kCounterBytes)          split-K arrival counters (int32), zero between calls
 // [kCounterBytes, +partials)  split-K partial tiles of the weight gradient (fp32)
-// then two K_out*K_in fp32 matrices and 8 doubles for the variance probe
+// then two K_out*K_in fp32 matrices and 32 doubles for the variance probe,
+// then R floats: the SampleW uniforms of vcas_linear_backward
 
 constexpr size_t kCounterInts = 16384;
 constexpr size_t kCounterBytes = kCounterInts * sizeof(int32_t);
 constexpr int kMaxSplit = 16;
 
 struct WorkspaceLayout {
-    size_t counters, partials, probe_exact, probe_draw, probe_acc, total;
+    size_t counters, partials, probe_exact, probe_draw, probe_acc, uniforms, total;
 };
 
 int wgrad_split(const vcas_shape *s);   // host: number of split-K slices for this shape
@@ -57,7 +58,8 @@ inline WorkspaceLayout workspace_layout(const vcas_shape *s)
     w.probe_exact = w.partials + mat * (size_t)wgrad_split(s);
     w.probe_draw = w.probe_exact + mat;
     w.probe_acc = w.probe_draw + mat;
-    w.total = w.probe_acc + 256;
+    w.uniforms = w.probe_acc + 256;
+    w.total = w.uniforms + (((size_t)s->N * s->T * sizeof(float) + 255) & ~(size_t)255);
     return w;
 }
 

@@ -206,6 +206,90 @@ __global__ __launch_bounds__(256) void broadcast_data_mask_kernel(const uint8_t 
     maskW[t] = m;
 }
 
+// ---- fused single-workgroup samplers (used by vcas_linear_backward) -----------
+// The vectors are at most R floats, so one workgroup of 1024 threads does the
+// whole decision chain of a sampler in one launch instead of five.
+
+// SampleA: ||G_i||_F from gsq, p, Bernoulli mask over samples, kept list.
+__global__ __launch_bounds__(1024) void sampler_a_kernel(const float *__restrict__ gsq, int N, int T, double budget,
+                                                         uint64_t seed, uint32_t layer, uint32_t draw,
+                                                         float *__restrict__ gnorm, float *__restrict__ p,
+                                                         uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
+                                                         int32_t *__restrict__ cntA)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = wave; i < N; i += 16) {
+        const float *row = gsq + (int64_t)i * T;
+        float acc = 0.0f;
+        for (int t = lane; t < T; t += 64) acc = acc + row[t];
+        acc = wave_exchange_sum(acc);
+        if (lane == 0) gnorm[i] = __builtin_sqrtf(acc);
+    }
+    __syncthreads();
+    keep_probs_block(gnorm, N, budget, p);
+    __syncthreads();
+    for (int i = tid; i < N; i += 1024) maskA[i] = philox_uniform(seed, layer, 0u, draw, (uint32_t)i) < p[i] ? 1 : 0;
+    __syncthreads();
+    compact_block(maskA, N, idxA, cntA);
+}
+
+// Uniforms of SampleW for every row (independent of the data, so they are
+// drawn by many workgroups while the row norms stream).
+__global__ __launch_bounds__(256) void uniforms_kernel(int64_t R, uint64_t seed, uint32_t layer, uint32_t stream_id,
+                                                       uint32_t draw, float *__restrict__ u)
+{
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r < R) u[r] = philox_uniform(seed, layer, stream_id, draw, (uint32_t)r);
+}
+
+// SampleW: leverage scores, q, Bernoulli mask over tokens (uniforms given),
+// per-token scale, kept list.  With token_sampling == 0 every token of a kept
+// sample is kept with q = 1.
+__global__ __launch_bounds__(1024) void sampler_w_kernel(const float *__restrict__ gsq, const float *__restrict__ xsq,
+                                                         const float *__restrict__ p,
+                                                         const uint8_t *__restrict__ maskA,
+                                                         const float *__restrict__ u, int N, int T, double budget,
+                                                         int token_sampling, float *__restrict__ score,
+                                                         float *__restrict__ q, uint8_t *__restrict__ maskW,
+                                                         float *__restrict__ scaleW, int32_t *__restrict__ idxW,
+                                                         int32_t *__restrict__ cntW)
+{
+    const int tid = threadIdx.x;
+    const int R = N * T;
+    for (int t = tid; t < R; t += 1024) {
+        const int i = t / T;
+        float s = 0.0f;
+        if (maskA[i]) {
+            const float inv = 1.0f / p[i];
+            const float a = inv * __builtin_sqrtf(gsq[t]);
+            s = a * __builtin_sqrtf(xsq[t]);
+        }
+        score[t] = s;
+    }
+    __syncthreads();
+    if (token_sampling) {
+        keep_probs_block(score, R, budget, q);
+        __syncthreads();
+    }
+    for (int t = tid; t < R; t += 1024) {
+        const int i = t / T;
+        uint8_t m;
+        float qt;
+        if (token_sampling) {
+            qt = q[t];
+            m = u[t] < qt ? 1 : 0;
+        } else {
+            m = maskA[i] ? 1 : 0;
+            qt = m ? 1.0f : 0.0f;
+            q[t] = qt;
+        }
+        maskW[t] = m;
+        scaleW[t] = m ? 1.0f / (p[i] * qt) : 0.0f;
+    }
+    __syncthreads();
+    compact_block(maskW, R, idxW, cntW);
+}
+
 // ---- host launchers ---------------------------------------------------------
 
 vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st)
@@ -252,6 +336,30 @@ vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q
 {
     hipLaunchKernelGGL(broadcast_data_mask_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, maskA, R, T,
                        q, maskW);
+    return launch_status();
+}
+
+vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
+                      uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st)
+{
+    hipLaunchKernelGGL(sampler_a_kernel, dim3(1), dim3(1024), 0, st, gsq, N, T, budget, rng.seed, rng.layer, rng.draw,
+                       gnorm, p, maskA, idxA, cntA);
+    return launch_status();
+}
+
+vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st)
+{
+    hipLaunchKernelGGL(uniforms_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, R, rng.seed, rng.layer,
+                       stream_id, rng.draw, u);
+    return launch_status();
+}
+
+vcas_status sampler_w(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, const float *u, int N,
+                      int T, double budget, int token_sampling, float *score, float *q, uint8_t *maskW, float *scaleW,
+                      int32_t *idxW, int32_t *cntW, hipStream_t st)
+{
+    hipLaunchKernelGGL(sampler_w_kernel, dim3(1), dim3(1024), 0, st, gsq, xsq, p, maskA, u, N, T, budget,
+                       token_sampling, score, q, maskW, scaleW, idxW, cntW);
     return launch_status();
 }
 
