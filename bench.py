@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -89,20 +90,34 @@ def main():
     torch.cuda.synchronize()
     dense_flops = sum(l.dense_flops for l in layers)
 
-    def step(draw, rho=None, nu=None):
+    # The draw index lives in device memory so that one captured graph gives fresh masks on
+    # every replay: each step first bumps the counter, every layer adds it to its draw.
+    draw_counter = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def step():
+        draw_counter.add_(1)
         for l in layers:
             s = l.spec
-            vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, s.rho if rho is None else rho,
-                                    s.nu if nu is None else nu, vb.Rng(s.seed, s.layer, draw), True, l.plan,
+            vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, s.rho, s.nu,
+                                    vb.Rng(s.seed, s.layer, 0, draw_counter.data_ptr()), True, l.plan,
                                     l.dX, l.dW, l.ws)
 
     # ---- timed region: K steps of the whole path --------------------------------
+    step()                                       # eager once: one-time kernel attribute set-up
+    torch.cuda.synchronize()
+    if args.eager:
+        run_step = step
+    else:                                        # the ~580 launches of a step as one HIP graph
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
     for i in range(args.warmup):
-        step(i)
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i)
+        run_step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -113,9 +128,14 @@ def main():
     # ---- per-kernel durations of the two GEMMs, HIP events on the launch stream ----
     # Replays each layer's dgrad / wgrad entry point on the plan the last step left,
     # one event pair per launch, same shapes, inputs and launch configuration.
+    # (wgrad = the GEMM launch plus, where split-K is active, its small reduction launch.)
+    busy_a = torch.randn(8192, 8192, device="cuda").bfloat16()
+
     def kernel_times(call):
         evs = []
         for _ in range(max(3, min(args.steps, 10))):
+            for _ in range(4):                  # keep the GPU busy while the host queues the launches below,
+                torch.mm(busy_a, busy_a)        # so that an event pair brackets the kernel and no host gap
             for l in layers:
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
@@ -180,6 +200,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "launch": "eager" if args.eager else "hip_graph",
         "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,

@@ -57,11 +57,15 @@ typedef struct {
  * samples, 1 = SampleW over tokens) is decided by the Philox4x32-10 block with
  * counter (r, layer, s, draw) and key (seed low word, seed high word): the top
  * 24 bits of output word 0, scaled to [0,1), are compared with the keep
- * probability.  (The paper writes Bern(p; eps) without naming a generator.) */
+ * probability.  (The paper writes Bern(p; eps) without naming a generator.)
+ * draw_offset, if not null, is a DEVICE pointer to one uint32 that the kernels
+ * add to `draw` when they run: a caller that replays a captured HIP graph
+ * bumps that word between replays to get fresh masks without new launches. */
 typedef struct {
     uint64_t seed;
     uint32_t layer;
     uint32_t draw;
+    const uint32_t *draw_offset;
 } vcas_rng;
 
 /* Everything the sampling steps decide for one layer; all device pointers,

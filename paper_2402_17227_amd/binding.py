@@ -32,7 +32,8 @@ class Shape(C.Structure):
 
 
 class Rng(C.Structure):
-    _fields_ = [("seed", C.c_uint64), ("layer", C.c_uint32), ("draw", C.c_uint32)]
+    """vcas_rng; draw_offset is the data_ptr() of a device uint32 (or 0 / omitted)."""
+    _fields_ = [("seed", C.c_uint64), ("layer", C.c_uint32), ("draw", C.c_uint32), ("draw_offset", C.c_void_p)]
 
 
 class PlanPtrs(C.Structure):

@@ -10,6 +10,8 @@ namespace vcas {
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
                       hipStream_t st);
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st);
+vcas_status row_sumsq_with_uniforms(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
+                                    const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st);
 // sampling.hip
 vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st);
 vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32_t stream_id, uint8_t *mask,
@@ -160,8 +162,8 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
     VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
-    if (token_sampling) VCAS_TRY(uniforms(R, rng, 1u, u, st));
-    VCAS_TRY(row_sumsq(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, st));
+    VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, token_sampling ? u : nullptr,
+                                     st));
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu, token_sampling, pl.score,
                        pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
     if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));

@@ -33,11 +33,26 @@ __device__ __forceinline__ float fold16(const uint4 &c, float acc)
 
 // One wavefront per row; CH 16-byte groups per lane are in flight at once.
 // Rows of samples whose sample_keep byte is 0 are not read and get 0.
+// If `uniforms` is given, the launch also draws the Philox uniform of every row
+// for sampler `stream_id` (they do not depend on the data; the arithmetic hides
+// under the memory stream).
+struct UniformJob {
+    float *uniforms;   // null: no job
+    uint64_t seed;
+    uint32_t layer, stream_id, draw;
+    const uint32_t *draw_offset;
+};
+
 template <bool BF16, int CH>
 __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
                                                         int T, const uint8_t *__restrict__ sample_keep,
-                                                        float *__restrict__ out)
+                                                        float *__restrict__ out, UniformJob job)
 {
+    if (job.uniforms) {
+        const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
+        for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < R; r += (int64_t)gridDim.x * 256)
+            job.uniforms[r] = philox_uniform(job.seed, job.layer, job.stream_id, draw, (uint32_t)r);
+    }
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -81,7 +96,7 @@ __global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restric
 
 template <bool BF16>
 static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, const uint8_t *keep, float *out,
-                                    hipStream_t st)
+                                    const UniformJob &job, hipStream_t st)
 {
     const int groups = K / (BF16 ? 8 : 4);
     const int need = (groups + 63) / 64;
@@ -89,7 +104,7 @@ static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, cons
     const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
     const uint4 *a = static_cast<const uint4 *>(A);
 #define VCAS_LAUNCH_CH(C) \
-    hipLaunchKernelGGL((row_sumsq_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, R, groups, T, keep, out)
+    hipLaunchKernelGGL((row_sumsq_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, R, groups, T, keep, out, job)
     if (need <= 1) VCAS_LAUNCH_CH(1);
     else if (need <= 2) VCAS_LAUNCH_CH(2);
     else if (need <= 3) VCAS_LAUNCH_CH(3);
@@ -103,8 +118,18 @@ static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, cons
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
                       hipStream_t st)
 {
-    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, st)
-                              : launch_row_sumsq<false>(A, R, K, T, keep, out, st);
+    const UniformJob none = {nullptr, 0, 0, 0, 0, nullptr};
+    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, none, st)
+                              : launch_row_sumsq<false>(A, R, K, T, keep, out, none, st);
+}
+
+// row norms plus the uniforms of sampler `stream_id` in one launch
+vcas_status row_sumsq_with_uniforms(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
+                                    const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st)
+{
+    const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
+    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, job, st)
+                              : launch_row_sumsq<false>(A, R, K, T, keep, out, job, st);
 }
 
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st)

@@ -119,10 +119,12 @@ __global__ __launch_bounds__(1024) void keep_probs_kernel(const float *__restric
 // mask[r] = [u_r < prob[r]]
 __global__ __launch_bounds__(256) void bernoulli_mask_kernel(const float *__restrict__ prob, int n, uint64_t seed,
                                                              uint32_t layer, uint32_t stream_id, uint32_t draw,
+                                                             const uint32_t *__restrict__ draw_offset,
                                                              uint8_t *__restrict__ mask)
 {
     const int r = blockIdx.x * 256 + threadIdx.x;
     if (r >= n) return;
+    if (draw_offset) draw += *draw_offset;
     const float u = philox_uniform(seed, layer, stream_id, draw, (uint32_t)r);
     mask[r] = u < prob[r] ? 1 : 0;
 }
@@ -210,14 +212,176 @@ __global__ __launch_bounds__(256) void broadcast_data_mask_kernel(const uint8_t 
 // The vectors are at most R floats, so one workgroup of 1024 threads does the
 // whole decision chain of a sampler in one launch instead of five.
 
+// keep_probs_block with the scores held in registers: thread tid owns elements
+// tid + 1024*j, j < E (zero past the end).  Same sums in the same order, but a
+// round costs one barrier and no memory traffic.
+template <int E>
+__device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob)[E])
+{
+    __shared__ double sd[2][16];
+    __shared__ int si[2][16];
+    double part = 0.0;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+        if (a[j] > 0.0f) {
+            part += (double)a[j];
+            ++cnt;
+        }
+    double S = block_sum_1024(part, sd[0]);
+    const int nonzero = block_sum_1024(cnt, si[0]);
+    if (budget >= (double)nonzero) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) prob[j] = a[j] > 0.0f ? 1.0f : 0.0f;
+        return;
+    }
+    uint32_t fixed = 0;   // bit j: element j is fixed at one
+    int ncap = 0;
+    double c = 0.0;
+    int flip = 1;
+    for (;;) {
+        const double rem = budget - (double)ncap;
+        if (!(S > 0.0) || !(rem > 0.0)) {
+            c = 0.0;
+            break;
+        }
+        c = rem / S;
+        part = 0.0;
+        cnt = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+            if (a[j] > 0.0f && !((fixed >> j) & 1u)) {
+                if (c * (double)a[j] >= 1.0) {
+                    fixed |= 1u << j;
+                    ++cnt;
+                } else {
+                    part += (double)a[j];
+                }
+            }
+        const double S_next = block_sum_1024(part, sd[flip]);
+        const int newly = block_sum_1024(cnt, si[flip]);
+        flip ^= 1;
+        if (newly == 0) break;
+        ncap += newly;
+        S = S_next;
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        float p = 0.0f;
+        if ((fixed >> j) & 1u) p = 1.0f;
+        else if (a[j] > 0.0f) {
+            p = (float)(c * (double)a[j]);
+            p = p < 1.0f ? p : 1.0f;
+        }
+        prob[j] = p;
+    }
+}
+
+// SampleA for N <= 1024 with every intermediate in LDS or registers.
+__global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__restrict__ gsq, int N, int T,
+                                                              double budget, uint64_t seed, uint32_t layer,
+                                                              uint32_t draw, const uint32_t *__restrict__ draw_offset,
+                                                              float *__restrict__ gnorm, float *__restrict__ p,
+                                                              uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
+                                                              int32_t *__restrict__ cntA)
+{
+    __shared__ float gn[1024];
+    __shared__ uint8_t mk[1024];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (draw_offset) draw += *draw_offset;
+    for (int i = wave; i < N; i += 16) {
+        const float *row = gsq + (int64_t)i * T;
+        float acc = 0.0f;
+        for (int t = lane; t < T; t += 64) acc = acc + row[t];
+        acc = wave_exchange_sum(acc);
+        if (lane == 0) gn[i] = __builtin_sqrtf(acc);
+    }
+    __syncthreads();
+    float a[1], pr[1];
+    a[0] = tid < N ? gn[tid] : 0.0f;
+    keep_probs_regs<1>(a, budget, pr);
+    uint8_t m = 0;
+    if (tid < N) {
+        m = philox_uniform(seed, layer, 0u, draw, (uint32_t)tid) < pr[0] ? 1 : 0;
+        gnorm[tid] = a[0];
+        p[tid] = pr[0];
+        maskA[tid] = m;
+    }
+    mk[tid] = m;
+    __syncthreads();
+    compact_block(mk, N, idxA, cntA);
+}
+
+// SampleW for R <= 1024*E.
+template <int E>
+__global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__restrict__ gsq,
+                                                              const float *__restrict__ xsq,
+                                                              const float *__restrict__ p,
+                                                              const uint8_t *__restrict__ maskA,
+                                                              const float *__restrict__ u, int N, int T, double budget,
+                                                              int token_sampling, float *__restrict__ score,
+                                                              float *__restrict__ q, uint8_t *__restrict__ maskW,
+                                                              float *__restrict__ scaleW, int32_t *__restrict__ idxW,
+                                                              int32_t *__restrict__ cntW)
+{
+    __shared__ uint8_t mk[1024 * E];
+    const int tid = threadIdx.x;
+    const int R = N * T;
+    float a[E], qv[E], pinv_src[E], uu[E];
+    uint8_t keepA[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const int t = tid + 1024 * j;
+        a[j] = 0.0f;
+        pinv_src[j] = 1.0f;
+        uu[j] = 2.0f;
+        keepA[j] = 0;
+        if (t < R) {
+            const int i = t / T;
+            keepA[j] = maskA[i];
+            pinv_src[j] = p[i];
+            const float g = gsq[t], x = xsq[t];
+            if (token_sampling) uu[j] = u[t];
+            if (keepA[j]) {
+                const float inv = 1.0f / pinv_src[j];
+                const float s1 = inv * __builtin_sqrtf(g);
+                a[j] = s1 * __builtin_sqrtf(x);
+            }
+            score[t] = a[j];
+        }
+    }
+    if (token_sampling) {
+        keep_probs_regs<E>(a, budget, qv);
+    } else {
+#pragma unroll
+        for (int j = 0; j < E; ++j) qv[j] = keepA[j] ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const int t = tid + 1024 * j;
+        uint8_t m = 0;
+        if (t < R) {
+            m = token_sampling ? (uu[j] < qv[j] ? 1 : 0) : (keepA[j] ? 1 : 0);
+            q[t] = qv[j];
+            maskW[t] = m;
+            scaleW[t] = m ? 1.0f / (pinv_src[j] * qv[j]) : 0.0f;
+        }
+        mk[t] = m;
+    }
+    __syncthreads();
+    compact_block(mk, R, idxW, cntW);
+}
+
 // SampleA: ||G_i||_F from gsq, p, Bernoulli mask over samples, kept list.
 __global__ __launch_bounds__(1024) void sampler_a_kernel(const float *__restrict__ gsq, int N, int T, double budget,
                                                          uint64_t seed, uint32_t layer, uint32_t draw,
+                                                         const uint32_t *__restrict__ draw_offset,
                                                          float *__restrict__ gnorm, float *__restrict__ p,
                                                          uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
                                                          int32_t *__restrict__ cntA)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (draw_offset) draw += *draw_offset;
     for (int i = wave; i < N; i += 16) {
         const float *row = gsq + (int64_t)i * T;
         float acc = 0.0f;
@@ -236,9 +400,11 @@ __global__ __launch_bounds__(1024) void sampler_a_kernel(const float *__restrict
 // Uniforms of SampleW for every row (independent of the data, so they are
 // drawn by many workgroups while the row norms stream).
 __global__ __launch_bounds__(256) void uniforms_kernel(int64_t R, uint64_t seed, uint32_t layer, uint32_t stream_id,
-                                                       uint32_t draw, float *__restrict__ u)
+                                                       uint32_t draw, const uint32_t *__restrict__ draw_offset,
+                                                       float *__restrict__ u)
 {
     const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (draw_offset) draw += *draw_offset;
     if (r < R) u[r] = philox_uniform(seed, layer, stream_id, draw, (uint32_t)r);
 }
 
@@ -303,7 +469,7 @@ vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32
 {
     if (n > 0) {
         hipLaunchKernelGGL(bernoulli_mask_kernel, dim3((n + 255) / 256), dim3(256), 0, st, prob, n, rng.seed,
-                           rng.layer, stream_id, rng.draw, mask);
+                           rng.layer, stream_id, rng.draw, rng.draw_offset, mask);
         if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     }
     hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, mask, n, idx, count);
@@ -342,15 +508,19 @@ vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q
 vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
                       uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st)
 {
-    hipLaunchKernelGGL(sampler_a_kernel, dim3(1), dim3(1024), 0, st, gsq, N, T, budget, rng.seed, rng.layer, rng.draw,
-                       gnorm, p, maskA, idxA, cntA);
+    if (N <= 1024)
+        hipLaunchKernelGGL(sampler_a_fast_kernel, dim3(1), dim3(1024), 0, st, gsq, N, T, budget, rng.seed, rng.layer,
+                           rng.draw, rng.draw_offset, gnorm, p, maskA, idxA, cntA);
+    else
+        hipLaunchKernelGGL(sampler_a_kernel, dim3(1), dim3(1024), 0, st, gsq, N, T, budget, rng.seed, rng.layer,
+                           rng.draw, rng.draw_offset, gnorm, p, maskA, idxA, cntA);
     return launch_status();
 }
 
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st)
 {
     hipLaunchKernelGGL(uniforms_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, R, rng.seed, rng.layer,
-                       stream_id, rng.draw, u);
+                       stream_id, rng.draw, rng.draw_offset, u);
     return launch_status();
 }
 
@@ -358,8 +528,15 @@ vcas_status sampler_w(const float *gsq, const float *xsq, const float *p, const 
                       int T, double budget, int token_sampling, float *score, float *q, uint8_t *maskW, float *scaleW,
                       int32_t *idxW, int32_t *cntW, hipStream_t st)
 {
-    hipLaunchKernelGGL(sampler_w_kernel, dim3(1), dim3(1024), 0, st, gsq, xsq, p, maskA, u, N, T, budget,
-                       token_sampling, score, q, maskW, scaleW, idxW, cntW);
+    const int64_t R = (int64_t)N * T;
+#define VCAS_SAMPLER_W_ARGS gsq, xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW, scaleW, idxW, cntW
+    if (R <= 4096)
+        hipLaunchKernelGGL(sampler_w_fast_kernel<4>, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
+    else if (R <= 16384)
+        hipLaunchKernelGGL(sampler_w_fast_kernel<16>, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
+    else
+        hipLaunchKernelGGL(sampler_w_kernel, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
+#undef VCAS_SAMPLER_W_ARGS
     return launch_status();
 }
 

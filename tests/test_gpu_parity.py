@@ -219,6 +219,19 @@ def test_linear_backward_small_cases(vb, spec):
         assert np.all(dW == 0)
 
 
+@pytest.mark.parametrize("N,T", [(20, 1000), (1100, 3), (33, 500)])
+def test_linear_backward_long_vectors(vb, N, T):
+    # more rows than the register-resident samplers hold (R > 16384) and more samples than 1024
+    from tests.gpu_util import run_layer_gpu, compare_plan, rel_l2
+    spec = workloads.LayerSpec("long", BF16, N, T, 64, 72, 0.4, 0.5, layer=2, seed=9, gen_seed=12, token_sigma=0.5)
+    G, X, W = workloads.make_layer(spec)
+    got_plan, dX, dW = run_layer_gpu(spec, G, X, W, draw=2)
+    want_plan, want_dX, want_dW = oracle.linear_backward(G, X, W, spec.dtype, spec.N, spec.T, spec.rho, spec.nu,
+                                                         spec.seed, spec.layer, 2)
+    compare_plan(got_plan, want_plan)
+    assert rel_l2(dX, want_dX) <= TOL[BF16] and rel_l2(dW, want_dW) <= TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_keep_ratio_one_is_the_dense_backward(vb, dtype):
     from tests.gpu_util import run_layer_gpu, rel_l2
