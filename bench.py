@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -94,13 +95,23 @@ def main():
     # every replay: each step first bumps the counter, every layer adds it to its draw.
     draw_counter = torch.zeros(1, dtype=torch.int32, device="cuda")
 
+    # Two streams: norms of G, SampleA and dX of every layer run in order on the main stream (the
+    # order a real backward pass imposes), each layer's weight-gradient half (norms of X, SampleW,
+    # dW) follows its SampleA on the side stream; the step ends when both have drained.
+    side = None if args.one_stream else torch.cuda.Stream()
+
     def step():
+        main = torch.cuda.current_stream()
         draw_counter.add_(1)
+        if side is not None:
+            side.wait_stream(main)
         for l in layers:
             s = l.spec
             vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, s.rho, s.nu,
                                     vb.Rng(s.seed, s.layer, 0, draw_counter.data_ptr()), True, l.plan,
-                                    l.dX, l.dW, l.ws)
+                                    l.dX, l.dW, l.ws, side)
+        if side is not None:
+            main.wait_stream(side)
 
     # ---- timed region: K steps of the whole path --------------------------------
     step()                                       # eager once: one-time kernel attribute set-up
@@ -126,30 +137,16 @@ def main():
     kept_fraction = (kept_rows + kept_toks) / dense_flops
 
     # ---- per-kernel durations of the two GEMMs, HIP events on the launch stream ----
-    # Replays each layer's dgrad / wgrad entry point on the plan the last step left,
-    # one event pair per launch, same shapes, inputs and launch configuration.
-    # (wgrad = the GEMM launch plus, where split-K is active, its small reduction launch.)
-    busy_a = torch.randn(8192, 8192, device="cuda").bfloat16()
-
-    def kernel_times(call):
-        evs = []
-        for _ in range(max(3, min(args.steps, 10))):
-            for _ in range(4):                  # keep the GPU busy while the host queues the launches below,
-                torch.mm(busy_a, busy_a)        # so that an event pair brackets the kernel and no host gap
-            for l in layers:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                call(l)
-                b.record()
-                evs.append((a, b))
-        torch.cuda.synchronize()
-        t = [a.elapsed_time(b) for a, b in evs]
-        return sum(t) / len(t), sum(t) / (len(t) / len(layers))
-
-    dg_avg, dg_total = kernel_times(lambda l: vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.plan.p, l.plan.idxA,
-                                                                    l.plan.cntA, l.dX))
-    wg_avg, wg_total = kernel_times(lambda l: vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.plan.scaleW, l.plan.idxW,
-                                                                    l.plan.cntW, l.dW, l.ws))
+    # The same steps once more, launched eagerly with the library's kernel timer on: every GEMM
+    # launch is bracketed by HIP events stamped by its own dispatch (an event pair recorded from
+    # the host around a launch would also count the gap until the host submits the kernel).
+    reps = max(3, min(args.steps, 10))
+    vb.vcas_profile_begin()
+    for _ in range(reps):
+        step()
+    (dg_ms, dg_n), (wg_ms, wg_n) = vb.vcas_profile_end()
+    dg_avg, dg_total = dg_ms / max(dg_n, 1), dg_ms / reps
+    wg_avg, wg_total = wg_ms / max(wg_n, 1), wg_ms / reps
     if dg_total >= wg_total:
         name, avg_ms, flops = "dgrad_bf16_kernel", dg_avg, kept_rows / len(layers)
     else:
@@ -200,7 +197,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "launch": "eager" if args.eager else "hip_graph",
+        "launch": ("eager" if args.eager else "hip_graph") + (", one stream" if args.one_stream else ", dW half on a side stream"),
         "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,

@@ -171,11 +171,21 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
  * token_sampling = 0 SampleW is skipped (Alg. 1's "SampleA only" backward):
  * q = maskW = the data mask repeated over tokens.  dX may be null (skip the
  * activation gradient), dW may be null.
+ *
+ * side_stream (a second hipStream_t, or null): the weight-gradient half of the
+ * path (row norms of X, SampleW, dW) depends only on SampleA's outcome, not on
+ * dX, so with a side stream it is enqueued there, ordered after SampleA by an
+ * event, while dX proceeds on `stream`.  The call does NOT join the two: xsq,
+ * score, q, maskW, idxW, cntW, scaleW and dW are complete once side_stream has
+ * drained (the caller waits on it, or makes `stream` wait for it with an
+ * event).  Consecutive calls may share one side stream; their weight-gradient
+ * halves then run in call order behind each other.  Both streams must have the
+ * default priority.  With side_stream null everything is on `stream`.
  */
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W,
                                  double rho, double nu, const vcas_rng *rng, int32_t token_sampling,
                                  const vcas_plan *plan, void *dX, float *dW, void *workspace,
-                                 void *stream);
+                                 void *stream, void *side_stream);
 
 /*
  * Variance probe for the adaptive keep ratios (Sec. 4.1 variance, Eq. 3, and
@@ -191,6 +201,18 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
 vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho,
                                 double nu, const vcas_rng *base, int32_t M, const vcas_plan *plan,
                                 double *out, void *workspace, void *stream);
+
+/*
+ * Profiling aid, not part of the method: between vcas_profile_begin and
+ * vcas_profile_end every dgrad / wgrad GEMM launch (Eq. 1 upper line resp.
+ * Sec. 4.2's grad_W) is bracketed by HIP events stamped by the kernel's own
+ * dispatch.  vcas_profile_end waits for them and returns, in HOST arrays of two
+ * entries ([0] dgrad, [1] wgrad), the summed kernel durations in milliseconds
+ * and the number of launches.  Not for use under graph capture; creates and
+ * destroys HIP events (the only calls of the library that do).
+ */
+vcas_status vcas_profile_begin(void);
+vcas_status vcas_profile_end(double *total_ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_variance_probe",
+    "vcas_linear_backward", "vcas_variance_probe", "vcas_profile_begin", "vcas_profile_end",
 ]
 
 
@@ -175,11 +175,13 @@ def vcas_sampled_wgrad(shape: Shape, G, X, row_scale, idxW, cntW, dW, workspace)
 
 
 def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan,
-                         dX, dW, workspace):
+                         dX, dW, workspace, side_stream=None):
+    """side_stream: a torch.cuda.Stream for the weight-gradient half (not joined by the call), or None."""
     ptrs = plan.ptrs()
+    side = C.c_void_p(side_stream.cuda_stream if side_stream is not None else 0)
     _check(lib().vcas_linear_backward(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.c_double(nu),
                                       C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
-                                      _ptr(dW), _ptr(workspace), _stream()), "vcas_linear_backward")
+                                      _ptr(dW), _ptr(workspace), _stream(), side), "vcas_linear_backward")
 
 
 def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M: int, plan: Plan, out, workspace):
@@ -187,3 +189,15 @@ def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M:
     _check(lib().vcas_variance_probe(C.byref(shape), _ptr(G), _ptr(X), C.c_double(rho), C.c_double(nu),
                                      C.byref(base), C.c_int32(M), C.byref(ptrs), _ptr(out), _ptr(workspace),
                                      _stream()), "vcas_variance_probe")
+
+
+def vcas_profile_begin():
+    _check(lib().vcas_profile_begin(), "vcas_profile_begin")
+
+
+def vcas_profile_end():
+    """Returns ((dgrad_ms, dgrad_launches), (wgrad_ms, wgrad_launches)); synchronises."""
+    ms = (C.c_double * 2)()
+    n = (C.c_int64 * 2)()
+    _check(lib().vcas_profile_end(ms, n), "vcas_profile_end")
+    return (ms[0], n[0]), (ms[1], n[1])

@@ -6,6 +6,12 @@
 
 namespace vcas {
 
+KernelTimer &kernel_timer()
+{
+    static KernelTimer t;
+    return t;
+}
+
 // norms.hip
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
                       hipStream_t st);
@@ -153,20 +159,35 @@ static bool ratio_ok(double r) { return r > 0.0 && r <= 1.0; }
         if (st__ != VCAS_OK) return st__;   \
     } while (0)
 
+// One event, created on first use and kept: orders the side stream after SampleA.
+static hipEvent_t fork_event()
+{
+    static hipEvent_t ev = nullptr;
+    if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ev = nullptr;
+    return ev;
+}
+
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                                         double nu, const vcas_rng &rng, int token_sampling, const vcas_plan &pl,
-                                        void *dX, float *dW, void *workspace, hipStream_t st)
+                                        void *dX, float *dW, void *workspace, hipStream_t st, hipStream_t side)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *u = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + workspace_layout(&s).uniforms);
     VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+    hipStream_t ws = st;   // stream of the weight-gradient half
+    if (side && side != st) {
+        hipEvent_t ev = fork_event();
+        if (!ev || hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(side, ev, 0) != hipSuccess)
+            return VCAS_EHIP;
+        ws = side;
+    }
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
     VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, token_sampling ? u : nullptr,
-                                     st));
+                                     ws));
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu, token_sampling, pl.score,
-                       pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
-    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+                       pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
+    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, ws));
     return VCAS_OK;
 }
 
@@ -277,7 +298,7 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
 
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
                                  double nu, const vcas_rng *rng, int32_t token_sampling, const vcas_plan *plan,
-                                 void *dX, float *dW, void *workspace, void *stream)
+                                 void *dX, float *dW, void *workspace, void *stream, void *side_stream)
 {
     VCAS_TRY(check_shape(shape));
     if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
@@ -288,7 +309,7 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
         (workspace && !aligned16(workspace)))
         return VCAS_EINVAL;
     return linear_backward_impl(*shape, G, X, W, rho, nu, *rng, token_sampling, *plan, dX, dW, workspace,
-                                as_stream(stream));
+                                as_stream(stream), as_stream(side_stream));
 }
 
 vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,
@@ -314,15 +335,15 @@ vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const vo
     hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t *>(out), (size_t)8);
     if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     vcas_rng rng = *base;
-    VCAS_TRY(linear_backward_impl(s, G, X, nullptr, 1.0, 1.0, rng, 1, *plan, nullptr, exact, workspace, st));
+    VCAS_TRY(linear_backward_impl(s, G, X, nullptr, 1.0, 1.0, rng, 1, *plan, nullptr, exact, workspace, st, nullptr));
     for (int j = 0; j < M; ++j) {
         rng.draw = base->draw + (uint32_t)j;
         // SampleA only
-        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 0, *plan, nullptr, draw, workspace, st));
+        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 0, *plan, nullptr, draw, workspace, st, nullptr));
         hipLaunchKernelGGL(sq_diff_partial_kernel, dim3(blocks), dim3(256), 0, st, draw, exact, nW, partial);
         hipLaunchKernelGGL(sq_diff_final_kernel, dim3(1), dim3(64), 0, st, partial, blocks, wgt, out + 2);
         // SampleA and SampleW
-        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 1, *plan, nullptr, draw, workspace, st));
+        VCAS_TRY(linear_backward_impl(s, G, X, nullptr, rho, nu, rng, 1, *plan, nullptr, draw, workspace, st, nullptr));
         hipLaunchKernelGGL(sq_diff_partial_kernel, dim3(blocks), dim3(256), 0, st, draw, exact, nW, partial);
         hipLaunchKernelGGL(sq_diff_final_kernel, dim3(1), dim3(64), 0, st, partial, blocks, wgt, out + 3);
         if (j == 0)
@@ -332,6 +353,45 @@ vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const vo
         if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     }
     return VCAS_OK;
+}
+
+vcas_status vcas_profile_begin(void)
+{
+    KernelTimer &t = kernel_timer();
+    for (auto &v : t.pairs) {
+        for (auto &pr : v) {
+            (void)hipEventDestroy(pr.first);
+            (void)hipEventDestroy(pr.second);
+        }
+        v.clear();
+    }
+    t.on = true;
+    return VCAS_OK;
+}
+
+vcas_status vcas_profile_end(double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) return VCAS_ENULL;
+    KernelTimer &t = kernel_timer();
+    t.on = false;
+    vcas_status status = VCAS_OK;
+    for (int w = 0; w < 2; ++w) {
+        total_ms[w] = 0.0;
+        launches[w] = 0;
+        for (auto &pr : t.pairs[w]) {
+            float ms = 0.0f;
+            if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+                total_ms[w] += ms;
+                ++launches[w];
+            } else {
+                status = VCAS_EHIP;
+            }
+            (void)hipEventDestroy(pr.first);
+            (void)hipEventDestroy(pr.second);
+        }
+        t.pairs[w].clear();
+    }
+    return status;
 }
 
 }  // extern "C"

@@ -2,7 +2,11 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
+
+#include <utility>
+#include <vector>
 
 #include "vcas.h"
 
@@ -61,6 +65,34 @@ inline WorkspaceLayout workspace_layout(const vcas_shape *s)
     w.uniforms = w.probe_acc + 256;
     w.total = w.uniforms + (((size_t)s->N * s->T * sizeof(float) + 255) & ~(size_t)255);
     return w;
+}
+
+// ---- optional kernel timer --------------------------------------------------
+// When switched on (vcas_profile_begin), every GEMM launch is bracketed by HIP
+// events that take their timestamps from the kernel's own dispatch, so the
+// durations are the kernels' and not the host's.  0 = dgrad GEMM, 1 = wgrad GEMM.
+
+struct KernelTimer {
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs[2];
+};
+KernelTimer &kernel_timer();
+
+template <typename Kern, typename... Args>
+inline void launch_timed(int which, Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args)
+{
+    KernelTimer &t = kernel_timer();
+    if (!t.on) {
+        hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+        return;
+    }
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+        return;
+    }
+    hipExtLaunchKernelGGL(kern, grid, block, lds, st, a, b, 0, args...);
+    t.pairs[which].push_back({a, b});
 }
 
 // ---- device helpers ---------------------------------------------------------

@@ -630,8 +630,8 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
         if (!allow_lds(kern, lds)) return VCAS_EHIP;
         allowed = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
-                       static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
+    launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
+                 static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
                        s.K_out, tiles_n, dbg);
     return launch_status();
 }
@@ -672,8 +672,8 @@ vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const 
         allowed = true;
     }
     const int grid = (tiles * splits + 7) / 8 * 8;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
-                       static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out,
+    launch_timed(1, kern, dim3(grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
+                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out,
                        tiles_n, tiles, splits, MIN_STEPS);
     if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);

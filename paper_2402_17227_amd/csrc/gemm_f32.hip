@@ -268,7 +268,7 @@ vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const f
     const int tiles_n = (s.K_in + 63) / 64;
     const int64_t grid = tiles_n * ((R + 63) / 64 + 1) + 8;
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
-    hipLaunchKernelGGL(dgrad_f32_kernel, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const float *>(G),
+    launch_timed(0, dgrad_f32_kernel, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const float *>(G),
                        static_cast<const float *>(W), p, idxA, cntA, static_cast<float *>(dX), s.N, s.T, s.K_in,
                        s.K_out, tiles_n);
     return launch_status();
@@ -283,7 +283,7 @@ vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const f
     const int tiles = ((s.K_out + 63) / 64) * tiles_n;
     if (splits > 8) splits = 8;
     const int grid = (tiles * splits + 7) / 8 * 8;
-    hipLaunchKernelGGL(wgrad_f32_kernel, dim3(grid), dim3(256), 0, st, static_cast<const float *>(G),
+    launch_timed(1, wgrad_f32_kernel, dim3(grid), dim3(256), 0, st, static_cast<const float *>(G),
                        static_cast<const float *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
                        tiles, splits, MIN_STEPS);
     if (hipGetLastError() != hipSuccess) return VCAS_EHIP;

@@ -60,3 +60,64 @@ def test_graph_replays_match_eager_launches():
         assert np.array_equal(dW.cpu().numpy(), ref_dW), d
         # eager work between replays
         _ = (torch.randn(256, 256, device="cuda") @ torch.randn(256, 256, device="cuda")).sum().item()
+
+
+def test_side_stream_gives_the_same_bits_eager_and_captured():
+    from paper_2402_17227_amd import binding as vb
+    from tests.gpu_util import to_device, plan_to_numpy
+    specs = [workloads.LayerSpec(f"side{k}", workloads.BF16, 10, 60, kin, kout, 0.6, 0.5, layer=k, seed=3, gen_seed=21,
+                                 token_sigma=0.5) for k, (kin, kout) in enumerate([(264, 200), (128, 256), (200, 136)])]
+    layers = []
+    for spec in specs:
+        G, X, W = workloads.make_layer(spec)
+        shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+        layers.append(dict(spec=spec, shape=shape, g=to_device(G, spec.dtype), x=to_device(X, spec.dtype),
+                           w=to_device(W, spec.dtype), plan=vb.Plan.allocate(spec.N, spec.T),
+                           ws=vb.make_workspace(shape),
+                           dX=torch.empty((spec.R, spec.K_in), dtype=torch.bfloat16, device="cuda"),
+                           dW=torch.empty((spec.K_out, spec.K_in), device="cuda")))
+    side = torch.cuda.Stream()
+
+    def run(use_side):
+        main = torch.cuda.current_stream()
+        if use_side:
+            side.wait_stream(main)
+        for l in layers:
+            s = l["spec"]
+            vb.vcas_linear_backward(l["shape"], l["g"], l["x"], l["w"], s.rho, s.nu, vb.Rng(s.seed, s.layer, 4), True,
+                                    l["plan"], l["dX"], l["dW"], l["ws"], side if use_side else None)
+        if use_side:
+            main.wait_stream(side)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [(plan_to_numpy(l["plan"]), l["dX"].float().cpu().numpy().copy(), l["dW"].cpu().numpy().copy())
+                for l in layers]
+
+    def clear():
+        for l in layers:
+            l["dX"].fill_(float("nan"))
+            l["dW"].fill_(float("nan"))
+            l["plan"].cntW.fill_(-1)
+
+    run(False)
+    want = snapshot()
+
+    def check(got):
+        for (gp, gx, gw), (wp, wx, ww) in zip(got, want):
+            for k in ("gsq", "xsq", "p", "q", "maskA", "maskW", "idxA", "idxW", "scaleW", "score"):
+                assert np.array_equal(gp[k], wp[k]), k
+            assert gp["cntA"] == wp["cntA"] and gp["cntW"] == wp["cntW"]
+            assert np.array_equal(gx, wx) and np.array_equal(gw, ww)
+
+    clear()
+    run(True)
+    check(snapshot())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(True)
+    for _ in range(3):
+        clear()
+        torch.cuda.synchronize()
+        graph.replay()
+        check(snapshot())

@@ -56,12 +56,12 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
     assert lib.vcas_sampled_wgrad(C.byref(good), fake, fake, fake, fake, fake, fake, null, null) == 4
     plan = vb.PlanPtrs(*([0x1000] * 13))
     assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(1.5), C.c_double(0.5), C.byref(rng),
-                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null) == 1
+                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null, null) == 1
     assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(0.5), C.c_double(0.0), C.byref(rng),
-                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null) == 1
+                                    C.c_int32(1), C.byref(plan), fake, fake, fake, null, null) == 1
     bad_plan = vb.PlanPtrs(*([0x1000] * 12 + [0]))
     assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
-                                    C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null) == 2
+                                    C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null, null) == 2
     assert lib.vcas_variance_probe(C.byref(good), fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
                                    C.c_int32(0), C.byref(plan), fake, fake, null) == 1
     assert lib.vcas_workspace_init(null, C.c_size_t(1 << 20), null) == 4
