@@ -21,6 +21,8 @@
 // per-row 1/p goes into the epilogue.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace vcas {
@@ -92,7 +94,7 @@ struct DirectLoader {
 };
 
 // Operand stored [k][col] (col contiguous).  64 x COLS tile; unit u = 4 k-rows
-// x 8 columns: column chunk u % (COLS/8), k-quad u / (COLS/8).
+// x 8 columns.
 template <int COLS, int NT>
 struct TransLoader {
     static constexpr int CH = COLS / 8;
@@ -100,8 +102,14 @@ struct TransLoader {
     static_assert(16 * CH % NT == 0 && PER >= 1, "tile/thread mismatch");
     typedef uint4 Regs[PER][4];
 
-    __device__ __forceinline__ static int chunk(int j) { return (threadIdx.x + j * NT) % CH; }
-    __device__ __forceinline__ static int kquad(int j) { return (threadIdx.x + j * NT) / CH; }
+    // Neighbouring lanes take the two k-quads that share a 16-byte LDS slot, so that their 8-byte
+    // writes fill whole slots and 16 lanes cover 8 distinct slots (no bank conflicts).
+    __device__ __forceinline__ static int chunk(int j) { return ((threadIdx.x + j * NT) >> 1) % CH; }
+    __device__ __forceinline__ static int kquad(int j)
+    {
+        const int u = threadIdx.x + j * NT;
+        return ((u >> 1) / CH) * 2 + (u & 1);
+    }
 
     // voff(j, i) -> byte offset of the 8 columns of k-row kquad(j)*4+i (or kOutside)
     template <typename Off>
@@ -166,20 +174,51 @@ __device__ __forceinline__ void mma_tile(const unsigned char *tileA, const unsig
 {
     const int lane = threadIdx.x & 63;
     const int r = lane & 31, h = lane >> 5;
+    constexpr int KS = BK / 16;
+    // all fragment reads of the step are issued before the first MFMA, so only the first one's
+    // LDS latency is exposed
+    bf16x8 a[KS][TM], b[KS][TN];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 a[TM], b[TN];
+    for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            a[i] = *reinterpret_cast<const bf16x8 *>(tileA + lds_off(rowA0 + i * 32 + r, ks * 2 + h));
+            a[ks][i] = *reinterpret_cast<const bf16x8 *>(tileA + lds_off(rowA0 + i * 32 + r, ks * 2 + h));
 #pragma unroll
         for (int i = 0; i < TN; ++i)
-            b[i] = *reinterpret_cast<const bf16x8 *>(tileB + lds_off(rowB0 + i * 32 + r, ks * 2 + h));
+            b[ks][i] = *reinterpret_cast<const bf16x8 *>(tileB + lds_off(rowB0 + i * 32 + r, ks * 2 + h));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+}
+
+// The instruction mix of one pipeline phase, spelled out for the scheduler (it
+// would otherwise sink every LDS read next to its MFMA and run global loads,
+// matrix work and LDS staging one after the other): global loads first, the
+// fragment reads of two k-slices, then each MFMA followed by one instruction of
+// the staging work (transposing VALU op or LDS write), with the fragment reads
+// of the slice after next in each slice's shadow.  Counts that exceed what the
+// region holds are harmless.
+template <int TM, int TN, int VMEM, int VALU, int DSW, int ID>
+__device__ __forceinline__ void schedule_phase()
+{
+    constexpr int KS = BK / 16, RD = TM + TN, MM = TM * TN, TOTAL = KS * MM;
+    constexpr int VALU_PER = (VALU + TOTAL - 1) / TOTAL, DSW_PER = (DSW + TOTAL - 1) / TOTAL;
+    __builtin_amdgcn_sched_group_barrier(0x020, VMEM, ID);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, ID);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
+            if (VALU_PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, ID);
+            if (DSW_PER > 0) __builtin_amdgcn_sched_group_barrier(0x200, DSW_PER, ID);
+        }
+        if (ks + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, RD, ID);
     }
 }
 
@@ -217,32 +256,34 @@ __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
 //   load(set, s)   issue the global loads of step s into register set `set`
 //   stage(set, b)  write register set `set` (transposed / scaled) to LDS buffer b
 //   compute(b)     MFMA over LDS buffer b
-template <typename Load, typename Stage, typename Compute>
-__device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Compute compute)
+template <typename Load, typename Stage, typename Compute, typename Schedule>
+__device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Compute compute, Schedule schedule)
 {
     if (steps <= 0) return;
     load(0, 0);
     if (steps > 1) load(1, 1);
     stage(0, 0);
     __syncthreads();
-    // Steady state without conditions inside (so that the waits on the older register set
-    // stay partial waits): LDS buffer 0 holds step s, register set 1 holds step s+1.
+    // Steady state without conditions inside: LDS buffer 0 holds step s, register set 1 holds
+    // step s+1 (landed or about to).  One phase = issue the loads of step s+2 into the free
+    // set, run the MFMAs of step s and, interleaved with them, move step s+1 from its register
+    // set into the other LDS buffer.
     int s = 0;
     for (; s + 3 < steps; s += 2) {
-        // the scheduling fences keep the loads at the top of each phase: hoisting the MFMAs
-        // above them (to save registers) would take the prefetch distance away
         load(0, s + 2);
-        __builtin_amdgcn_sched_barrier(0);
         compute(0);
-        __builtin_amdgcn_sched_barrier(0);
         stage(1, 1);
+        schedule(std::integral_constant<int, 0>());
+        __builtin_amdgcn_sched_barrier(0);   // nothing moves across the phase boundary
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
         load(1, s + 3);
-        __builtin_amdgcn_sched_barrier(0);
         compute(1);
-        __builtin_amdgcn_sched_barrier(0);
         stage(0, 0);
+        schedule(std::integral_constant<int, 1>());
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
     }
     const int left = steps - s;   // 1, 2 or 3
     if (left == 3) load(0, s + 2);
@@ -269,7 +310,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   const int32_t *__restrict__ idxA,
                                                                   const int32_t *__restrict__ cntA,
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
-                                                                  int K_out, int tiles_n, int dbg)
+                                                                  int K_out, int tiles_n)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -362,7 +403,6 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     auto load = [&](int set, int s) {
-        if (dbg & 1) return;
         const uint32_t kb = (uint32_t)s * BK * 2u;                       // bytes along a G row
         const uint32_t wb = (uint32_t)s * BK * (uint32_t)K_in * 2u;      // bytes down the rows of W
         auto w_voff = [&](int j, int i) { return w_off[j][i]; };
@@ -375,7 +415,6 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
         }
     };
     auto stage = [&](int set, int buf) {
-        if (dbg & 2) return;
         if (set == 0) {
             LA::store(ra[0], tA(buf));
             LB::store(rb[0], tB(buf));
@@ -384,8 +423,11 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
             LB::store(rb[1], tB(buf));
         }
     };
-    auto compute_step = [&](int buf) { if (dbg & 4) return; mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
-    pipeline((K_out + BK - 1) / BK, load, stage, compute_step);
+    auto compute_step = [&](int buf) { mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
+    auto schedule = [&](auto id) {
+        schedule_phase<TM, TN, LA::PER + 4 * LB::PER, 16 * LB::PER, LA::PER + 8 * LB::PER, decltype(id)::value>();
+    };
+    pipeline((K_out + BK - 1) / BK, load, stage, compute_step, schedule);
 
     // Epilogue: scale by 1/p, round to bf16, pair neighbouring columns (lanes l, l^1)
     // so that every lane stores one 32-bit word: even lanes rows of even v, odd lanes odd v.
@@ -469,11 +511,6 @@ vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW,
     return launch_status();
 }
 
-struct TokenQuad {
-    int32_t tok[4];
-    float sc[4];
-};
-
 // grid: 1-D, splits * tiles workgroups (rounded up to a multiple of 8), split-
 // major, so that the workgroups one XCD gets (a contiguous run after the remap)
 // contract the same tokens and share those G and X rows in its L2.  Split s of
@@ -522,24 +559,32 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
     typename LA::Regs ra[2];
     typename LB::Regs rb[2];
     float scale_of_set[2][4];   // per-token scales of the step held in the register set of the same index
-    TokenQuad ahead;     // fetched one step before its data loads are issued
 
-    auto fetch_quad = [&](int step) {
-        TokenQuad t;
+    // Token indices and scales run two resp. one step ahead of the tile loads, and each small
+    // load is issued BEFORE the 16 tile loads of its phase: the memory counter is in-order, so
+    // waiting for an index then leaves the younger tile loads in flight.
+    const __amdgpu_buffer_rsrc_t rsrcI = make_rsrc(idxW, (uint32_t)(R * 4));
+    const __amdgpu_buffer_rsrc_t rsrcS = make_rsrc(row_scale, (uint32_t)(R * 4));
+    const int64_t k_end = min(cnt, (int64_t)s_end * BK);
+    struct Tokens {
+        int32_t tok[4];   // row of G / X, or -1
+    };
+    auto fetch_tokens = [&](int step) {
+        const int64_t k0 = (int64_t)(s_begin + step) * BK + kq * 4;
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcI, k0 < k_end ? (int)(k0 * 4) : (int)kOutside, 0, 0);
+        Tokens t;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t k = (int64_t)(s_begin + step) * BK + kq * 4 + i;
-            t.tok[i] = -1;
-            t.sc[i] = 0.0f;
-            if (s_begin + step < s_end && k < cnt) {
-                const int32_t r = idxW[k];
-                if (r >= 0 && r < R) {
-                    t.tok[i] = r;
-                    t.sc[i] = row_scale[r];
-                }
-            }
+            const int32_t r = (int32_t)v[i];
+            t.tok[i] = (k0 + i < k_end && r >= 0 && r < R) ? r : -1;
         }
         return t;
+    };
+    auto fetch_scales = [&](const Tokens &t, float (&sc)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            sc[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                  rsrcS, t.tok[i] >= 0 ? t.tok[i] * 4 : (int)kOutside, 0, 0));
     };
 
     const int wave = threadIdx.x >> 6;
@@ -552,11 +597,15 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    ahead = fetch_quad(0);
+    Tokens tok_cur = fetch_tokens(0), tok_next = fetch_tokens(1);
+    float sc_cur[4];
+    fetch_scales(tok_cur, sc_cur);
     auto load = [&](int set, int s) {
-        // `ahead` holds the quad of step s (steps are loaded in order); fetch the next one
-        const TokenQuad q = ahead;
-        ahead = fetch_quad(s + 1);
+        // steps are loaded in order: tok_cur / sc_cur belong to step s, tok_next to step s + 1
+        float sc_next[4];
+        fetch_scales(tok_next, sc_next);
+        const Tokens tok_after = fetch_tokens(s + 2);
+        const Tokens q = tok_cur;
         auto g_voff = [&](int, int i) {
             return (q.tok[i] >= 0 && cola < K_out) ? ((uint32_t)q.tok[i] * (uint32_t)K_out + cola) * 2u : kOutside;
         };
@@ -565,15 +614,19 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
         };
         if (set == 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) scale_of_set[0][i] = q.sc[i];
+            for (int i = 0; i < 4; ++i) scale_of_set[0][i] = sc_cur[i];
             LA::load(ra[0], rsrcG, g_voff, 0u);
             LB::load(rb[0], rsrcX, x_voff, 0u);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) scale_of_set[1][i] = q.sc[i];
+            for (int i = 0; i < 4; ++i) scale_of_set[1][i] = sc_cur[i];
             LA::load(ra[1], rsrcG, g_voff, 0u);
             LB::load(rb[1], rsrcX, x_voff, 0u);
         }
+        tok_cur = tok_next;
+        tok_next = tok_after;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sc_cur[i] = sc_next[i];
     };
     auto stage = [&](int set, int buf) {
         if (set == 0) {
@@ -585,7 +638,9 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
         }
     };
     auto compute_step = [&](int buf) { mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
-    pipeline(s_end - s_begin, load, stage, compute_step);
+    // staging VALU per thread: G unit 40 (unpack, scale, pack), X unit 16 (byte permutes), a few for the token fetch
+    auto schedule = [&](auto id) { schedule_phase<TM, TN, 8 + 5, 64, 16, decltype(id)::value>(); };
+    pipeline(s_end - s_begin, load, stage, compute_step, schedule);
 
     const int lane = threadIdx.x & 63;
     float *dst = active == 1 ? dW : partials + (int64_t)split * K_out * K_in;
@@ -623,7 +678,6 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     const int64_t grid = tiles_n * ((R + BM - 1) / BM + 1) + 8;
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
     const size_t lds = 2 * (BM + BN) * 128 + BM * 8;
-    static const int dbg = getenv("VCAS_DBG") ? atoi(getenv("VCAS_DBG")) : 0;
     auto kern = dgrad_bf16_kernel<BM, BN, WM, WN, OCC>;
     static bool allowed = false;   // once per instantiation
     if (!allowed) {
@@ -632,7 +686,7 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                       s.K_out, tiles_n, dbg);
+                       s.K_out, tiles_n);
     return launch_status();
 }
 
