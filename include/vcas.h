@@ -15,9 +15,11 @@
  *    bfloat16 bit patterns.  K_in and K_out must be multiples of 8 (one 16-byte
  *    vector of bf16; fp32 needs only a multiple of 4 but the same rule is kept),
  *    and tensor base addresses 16-byte aligned.
- *  - The caller owns every buffer.  The library allocates nothing; calls that
- *    need scratch take a `workspace` of at least vcas_workspace_bytes(shape)
- *    bytes that was passed once to vcas_workspace_init after allocation.
+ *  - The caller owns every buffer.  The library allocates no device memory;
+ *    calls that need scratch take a `workspace` of at least
+ *    vcas_workspace_bytes(shape) bytes, 16-byte aligned, contents don't matter.
+ *    bf16 tensors must be smaller than 2 GiB each and K_in, K_out <= 8184
+ *    (buffer-addressing limits of the GEMM kernels).
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *    default stream); calls return without synchronising.  Kept counts stay on
  *    the device.  Two calls that share a workspace must be ordered (same stream).
@@ -92,12 +94,6 @@ const char *vcas_status_string(vcas_status s);
  * bad shape). */
 size_t vcas_workspace_bytes(const vcas_shape *shape);
 
-/* Must be called once on a freshly allocated workspace (and again after a
- * failed launch) before it is used: clears the split-K arrival counters, which
- * the kernels afterwards leave at zero themselves.  `bytes` is the buffer's
- * size and must be at least vcas_workspace_bytes(shape). */
-vcas_status vcas_workspace_init(void *workspace, size_t bytes, void *stream);
-
 /*
  * Squared row norms, the ||.||_2^2 factors of Eq. 3 and the ||G_i||_F of
  * Sec. 4.1.  G [R,K_out] and/or X [R,K_in] (either may be null, not both).
@@ -158,7 +154,8 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
  * Sampled weight gradient (Sec. 4.2, grad_W = Gtilde^T X):
  *   dW[o,k] = sum over the *cntW rows t = idxW[.] of row_scale[t] G[t,o] X[t,k].
  * dW [K_out,K_in] fp32 is overwritten.  Needs the workspace (split-K partial
- * tiles, combined in a fixed order, so the result is deterministic).
+ * tiles, added up in a fixed order by a second small launch, so the result is
+ * deterministic).
  */
 vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X,
                                const float *row_scale, const int32_t *idxW, const int32_t *cntW,

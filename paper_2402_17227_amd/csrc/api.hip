@@ -1,7 +1,5 @@
 // C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
 // launches on the caller's stream.  See include/vcas.h for the contract.
-#include <stdlib.h>
-
 #include "common.hpp"
 
 namespace vcas {
@@ -138,9 +136,7 @@ static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void
     const WorkspaceLayout w = workspace_layout(&s);
     unsigned char *base = static_cast<unsigned char *>(workspace);
     float *partials = reinterpret_cast<float *>(base + w.partials);
-    int splits = wgrad_split(&s);
-    static const char *force = getenv("VCAS_WGRAD_SPLIT");
-    if (force && atoi(force) < splits) splits = atoi(force);
+    const int splits = wgrad_split(&s);
     return s.dtype == VCAS_BF16 ? wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, splits, st)
                                 : wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, splits, st);
 }
@@ -216,15 +212,6 @@ size_t vcas_workspace_bytes(const vcas_shape *shape)
     return workspace_layout(shape).total;
 }
 
-vcas_status vcas_workspace_init(void *workspace, size_t bytes, void *stream)
-{
-    if (!workspace) return VCAS_EWORKSPACE;
-    if (bytes < kCounterBytes) return VCAS_EINVAL;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((kCounterInts + 255) / 256)), dim3(256), 0, as_stream(stream),
-                       static_cast<uint32_t *>(workspace), kCounterInts);
-    return launch_status();
-}
-
 vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X, const uint8_t *sample_mask,
                            float *gsq, float *xsq, float *gnorm, void *stream)
 {
@@ -281,6 +268,7 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
                                const int32_t *idxA, const int32_t *cntA, void *dX, void *stream)
 {
     VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
     if (!G || !W || !p || !idxA || !cntA || !dX) return VCAS_ENULL;
     if (!aligned16(G) || !aligned16(W) || !aligned16(dX)) return VCAS_EINVAL;
     return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, as_stream(stream));
@@ -290,6 +278,7 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
                                const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace, void *stream)
 {
     VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
     if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
     if (!aligned16(G) || !aligned16(X) || !aligned16(dW) || !aligned16(workspace)) return VCAS_EINVAL;
@@ -301,6 +290,7 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
                                  void *dX, float *dW, void *workspace, void *stream, void *side_stream)
 {
     VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
     if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
     if (dX && !W) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
@@ -317,6 +307,7 @@ vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const vo
                                 void *stream)
 {
     VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
     if (!G || !X || !base || !out || !plan_complete(plan)) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
     if (!ratio_ok(rho) || !ratio_ok(nu) || M <= 0) return VCAS_EINVAL;

@@ -35,20 +35,26 @@ inline vcas_status check_shape(const vcas_shape *s)
     return VCAS_OK;
 }
 
+// The bf16 GEMM kernels address G, X and W through 32-bit buffer offsets below 2 GiB.
+inline vcas_status check_gemm_limits(const vcas_shape *s)
+{
+    if (s->dtype == VCAS_BF16) {
+        const int64_t R = (int64_t)s->N * s->T;
+        const int64_t kmax = s->K_in > s->K_out ? s->K_in : s->K_out;
+        if (kmax > 8184 || R * kmax * 2 >= (int64_t)1 << 31) return VCAS_EINVAL;
+    }
+    return VCAS_OK;
+}
+
 inline int elem_bytes(int dtype) { return dtype == VCAS_BF16 ? 2 : 4; }
 
 // ---- workspace layout -------------------------------------------------------
-// [0, kCounterBytes)          split-K arrival counters (int32), zero between calls
-// [kCounterBytes, +partials)  split-K partial tiles of the weight gradient (fp32)
+// splits * K_out * K_in fp32: split-K partial tiles of the weight gradient,
 // then two K_out*K_in fp32 matrices and 32 doubles for the variance probe,
 // then R floats: the SampleW uniforms of vcas_linear_backward
 
-constexpr size_t kCounterInts = 16384;
-constexpr size_t kCounterBytes = kCounterInts * sizeof(int32_t);
-constexpr int kMaxSplit = 16;
-
 struct WorkspaceLayout {
-    size_t counters, partials, probe_exact, probe_draw, probe_acc, uniforms, total;
+    size_t partials, probe_exact, probe_draw, probe_acc, uniforms, total;
 };
 
 int wgrad_split(const vcas_shape *s);   // host: number of split-K slices for this shape
@@ -57,8 +63,7 @@ inline WorkspaceLayout workspace_layout(const vcas_shape *s)
 {
     WorkspaceLayout w;
     size_t mat = (size_t)s->K_out * s->K_in * sizeof(float);
-    w.counters = 0;
-    w.partials = kCounterBytes;
+    w.partials = 0;
     w.probe_exact = w.partials + mat * (size_t)wgrad_split(s);
     w.probe_draw = w.probe_exact + mat;
     w.probe_acc = w.probe_draw + mat;

@@ -53,6 +53,8 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
     assert lib.vcas_keep_probs(fake, C.c_int32(5), C.c_double(float("nan")), fake, null) == 1
     assert lib.vcas_sample_compact(fake, C.c_int32(4), None, C.c_uint32(0), fake, fake, fake, null) == 2
     assert lib.vcas_sampled_dgrad(C.byref(good), fake, fake, fake, fake, null, fake, null) == 2
+    wide = vb.shape_of(8, 128, 768, 8192, vb.VCAS_BF16)          # K above the bf16 GEMM kernels' limit
+    assert lib.vcas_sampled_dgrad(C.byref(wide), fake, fake, fake, fake, fake, fake, null) == 1
     assert lib.vcas_sampled_wgrad(C.byref(good), fake, fake, fake, fake, fake, fake, null, null) == 4
     plan = vb.PlanPtrs(*([0x1000] * 13))
     assert lib.vcas_linear_backward(C.byref(good), fake, fake, fake, C.c_double(1.5), C.c_double(0.5), C.byref(rng),
@@ -64,7 +66,6 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
                                     C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null, null) == 2
     assert lib.vcas_variance_probe(C.byref(good), fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
                                    C.c_int32(0), C.byref(plan), fake, fake, null) == 1
-    assert lib.vcas_workspace_init(null, C.c_size_t(1 << 20), null) == 4
 
 
 def test_binding_refuses_to_run_without_the_library(vb, monkeypatch, tmp_path):
