@@ -29,9 +29,11 @@ vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q
 vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
                       uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st);
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
-vcas_status sampler_w(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, const float *u, int N,
-                      int T, double budget, int token_sampling, float *score, float *q, uint8_t *maskW, float *scaleW,
-                      int32_t *idxW, int32_t *cntW, hipStream_t st);
+vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
+                      const float *u, int N, int T, double budget, int token_sampling, float *score, float *q,
+                      uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st);
+vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
+                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st);
 // gemm_bf16.hip / gemm_f32.hip
 int wgrad_tiles_bf16(int K_out, int K_in);
 int wgrad_tiles_f32(int K_out, int K_in);
@@ -169,7 +171,15 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *u = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + workspace_layout(&s).uniforms);
-    VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
+    // Small layers: the row norms of X do not wait for SampleA; they are taken for every row in
+    // the same launch as those of G (one launch and one dependency fewer; rows of dropped samples
+    // are zeroed afterwards).  Large layers: a second launch that skips dropped samples' rows.
+    const bool together = (int64_t)R * s.K_in * elem_bytes(s.dtype) <= ((int64_t)16 << 20);
+    float *uw = token_sampling ? u : nullptr;
+    if (together)
+        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
+    else
+        VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
     hipStream_t ws = st;   // stream of the weight-gradient half
     if (side && side != st) {
@@ -179,10 +189,9 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
         ws = side;
     }
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
-    VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, token_sampling ? u : nullptr,
-                                     ws));
-    VCAS_TRY(sampler_w(pl.gsq, pl.xsq, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu, token_sampling, pl.score,
-                       pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
+    if (!together) VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, uw, ws));
+    VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
+                       token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
     if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, ws));
     return VCAS_OK;
 }

@@ -79,6 +79,45 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict_
     }
 }
 
+// Row norms of two matrices with the same number of rows in one launch (G and X
+// of a layer when both are small enough that a second launch would cost more
+// than reading the rows of X that SampleA is about to drop): wavefronts
+// [0, R) take the rows of A, [R, 2R) the rows of B.
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__restrict__ A, int groups_a,
+                                                             float *__restrict__ out_a, const uint4 *__restrict__ B,
+                                                             int groups_b, float *__restrict__ out_b, int64_t R,
+                                                             UniformJob job)
+{
+    if (job.uniforms) {
+        const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
+        for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < R; r += (int64_t)gridDim.x * 256)
+            job.uniforms[r] = philox_uniform(job.seed, job.layer, job.stream_id, draw, (uint32_t)r);
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t w = wave; w < 2 * R; w += nwaves) {
+        const bool second = w >= R;
+        const int64_t row = second ? w - R : w;
+        const int groups = second ? groups_b : groups_a;
+        const uint4 *p = (second ? B : A) + row * groups;
+        float acc = 0.0f;
+        for (int base = 0; base < groups; base += 64 * CH) {
+            uint4 v[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                int g = base + lane + 64 * j;
+                v[j] = g < groups ? p[g] : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int j = 0; j < CH; ++j) acc = fold16<BF16>(v[j], acc);
+        }
+        acc = wave_exchange_sum(acc);
+        if (lane == 0) (second ? out_b : out_a)[row] = acc;
+    }
+}
+
 // ||G_i||_F: value t of a sample belongs to lane t mod 64, plain fp32 adds in
 // ascending t, exchange steps, correctly rounded sqrt.  One wavefront per sample.
 __global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restrict__ gsq, int N, int T,
@@ -130,6 +169,35 @@ vcas_status row_sumsq_with_uniforms(const void *A, int dtype, int64_t R, int K, 
     const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
     return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, job, st)
                               : launch_row_sumsq<false>(A, R, K, T, keep, out, job, st);
+}
+
+template <bool BF16>
+static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void *B, int K_b, float *out_b, int64_t R,
+                               const UniformJob &job, hipStream_t st)
+{
+    const int ga = K_a / (BF16 ? 8 : 4), gb = K_b / (BF16 ? 8 : 4);
+    const int need = ((ga > gb ? ga : gb) + 63) / 64;
+    int64_t blocks64 = (2 * R + 3) / 4;
+    const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
+    const uint4 *a = static_cast<const uint4 *>(A), *b = static_cast<const uint4 *>(B);
+#define VCAS_LAUNCH_CH(C)                                                                                         \
+    hipLaunchKernelGGL((row_sumsq_pair_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, ga, out_a, b, gb, out_b, \
+                       R, job)
+    if (need <= 2) VCAS_LAUNCH_CH(2);
+    else if (need <= 4) VCAS_LAUNCH_CH(4);
+    else VCAS_LAUNCH_CH(8);
+#undef VCAS_LAUNCH_CH
+    return launch_status();
+}
+
+// gsq of every row of G, xsq of EVERY row of X (the caller zeroes the rows of dropped samples
+// later) and the uniforms of sampler `stream_id`, one launch
+vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
+                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st)
+{
+    const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
+    return dtype == VCAS_BF16 ? launch_pair<true>(G, K_out, gsq, X, K_in, xsq, R, job, st)
+                              : launch_pair<false>(G, K_out, gsq, X, K_in, xsq, R, job, st);
 }
 
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st)

@@ -38,6 +38,29 @@ __device__ __forceinline__ int block_sum_1024(int v, int *buf)
     return t;
 }
 
+// Both sums of a keep-probability round behind one barrier.
+__device__ __forceinline__ void block_sum_pair_1024(double v, int c, double *bufd, int *bufi, double &sum_v, int &sum_c)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_exchange_sum(v);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, kWave);
+    if (lane == 0) {
+        bufd[wave] = v;
+        bufi[wave] = c;
+    }
+    __syncthreads();
+    double t = bufd[lane & 15];
+    int u = bufi[lane & 15];
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) {
+        t = t + __shfl_xor(t, d, kWave);
+        u += __shfl_xor(u, d, kWave);
+    }
+    sum_v = t;
+    sum_c = u;
+}
+
 // prob_i = min(1, c * score_i), sum prob = min(budget, #positive scores).
 // c is found by rounds: every not-yet-fixed entry that the current c pushes to
 // >= 1 is fixed at one, then c is recomputed from what is left, until a round
@@ -60,8 +83,9 @@ __device__ void keep_probs_block(const float *__restrict__ score, int n, double 
         }
         prob[i] = 0.0f;
     }
-    double S = block_sum_1024(part, sd[0]);
-    const int nonzero = block_sum_1024(cnt, si[0]);
+    double S;
+    int nonzero;
+    block_sum_pair_1024(part, cnt, sd[0], si[0], S, nonzero);
 
     if (budget >= (double)nonzero) {
         for (int i = tid; i < n; i += 1024) prob[i] = score[i] > 0.0f ? 1.0f : 0.0f;
@@ -91,8 +115,9 @@ __device__ void keep_probs_block(const float *__restrict__ score, int n, double 
                 }
             }
         }
-        const double S_next = block_sum_1024(part, sd[flip]);
-        const int newly = block_sum_1024(cnt, si[flip]);
+        double S_next;
+        int newly;
+        block_sum_pair_1024(part, cnt, sd[flip], si[flip], S_next, newly);
         flip ^= 1;
         if (newly == 0) break;
         ncap += newly;
@@ -228,8 +253,9 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
             part += (double)a[j];
             ++cnt;
         }
-    double S = block_sum_1024(part, sd[0]);
-    const int nonzero = block_sum_1024(cnt, si[0]);
+    double S;
+    int nonzero;
+    block_sum_pair_1024(part, cnt, sd[0], si[0], S, nonzero);
     if (budget >= (double)nonzero) {
 #pragma unroll
         for (int j = 0; j < E; ++j) prob[j] = a[j] > 0.0f ? 1.0f : 0.0f;
@@ -258,8 +284,9 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
                     part += (double)a[j];
                 }
             }
-        const double S_next = block_sum_1024(part, sd[flip]);
-        const int newly = block_sum_1024(cnt, si[flip]);
+        double S_next;
+        int newly;
+        block_sum_pair_1024(part, cnt, sd[flip], si[flip], S_next, newly);
         flip ^= 1;
         if (newly == 0) break;
         ncap += newly;
@@ -315,7 +342,7 @@ __global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__res
 // SampleW for R <= 1024*E.
 template <int E>
 __global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__restrict__ gsq,
-                                                              const float *__restrict__ xsq,
+                                                              float *__restrict__ xsq, int zero_dropped_xsq,
                                                               const float *__restrict__ p,
                                                               const uint8_t *__restrict__ maskA,
                                                               const float *__restrict__ u, int N, int T, double budget,
@@ -346,6 +373,8 @@ __global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__res
                 const float inv = 1.0f / pinv_src[j];
                 const float s1 = inv * __builtin_sqrtf(g);
                 a[j] = s1 * __builtin_sqrtf(x);
+            } else if (zero_dropped_xsq) {
+                xsq[t] = 0.0f;
             }
             score[t] = a[j];
         }
@@ -411,8 +440,8 @@ __global__ __launch_bounds__(256) void uniforms_kernel(int64_t R, uint64_t seed,
 // SampleW: leverage scores, q, Bernoulli mask over tokens (uniforms given),
 // per-token scale, kept list.  With token_sampling == 0 every token of a kept
 // sample is kept with q = 1.
-__global__ __launch_bounds__(1024) void sampler_w_kernel(const float *__restrict__ gsq, const float *__restrict__ xsq,
-                                                         const float *__restrict__ p,
+__global__ __launch_bounds__(1024) void sampler_w_kernel(const float *__restrict__ gsq, float *__restrict__ xsq,
+                                                         int zero_dropped_xsq, const float *__restrict__ p,
                                                          const uint8_t *__restrict__ maskA,
                                                          const float *__restrict__ u, int N, int T, double budget,
                                                          int token_sampling, float *__restrict__ score,
@@ -429,6 +458,8 @@ __global__ __launch_bounds__(1024) void sampler_w_kernel(const float *__restrict
             const float inv = 1.0f / p[i];
             const float a = inv * __builtin_sqrtf(gsq[t]);
             s = a * __builtin_sqrtf(xsq[t]);
+        } else if (zero_dropped_xsq) {
+            xsq[t] = 0.0f;
         }
         score[t] = s;
     }
@@ -524,12 +555,13 @@ vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *
     return launch_status();
 }
 
-vcas_status sampler_w(const float *gsq, const float *xsq, const float *p, const uint8_t *maskA, const float *u, int N,
-                      int T, double budget, int token_sampling, float *score, float *q, uint8_t *maskW, float *scaleW,
-                      int32_t *idxW, int32_t *cntW, hipStream_t st)
+vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
+                      const float *u, int N, int T, double budget, int token_sampling, float *score, float *q,
+                      uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st)
 {
     const int64_t R = (int64_t)N * T;
-#define VCAS_SAMPLER_W_ARGS gsq, xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW, scaleW, idxW, cntW
+#define VCAS_SAMPLER_W_ARGS \
+    gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW, scaleW, idxW, cntW
     if (R <= 4096)
         hipLaunchKernelGGL(sampler_w_fast_kernel<4>, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
     else if (R <= 16384)
