@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
+    ap.add_argument("--side-streams", type=int, default=1, help="streams the weight-gradient halves rotate over")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,20 +99,22 @@ def main():
     # Two streams: norms of G, SampleA and dX of every layer run in order on the main stream (the
     # order a real backward pass imposes), each layer's weight-gradient half (norms of X, SampleW,
     # dW) follows its SampleA on the side stream; the step ends when both have drained.
-    side = None if args.one_stream else torch.cuda.Stream()
+    # The weight gradients of different layers do not depend on each other, so their halves rotate
+    # over a few side streams and may overlap one another as well.
+    sides = [] if args.one_stream else [torch.cuda.Stream() for _ in range(args.side_streams)]
 
     def step():
         main = torch.cuda.current_stream()
         draw_counter.add_(1)
-        if side is not None:
-            side.wait_stream(main)
-        for l in layers:
+        for sd in sides:
+            sd.wait_stream(main)
+        for k, l in enumerate(layers):
             s = l.spec
             vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, s.rho, s.nu,
                                     vb.Rng(s.seed, s.layer, 0, draw_counter.data_ptr()), True, l.plan,
-                                    l.dX, l.dW, l.ws, side)
-        if side is not None:
-            main.wait_stream(side)
+                                    l.dX, l.dW, l.ws, sides[k % len(sides)] if sides else None)
+        for sd in sides:
+            main.wait_stream(sd)
 
     # ---- timed region: K steps of the whole path --------------------------------
     step()                                       # eager once: one-time kernel attribute set-up
@@ -197,7 +200,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "launch": ("eager" if args.eager else "hip_graph") + (", one stream" if args.one_stream else ", dW half on a side stream"),
+        "launch": ("eager" if args.eager else "hip_graph") + (", one stream" if args.one_stream else f", dW halves on {args.side_streams} side streams"),
         "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,

@@ -127,8 +127,9 @@ float orc_uniform(uint64_t seed, uint32_t layer, uint32_t stream, uint32_t draw,
 /*
  * fp32 sum in the written-down "64-lane" order: value j of the sequence goes
  * to accumulator (j / group) mod 64, accumulators fold their values in
- * ascending j, then six pairwise exchange steps (distance 32,16,...,1) add
- * accumulator l and l^distance.  `sq` selects acc = fma(v,v,acc) or acc += v.
+ * ascending j, then six pairwise exchange steps (distance 1,2,4,...,32) add
+ * accumulator l and l^distance, i.e. neighbours first.  `sq` selects
+ * acc = fma(v,v,acc) or acc += v.
  */
 static float lane_sum(const void *base, int dtype, size_t first, int count, int group, int sq)
 {
@@ -140,7 +141,7 @@ static float lane_sum(const void *base, int dtype, size_t first, int count, int 
         float v = elem(base, dtype, first + (size_t)j);
         acc[l] = sq ? fmaf(v, v, acc[l]) : acc[l] + v;
     }
-    for (int dist = 32; dist >= 1; dist >>= 1) {
+    for (int dist = 1; dist <= 32; dist <<= 1) {
         float nxt[64];
         for (int l = 0; l < 64; ++l)
             nxt[l] = acc[l] + acc[l ^ dist];
@@ -190,9 +191,17 @@ void orc_sample_norms(const float *gsq, int N, int T, float *gnorm)
 /* --------------------------- keep probabilities (Sec. 4.1, Sec. 4.2) */
 
 /* fp64 sum in the written-down "1024-slot" order: slot = i mod 1024, ascending
- * inside a slot; each run of 64 consecutive slots is halved pairwise
- * (j, j+32), (j, j+16), ... (j, j+1); the 16 run sums are then halved pairwise
- * (j, j+8), ... (j, j+1). */
+ * inside a slot; each run of 64 consecutive slots is reduced by adding
+ * neighbours pairwise, (0,1), (2,3), ..., then the pair sums pairwise, and so
+ * on; the 16 run sums are then reduced the same way. */
+static double pairwise_tree(double *v, int n)
+{
+    for (; n > 1; n /= 2)
+        for (int j = 0; j < n / 2; ++j)
+            v[j] = v[2 * j] + v[2 * j + 1];
+    return v[0];
+}
+
 static double slot_sum(const double *v, int n)
 {
     double part[1024], run[16];
@@ -200,17 +209,9 @@ static double slot_sum(const double *v, int n)
         part[s] = 0.0;
     for (int i = 0; i < n; ++i)
         part[i % 1024] += v[i];
-    for (int r = 0; r < 16; ++r) {
-        double *g = part + 64 * r;
-        for (int half = 32; half >= 1; half >>= 1)
-            for (int j = 0; j < half; ++j)
-                g[j] = g[j] + g[j + half];
-        run[r] = g[0];
-    }
-    for (int half = 8; half >= 1; half >>= 1)
-        for (int j = 0; j < half; ++j)
-            run[j] = run[j] + run[j + half];
-    return run[0];
+    for (int r = 0; r < 16; ++r)
+        run[r] = pairwise_tree(part + 64 * r, 64);
+    return pairwise_tree(run, 16);
 }
 
 /*

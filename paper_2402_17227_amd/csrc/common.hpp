@@ -106,20 +106,66 @@ inline void launch_timed(int which, Kern kern, dim3 grid, dim3 block, size_t lds
 __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
-// Sum over the 64 lanes by pairwise exchange at distances 32,16,8,4,2,1.
-// Every lane ends with the same value.
-__device__ __forceinline__ float wave_exchange_sum(float v)
+// Sum over the 64 lanes as a fixed tree: neighbours first (exchange-add at distances
+// 1, 2, 4, 8, 16, 32).  Every lane ends with the same value.  The first four levels are DPP
+// lane permutes (quad swaps, then mirrors within 8 and within 16 lanes, which pair the same
+// groups as distances 4 and 8 once the lanes of a group agree); the last two levels take the
+// four 16-lane row values through scalar registers.  No LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = v + __shfl_xor(v, d, kWave);
-    return v;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
-__device__ __forceinline__ double wave_exchange_sum(double v)
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = v + __shfl_xor(v, d, kWave);
-    return v;
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ float read_lane(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+template <typename F>
+__device__ __forceinline__ F wave_exchange_sum(F v)
+{
+    v = v + dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: distance 1
+    v = v + dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: distance 2
+    v = v + dpp_move<0x141>(v);   // row_half_mirror: the other quad of each 8 lanes
+    v = v + dpp_move<0x140>(v);   // row_mirror: the other 8 lanes of each 16
+    const F r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    return (r0 + r1) + (r2 + r3);
+}
+
+__device__ __forceinline__ int wave_sum_int(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);
+    return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+           (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
+
+// The same neighbours-first tree over 16 values (the per-wavefront sums of a 1024-thread block).
+template <typename F>
+__device__ __forceinline__ F tree16(const F *w)
+{
+    return (((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]))) +
+           (((w[8] + w[9]) + (w[10] + w[11])) + ((w[12] + w[13]) + (w[14] + w[15])));
 }
 
 // Philox4x32-10 (Salmon et al., SC'11, Sec. 3.3); returns output word 0.

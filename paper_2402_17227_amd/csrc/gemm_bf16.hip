@@ -443,7 +443,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
             for (int j = 0; j < TN; ++j) {
                 const float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
                 const float send = odd ? mine_e : mine_o;
-                const float recv = __shfl_xor(send, 1, kWave);
+                const float recv = dpp_move<0xB1>(send);   // the neighbouring lane
                 const uint32_t word = odd ? pack_bf16(recv, mine_o) : pack_bf16(mine_e, recv);
                 const int col = n0 + wn0 + j * 32 + (lane & 30);
                 if (dst >= 0 && col < K_in)

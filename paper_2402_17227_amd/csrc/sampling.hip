@@ -8,57 +8,29 @@
 namespace vcas {
 
 // ---- block-wide sums over 1024 threads in a fixed order ---------------------
-// Thread tid is "slot" tid.  Each 64-slot group is combined by exchange steps
-// 32..1, then the 16 group sums by exchange steps 8,4,2,1.  Every thread
-// returns the total.  `buf` is 16 values of LDS; calls must alternate buffers
-// or be separated by a barrier.
-
-__device__ __forceinline__ double block_sum_1024(double v, double *buf)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    v = wave_exchange_sum(v);
-    if (lane == 0) buf[wave] = v;
-    __syncthreads();
-    double t = buf[lane & 15];
-#pragma unroll
-    for (int d = 8; d >= 1; d >>= 1) t = t + __shfl_xor(t, d, kWave);
-    return t;
-}
-
-__device__ __forceinline__ int block_sum_1024(int v, int *buf)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
-    if (lane == 0) buf[wave] = v;
-    __syncthreads();
-    int t = buf[lane & 15];
-#pragma unroll
-    for (int d = 8; d >= 1; d >>= 1) t += __shfl_xor(t, d, kWave);
-    return t;
-}
-
-// Both sums of a keep-probability round behind one barrier.
+// Thread tid is "slot" tid.  Each 64-slot group (one wavefront) is combined by
+// the neighbours-first tree, then the 16 group sums by the same kind of tree.
+// Every thread returns the totals.  `bufd` / `bufi` are 16 values of LDS each;
+// calls must alternate buffers or be separated by a barrier.
 __device__ __forceinline__ void block_sum_pair_1024(double v, int c, double *bufd, int *bufi, double &sum_v, int &sum_c)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     v = wave_exchange_sum(v);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, kWave);
+    c = wave_sum_int(c);
     if (lane == 0) {
         bufd[wave] = v;
         bufi[wave] = c;
     }
     __syncthreads();
-    double t = bufd[lane & 15];
-    int u = bufi[lane & 15];
+    double wd[16];
+    int total = 0;
 #pragma unroll
-    for (int d = 8; d >= 1; d >>= 1) {
-        t = t + __shfl_xor(t, d, kWave);
-        u += __shfl_xor(u, d, kWave);
+    for (int i = 0; i < 16; ++i) {
+        wd[i] = bufd[i];
+        total += bufi[i];
     }
-    sum_v = t;
-    sum_c = u;
+    sum_v = tree16(wd);
+    sum_c = total;
 }
 
 // prob_i = min(1, c * score_i), sum prob = min(budget, #positive scores).
