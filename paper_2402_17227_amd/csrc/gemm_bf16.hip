@@ -233,6 +233,17 @@ __device__ __forceinline__ int xcd_remap(int id, int total)
     return (id & 7) * per + (id >> 3);
 }
 
+// Tile number -> (row tile, column tile), column panels of PANEL tiles, row-major inside a panel.
+template <int PANEL>
+__device__ __forceinline__ void panel_order(int tile, int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+{
+    const int panel = tile / (tiles_m * PANEL);
+    const int in_panel = tile - panel * tiles_m * PANEL;
+    const int width = min(PANEL, tiles_n - panel * PANEL);
+    tile_m = in_panel / width;
+    tile_n = panel * PANEL + in_panel % width;
+}
+
 // The j-th sample (0-based) that is NOT in the ascending list idx[0..cnt).
 __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
 {
@@ -347,7 +358,11 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
     }
     const int tile = xcd_remap(blockIdx.x, compute);
     if (tile >= compute) return;
-    const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+    // Walk the tiles in column panels of 8: the ~64 workgroups an XCD runs at a time then cover
+    // about 8 x 8 tiles and share 8 row blocks of G and 8 column blocks of W through its L2,
+    // instead of 2 row blocks and every column block of a wide W.
+    int tile_m, tile_n;
+    panel_order<8>(tile, compute / tiles_n, tiles_n, tile_m, tile_n);
     const int n0 = tile_n * BN;
 
     const int64_t m0 = (int64_t)tile_m * BM;
@@ -538,7 +553,9 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
     const int id = xcd_remap(blockIdx.x, total);
     if (id >= total) return;
     const int split = id / tiles, tile = id % tiles;
-    const int o0 = (tile / tiles_n) * BM, c0 = (tile % tiles_n) * BN;
+    int tile_o, tile_c;   // panels of 4 column tiles: an XCD's ~32-64 workgroups cover a squarish patch of dW
+    panel_order<4>(tile, tiles / tiles_n, tiles_n, tile_o, tile_c);
+    const int o0 = tile_o * BM, c0 = tile_c * BN;
 
     const int64_t cnt = min((int64_t)max(*cntW, 0), R);
     const int steps_all = (int)((cnt + BK - 1) / BK);
