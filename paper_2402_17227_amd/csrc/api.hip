@@ -47,8 +47,8 @@ vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const f
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
                       const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st);
 
-// Split-K slices of the weight gradient: enough workgroups to cover the chip
-// once, at most 8 (the last-arriving workgroup of a tile reads every partial,
+// Split-K slices of the weight gradient: about one and a half workgroups per
+// CU (a second one hides the first one's waits; more splits cost reduction traffic), at most 8 (the last-arriving workgroup of a tile reads every partial,
 // so that tail grows with the split count), and never so many that a slice at
 // full length R would have fewer than 4 contraction steps.
 int wgrad_split(const vcas_shape *s)
@@ -57,7 +57,7 @@ int wgrad_split(const vcas_shape *s)
     const int tiles = bf ? wgrad_tiles_bf16(s->K_out, s->K_in) : wgrad_tiles_f32(s->K_out, s->K_in);
     const int64_t R = (int64_t)s->N * s->T;
     const int64_t steps = (R + (bf ? 63 : 15)) / (bf ? 64 : 16);
-    int64_t want = (256 + tiles - 1) / tiles;
+    int64_t want = (384 + tiles - 1) / tiles;
     int64_t cap = steps / (bf ? 2 : 8);
     if (want > cap) want = cap;
     if (want > 8) want = 8;

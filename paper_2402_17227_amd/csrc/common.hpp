@@ -35,13 +35,14 @@ inline vcas_status check_shape(const vcas_shape *s)
     return VCAS_OK;
 }
 
-// The bf16 GEMM kernels address G, X and W through 32-bit buffer offsets below 2 GiB.
+// The bf16 GEMM kernels address G, X and W through 32-bit buffer offsets below 2 GiB and form
+// row offsets with 24-bit multiplies.
 inline vcas_status check_gemm_limits(const vcas_shape *s)
 {
     if (s->dtype == VCAS_BF16) {
         const int64_t R = (int64_t)s->N * s->T;
         const int64_t kmax = s->K_in > s->K_out ? s->K_in : s->K_out;
-        if (kmax > 8184 || R * kmax * 2 >= (int64_t)1 << 31) return VCAS_EINVAL;
+        if (kmax > 8184 || R >= (int64_t)1 << 24 || R * kmax * 2 >= (int64_t)1 << 31) return VCAS_EINVAL;
     }
     return VCAS_OK;
 }

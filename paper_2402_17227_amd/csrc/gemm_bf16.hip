@@ -584,6 +584,9 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
     struct Tokens {
         int32_t tok[4];   // row of G / X, or -1
     };
+    // this thread's column chunk lies inside G resp. X (only ragged edge tiles have chunks outside)
+    const bool a_inside = cola < K_out, b_inside = colb < K_in;
+    const uint32_t g_pitch = (uint32_t)K_out * 2u, x_pitch = (uint32_t)K_in * 2u;   // row bytes, < 2^15
     auto fetch_tokens = [&](int step) {
         const int64_t k0 = (int64_t)(s_begin + step) * BK + kq * 4;
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcI, k0 < k_end ? (int)(k0 * 4) : (int)kOutside, 0, 0);
@@ -591,7 +594,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int32_t r = (int32_t)v[i];
-            t.tok[i] = (k0 + i < k_end && r >= 0 && r < R) ? r : -1;
+            t.tok[i] = (k0 + i < k_end && (uint32_t)r < (uint32_t)R) ? r : -1;
         }
         return t;
     };
@@ -621,11 +624,12 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
         fetch_scales(tok_next, sc_next);
         const Tokens tok_after = fetch_tokens(s + 2);
         const Tokens q = tok_cur;
+        // rows < 2^24 and row bytes < 2^15 (checked on the host): 24-bit multiplies are exact and full rate
         auto g_voff = [&](int, int i) {
-            return (q.tok[i] >= 0 && cola < K_out) ? ((uint32_t)q.tok[i] * (uint32_t)K_out + cola) * 2u : kOutside;
+            return (q.tok[i] >= 0 && a_inside) ? __umul24((uint32_t)q.tok[i], g_pitch) + (uint32_t)cola * 2u : kOutside;
         };
         auto x_voff = [&](int, int i) {
-            return (q.tok[i] >= 0 && colb < K_in) ? ((uint32_t)q.tok[i] * (uint32_t)K_in + colb) * 2u : kOutside;
+            return (q.tok[i] >= 0 && b_inside) ? __umul24((uint32_t)q.tok[i], x_pitch) + (uint32_t)colb * 2u : kOutside;
         };
         if (set == 0) {
 #pragma unroll
