@@ -38,7 +38,7 @@ vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, 
 int wgrad_tiles_bf16(int K_out, int K_in);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, hipStream_t st);
+                       const int32_t *cntA, void *dX, int64_t expected_rows, hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
                        hipStream_t st);
@@ -125,9 +125,10 @@ __global__ __launch_bounds__(64) void sq_diff_final_kernel(const double *__restr
 }
 
 static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
-                                  const int32_t *idxA, const int32_t *cntA, void *dX, hipStream_t st)
+                                  const int32_t *idxA, const int32_t *cntA, void *dX, int64_t expected_rows,
+                                  hipStream_t st)
 {
-    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, st)
+    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, expected_rows, st)
                                 : dgrad_f32(s, G, W, p, idxA, cntA, dX, st);
 }
 
@@ -188,7 +189,8 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
             return VCAS_EHIP;
         ws = side;
     }
-    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, st));
+    // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
+    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
     if (!together) VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, uw, ws));
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
                        token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
@@ -280,7 +282,7 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
     VCAS_TRY(check_gemm_limits(shape));
     if (!G || !W || !p || !idxA || !cntA || !dX) return VCAS_ENULL;
     if (!aligned16(G) || !aligned16(W) || !aligned16(dX)) return VCAS_EINVAL;
-    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, as_stream(stream));
+    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, 0, as_stream(stream));
 }
 
 vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X, const float *row_scale_,

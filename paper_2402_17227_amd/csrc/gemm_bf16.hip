@@ -66,31 +66,6 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// Operand whose rows are contiguous along the contraction (G in dgrad).
-// ROWS x 64 tile; thread owns 16-byte slot (tid % 8) of rows tid/8 + j*NT/8.
-template <int ROWS, int NT>
-struct DirectLoader {
-    static constexpr int PER = ROWS * 8 / NT;
-    static_assert(ROWS * 8 % NT == 0 && NT % 8 == 0, "tile/thread mismatch");
-    typedef uint4 Regs[PER];
-    uint32_t voff[PER];   // byte offset of (row, slot) at contraction index 0, or kOutside
-
-    __device__ __forceinline__ void load(Regs &regs, __amdgpu_buffer_rsrc_t rsrc, uint32_t k_bytes) const
-    {
-#pragma unroll
-        for (int j = 0; j < PER; ++j) regs[j] = buffer_load16(rsrc, voff[j], k_bytes);
-    }
-    __device__ __forceinline__ static void store(const Regs &regs, unsigned char *tile)
-    {
-        const int slot = threadIdx.x & 7;
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const int row = (threadIdx.x >> 3) + j * (NT / 8);
-            *reinterpret_cast<uint4 *>(tile + lds_off(row, slot)) = regs[j];
-        }
-    }
-};
-
 // Operand stored [k][col] (col contiguous).  64 x COLS tile; unit u = 4 k-rows
 // x 8 columns.
 template <int COLS, int NT>
@@ -256,9 +231,9 @@ __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
     return j + lo;
 }
 
-// ------------------------------------------------------------------ dgrad
+// ------------------------------------------------- register-staged pipeline
 
-// Software pipeline shared by both kernels.  Two register sets and two LDS
+// Software pipeline of the weight-gradient kernel.  Two register sets and two LDS
 // buffers: while step s is on the matrix cores, the loads of step s+1 are
 // landing in one register set and the loads of step s+2 are being issued into
 // the other, so a global load has about one and a half steps to arrive.
@@ -309,10 +284,67 @@ __device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Comp
     }
 }
 
+// ------------------------------------------------------------------ dgrad
+//
+// The operand tiles of dgrad never pass through registers: buffer loads write
+// straight into LDS (16 bytes per lane, a wavefront fills 1 KiB of consecutive
+// LDS per instruction).  G lands as [row][64 k] rows with the XOR slot swizzle
+// realised by WHICH 16-byte piece of the row each lane fetches; W lands as it
+// lies in memory, [64 k][BN n], its slots swizzled the same way, and is
+// transposed on the way out of LDS by ds_read_b64_tr_b16 (a block of 16 lanes
+// reads 4 k-rows x 16 columns and each lane receives one column's 4 k values).
+// NS stages; the loads of step s+NS-1 are issued while step s is computed.  One
+// barrier per step: before it every wavefront waits until its own loads of the
+// step have landed (s_waitcnt vmcnt, the counter is in order), after it the
+// stage computed in the previous step is free.
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// slot XOR of W-tile row k: the four k rows that a half-wave transposes at once land in four
+// different 64-byte bank groups
+__device__ __forceinline__ int wswz(int k) { return (k & 3) * 4; }
+
+// 128-bit buffer descriptor built by hand (base, stride 0, size in bytes, raw dword format) for
+// use in inline assembly.
+__device__ __forceinline__ i32x4 raw_descriptor(const void *base, uint32_t bytes)
+{
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    i32x4 d;
+    d[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    d[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xffffu));
+    d[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    d[3] = 0x00020000;
+    return d;
+}
+
+// One LDS-direct load: every lane fetches 16 bytes at buffer offset voffset + soffset, the
+// wavefront's 1 KiB lands at LDS byte address lds_base (wave-uniform) in lane order.  Written as
+// assembly so that the compiler does not track it: it would otherwise make every later LDS read
+// wait for ALL loads in flight (it cannot tell the stages apart), and the waits are placed by
+// hand before the barrier anyway.
+__device__ __forceinline__ void lds_direct_load16(i32x4 desc, uint32_t lds_base, uint32_t voffset, uint32_t soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_loads_outstanding()
+{
+    // s_waitcnt vmcnt(N) only: expcnt and lgkmcnt fields left at "no wait"
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+constexpr int kIdxStaged = 1024;   // kept-sample indices a workgroup stages in LDS ahead of the count
+
 // grid: 1-D, tiles_n * (ceil(R/BM) + 1) + 8 workgroups.  The first ceil8(compute
 // tiles) ids compute (spread over the XCDs in contiguous runs), the following
 // ones write the zero rows of dropped samples, the rest exit.
-template <int BM, int BN, int WM, int WN, int OCC>
+// SPQ: the loads of the next step are spread over the MFMAs of the first SPQ
+// quarters of the current one (0: all issued right after the barrier).
+template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint16_t *__restrict__ G,
                                                                   const uint16_t *__restrict__ W,
                                                                   const float *__restrict__ p,
@@ -321,13 +353,22 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
                                                                   int K_out, int tiles_n)
 {
-    constexpr int NT = WM * WN * 64;
+    constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int AI = BM / (8 * NW), BI = BN / (8 * NW);     // LDS-direct loads per wavefront and step
+    constexpr int B_ROWS = 512 / BN, B_SLOTS = BN / 8;         // k rows per W load, 16-byte slots per W row
+    constexpr int STAGE = (BM + BN) * 128, B_AT = BM * 128, B_PITCH = BN * 2;
+    constexpr int LOADS = AI + BI;
+    static_assert(AI >= 1 && BI >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
+    static_assert(STAGE >= kIdxStaged * 4, "index staging area does not fit a stage");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto tA = [&](int buf) { return smem + buf * (BM * 128); };
-    auto tB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
-    int32_t *row_of = reinterpret_cast<int32_t *>(smem + 2 * (BM + BN) * 128);  // [BM] destination row or -1
-    float *scale_of = reinterpret_cast<float *>(row_of + BM);                  // [BM] 1/p of the row's sample
+    int32_t *row_of = reinterpret_cast<int32_t *>(smem + NS * STAGE);
+    float *scale_of = reinterpret_cast<float *>(row_of + BM);
+    // The last stage is not loaded before the first barrier of the main loop; until then it
+    // holds the kept-sample list, fetched together with the count instead of after it.
+    int32_t *idx_staged = reinterpret_cast<int32_t *>(smem + (NS - 1) * STAGE);
+    const int staged = min(N, kIdxStaged);
+    for (int j = threadIdx.x; j < staged; j += NT) idx_staged[j] = idxA[j];
 
     const int cnt = min(max(*cntA, 0), N);
     const int64_t M = (int64_t)cnt * T;
@@ -336,7 +377,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
     const int compute8 = (compute + 7) / 8 * 8;
 
     if ((int)blockIdx.x >= compute8) {
-        // zero rows of dropped samples
+        // zero-fill duty: rows of the samples that are not in the kept list
         const int z = blockIdx.x - compute8;
         const int64_t d0 = (int64_t)(z / tiles_n) * BM;
         const int n0 = (z % tiles_n) * BN;
@@ -358,54 +399,73 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
     }
     const int tile = xcd_remap(blockIdx.x, compute);
     if (tile >= compute) return;
-    // Walk the tiles in column panels of 8: the ~64 workgroups an XCD runs at a time then cover
-    // about 8 x 8 tiles and share 8 row blocks of G and 8 column blocks of W through its L2,
-    // instead of 2 row blocks and every column block of a wide W.
     int tile_m, tile_n;
     panel_order<8>(tile, compute / tiles_n, tiles_n, tile_m, tile_n);
     const int n0 = tile_n * BN;
-
     const int64_t m0 = (int64_t)tile_m * BM;
+    __syncthreads();   // idx_staged complete
     for (int r = threadIdx.x; r < BM; r += NT) {
         const int64_t m = m0 + r;
         int32_t dst = -1;
-        float sc = 0.0f;
         if (m < M) {
-            const int s = idxA[m / T];
-            if (s >= 0 && s < N) {
-                dst = s * T + (int)(m % T);
-                sc = 1.0f / p[s];
-            }
+            const int j = (int)(m / T);
+            const int s = j < staged ? idx_staged[j] : idxA[j];
+            if (s >= 0 && s < N) dst = s * T + (int)(m % T);
         }
         row_of[r] = dst;
-        scale_of[r] = sc;
     }
     __syncthreads();
 
-    typedef DirectLoader<BM, NT> LA;
-    typedef TransLoader<BN, NT> LB;
-    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
-    const __amdgpu_buffer_rsrc_t rsrcW = make_rsrc(W, (uint32_t)((int64_t)K_out * K_in * 2));
-    LA la;
+    const i32x4 descG = raw_descriptor(G, (uint32_t)(R * K_out * 2));
+    const i32x4 descW = raw_descriptor(W, (uint32_t)((int64_t)K_out * K_in * 2));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    // G load j: rows (wave*AI + j)*8 + lane/8, LDS slot lane%8 <- the row's 16-byte piece (slot ^ swz)
+    // W load j: k rows (wave*BI + j)*B_ROWS + lane/B_SLOTS, LDS slot lane%B_SLOTS <- column chunk (slot ^ wswz)
+    uint32_t a_off[AI], b_off[BI];
 #pragma unroll
-    for (int j = 0; j < LA::PER; ++j) {
-        const int32_t src = row_of[(threadIdx.x >> 3) + j * (NT / 8)];
-        la.voff[j] = src >= 0 ? (uint32_t)src * (uint32_t)K_out * 2u + (threadIdx.x & 7) * 16u : kOutside;
+    for (int j = 0; j < AI; ++j) {
+        const int row = (wave * AI + j) * 8 + (lane >> 3);
+        const int32_t src = row_of[row];
+        a_off[j] = src >= 0 ? (uint32_t)src * (uint32_t)K_out * 2u + (uint32_t)(((lane & 7) ^ swz(row)) * 16) : kOutside;
     }
-    // W rows k0 + kquad*4 + i at this thread's 8 columns; rows past K_out fall off the end of W and read
-    // as zero, which also cancels whatever G holds there (only the last step can be ragged)
-    uint32_t w_off[LB::PER][4];
 #pragma unroll
-    for (int j = 0; j < LB::PER; ++j)
+    for (int j = 0; j < BI; ++j) {
+        const int krow = (wave * BI + j) * B_ROWS + lane / B_SLOTS;
+        const int col = n0 + ((lane % B_SLOTS) ^ wswz(krow)) * 8;
+        b_off[j] = col < K_in ? ((uint32_t)krow * (uint32_t)K_in + (uint32_t)col) * 2u : kOutside;
+    }
+    // the d-th of the LOADS loads of contraction step `step` into stage `stage`: G and W pieces alternate
+    auto issue_nth = [&](int d, int stage, int step) {
+        const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + wave * AI * 1024);
+        const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + B_AT + wave * BI * 1024);
+        const uint32_t kb = __builtin_amdgcn_readfirstlane(step * BK * 2);
+        const uint32_t wb = __builtin_amdgcn_readfirstlane(step * BK * K_in * 2);
+        int seen = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int col = n0 + LB::chunk(j) * 8;
-            w_off[j][i] = col < K_in ? ((uint32_t)(LB::kquad(j) * 4 + i) * (uint32_t)K_in + col) * 2u : kOutside;
+        for (int j = 0; j < (AI > BI ? AI : BI); ++j) {
+            if (j < AI) {
+                if (seen == d) lds_direct_load16(descG, a_dst + j * 1024, a_off[j], kb);
+                ++seen;
+            }
+            if (j < BI) {
+                if (seen == d) lds_direct_load16(descW, b_dst + j * 1024, b_off[j], wb);
+                ++seen;
+            }
         }
-    typename LA::Regs ra[2];
-    typename LB::Regs rb[2];
+    };
+    const int steps = (K_out + BK - 1) / BK;
+    // prologue: steps 0 .. NS-2 in flight (a step past the end loads zeros and keeps the counts uniform)
+#pragma unroll
+    for (int d = 0; d < NS - 1; ++d)
+#pragma unroll
+        for (int q = 0; q < LOADS; ++q) issue_nth(q, d, d < steps ? d : steps + 64);
+    // 1/p of the tile's rows is needed in the epilogue only: fetched behind the first tile loads
+    for (int r = threadIdx.x; r < BM; r += NT) {
+        const int32_t dst = row_of[r];
+        scale_of[r] = dst >= 0 ? 1.0f / p[dst / T] : 0.0f;
+    }
 
-    const int wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -415,36 +475,77 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    auto load = [&](int set, int s) {
-        const uint32_t kb = (uint32_t)s * BK * 2u;                       // bytes along a G row
-        const uint32_t wb = (uint32_t)s * BK * (uint32_t)K_in * 2u;      // bytes down the rows of W
-        auto w_voff = [&](int j, int i) { return w_off[j][i]; };
-        if (set == 0) {
-            la.load(ra[0], rsrcG, kb);
-            LB::load(rb[0], rsrcW, w_voff, wb);
-        } else {
-            la.load(ra[1], rsrcG, kb);
-            LB::load(rb[1], rsrcW, w_voff, wb);
+    const int r32 = lane & 31, h = lane >> 5;
+    const int blk = lane >> 4, sl = lane & 15;    // 16-lane block and lane within it
+    constexpr int KS = BK / 16, MM = TM * TN, SPAN = KS * MM * SPQ / 4;
+    // One contraction step on stage `stage`; the loads of step `nstep` go to stage `nstage`.
+    // Fragments of two k-slices are read ahead; load d goes out after MFMA number d*SPAN/LOADS.
+    auto step_body = [&](int stage, int nstage, int nstep) {
+        const unsigned char *tileA = smem + stage * STAGE;
+        const unsigned char *tileB = tileA + B_AT;
+        bf16x8 a[2][TM], b[2][TN];
+        auto read_frags = [&](int ks, bf16x8(&fa)[TM], bf16x8(&fb)[TN]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(tileA + lds_off(wm0 + i * 32 + r32, ks * 2 + h));
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                bf16x4 half[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int k = ks * 16 + (blk >> 1) * 8 + e * 4 + (sl >> 2);
+                    const int col = wn0 + i * 32 + (blk & 1) * 16 + (sl & 3) * 4;
+                    const unsigned char *src = tileB + k * B_PITCH + (((col >> 3) ^ wswz(k)) << 4) + (col & 7) * 2;
+                    half[e] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4 *)(src));
+                }
+                fb[i] = __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        };
+        if (SPQ == 0) {
+#pragma unroll
+            for (int d = 0; d < LOADS; ++d) issue_nth(d, nstage, nstep);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        read_frags(0, a[0], b[0]);
+        if (KS > 1) read_frags(1, a[1], b[1]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+                    if (SPQ > 0) {
+                        const int m = ks * MM + i * TN + j;
+#pragma unroll
+                        for (int d = 0; d < LOADS; ++d)
+                            if (d * SPAN / LOADS == m) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                issue_nth(d, nstage, nstep);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                    }
+                }
+            if (ks + 2 < KS) read_frags(ks + 2, a[ks & 1], b[ks & 1]);
         }
     };
-    auto stage = [&](int set, int buf) {
-        if (set == 0) {
-            LA::store(ra[0], tA(buf));
-            LB::store(rb[0], tB(buf));
-        } else {
-            LA::store(ra[1], tA(buf));
-            LB::store(rb[1], tB(buf));
-        }
-    };
-    auto compute_step = [&](int buf) { mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
-    auto schedule = [&](auto id) {
-        schedule_phase<TM, TN, LA::PER + 4 * LB::PER, 16 * LB::PER, LA::PER + 8 * LB::PER, decltype(id)::value>();
-    };
-    pipeline((K_out + BK - 1) / BK, load, stage, compute_step, schedule);
 
-    // Epilogue: scale by 1/p, round to bf16, pair neighbouring columns (lanes l, l^1)
-    // so that every lane stores one 32-bit word: even lanes rows of even v, odd lanes odd v.
-    const int lane = threadIdx.x & 63;
+    for (int s = 0; s < steps; ++s) {
+        // the NS-2 younger steps may stay in flight; step s must have landed
+        wait_loads_outstanding<(NS - 2) * LOADS>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const int nxt = s + NS - 1;
+        __builtin_amdgcn_sched_barrier(0);
+        step_body(s % NS, nxt % NS, nxt < steps ? nxt : steps + 64);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_loads_outstanding<0>();
+
+    // Each MFMA lane holds one column of 16 rows; neighbouring lanes swap every second value so
+    // that a lane owns two adjacent columns of one row and stores them as one dword.
     const bool odd = lane & 1;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -458,7 +559,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
             for (int j = 0; j < TN; ++j) {
                 const float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
                 const float send = odd ? mine_e : mine_o;
-                const float recv = dpp_move<0xB1>(send);   // the neighbouring lane
+                const float recv = dpp_move<0xB1>(send);
                 const uint32_t word = odd ? pack_bf16(recv, mine_o) : pack_bf16(mine_e, recv);
                 const int col = n0 + wn0 + j * 32 + (lane & 30);
                 if (dst >= 0 && col < K_in)
@@ -688,7 +789,7 @@ static bool allow_lds(Kern kern, size_t bytes)
                                (int)bytes) == hipSuccess;
 }
 
-template <int BM, int BN, int WM, int WN, int OCC>
+template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
                                 const int32_t *idxA, const int32_t *cntA, void *dX, hipStream_t st)
 {
@@ -696,29 +797,40 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     const int tiles_n = (s.K_in + BN - 1) / BN;
     const int64_t grid = tiles_n * ((R + BM - 1) / BM + 1) + 8;
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
-    const size_t lds = 2 * (BM + BN) * 128 + BM * 8;
-    auto kern = dgrad_bf16_kernel<BM, BN, WM, WN, OCC>;
-    static bool allowed = false;   // once per instantiation
+    const size_t lds = NS * (BM + BN) * 128 + BM * 8;
+    auto kern = dgrad_bf16_kernel<BM, BN, WM, WN, NS, OCC, SPQ>;
+    static bool allowed = false;
     if (!allowed) {
         if (!allow_lds(kern, lds)) return VCAS_EHIP;
         allowed = true;
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                       s.K_out, tiles_n);
+                 s.K_out, tiles_n);
     return launch_status();
 }
 
+// expected_rows: how many of the R rows the caller expects to be kept (R if unknown); it only
+// steers the tile choice, any count is computed correctly by every variant.
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, hipStream_t st)
+                       const int32_t *cntA, void *dX, int64_t expected_rows, hipStream_t st)
 {
-    // 128x128 tiles, unless even the full problem (keep ratio one) would leave a quarter of the
-    // chip's 256 CUs x 2 resident workgroups idle: then 64x128 tiles, twice as many workgroups
-    // with half the serial work each (measured on 768-wide BERT-base layers: 11 vs 14 us).
+    // The loads into LDS run at about 40 bytes per clock and CU, so the largest tile that still
+    // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 192 tiles up; else 128x128
+    // (two per CU) while more than 256 of them exist; else 64x128, twice as many workgroups with
+    // half the serial work each.  Measured, R=16384, 1024->4096: 123 / 137 / 191 us; R=4096,
+    // 768->3072: 68 / 37 / 33 us.  When even the 64x128 tiles leave CUs with a single workgroup,
+    // nothing overlaps a tile's own load latency, so the pipeline goes four stages deep instead
+    // (2048 kept rows, 768->3072: 22 vs 29 us).
     const int64_t R = (int64_t)s.N * s.T;
-    const int64_t tiles128 = ((R + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles128 <= 256) return launch_dgrad<64, 128, 2, 2, 2>(s, G, W, p, idxA, cntA, dX, st);
-    return launch_dgrad<128, 128, 2, 2, 2>(s, G, W, p, idxA, cntA, dX, st);
+    const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
+    const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
+    const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
+    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, st);
+    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, st);
+    const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
+    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, st);
+    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, st);
 }
 
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,

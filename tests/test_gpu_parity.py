@@ -169,6 +169,41 @@ def test_dgrad_with_given_mask(vb, dtype, N, T, kin, kout, keep):
         assert rel_l2(got, want) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("N,T,kin,kout,frac", [(17, 128, 2040, 136, 1.0),     # 128x128 tiles, ragged columns
+                                                (17, 128, 2040, 136, 0.6),
+                                                (33, 125, 3080, 200, 1.0),     # 256x256 tiles, ragged rows and columns
+                                                (33, 125, 3080, 200, 0.5),
+                                                (17, 128, 1024, 72, 1.0),      # 64x128 tiles, two stages
+                                                (1100, 4, 264, 72, 0.7)])     # more kept samples than are staged in LDS
+def test_dgrad_bf16_tile_variants(vb, N, T, kin, kout, frac):
+    """Every tile shape the bf16 dgrad launcher can choose, against the oracle (Eq. 1, upper line)."""
+    rng = np.random.default_rng(N * 1000 + kin)
+    R = N * T
+    G = workloads.f32_to_bf16_bits(rng.standard_normal((R, kout)).astype(np.float32))
+    W = workloads.f32_to_bf16_bits((rng.standard_normal((kout, kin)) * 0.05).astype(np.float32))
+    p = rng.uniform(0.2, 1, N).astype(np.float32)
+    maskA = (rng.uniform(size=N) < frac).astype(np.uint8)
+    idxA = np.nonzero(maskA)[0].astype(np.int32)
+    idx_buf = np.full(N, -1, np.int32)
+    idx_buf[:idxA.size] = idxA
+    shape = vb.shape_of(N, T, kin, kout, BF16)
+    dX = torch.full((R, kin), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vb.vcas_sampled_dgrad(shape, _dev(G, BF16), _dev(W, BF16), _dev(p), _dev(idx_buf),
+                          _dev(np.array([idxA.size], np.int32)), dX)
+    torch.cuda.synchronize()
+    from tests.gpu_util import from_device, rel_l2
+    got = from_device(dX)
+    want = oracle.dgrad(G, W, BF16, N, T, p, maskA)
+    assert np.isfinite(got).all()
+    assert np.all(got[np.repeat(maskA == 0, T)] == 0)
+    assert rel_l2(got, want) <= TOL[BF16]
+    # every kept row on its own, so that a misplaced tile cannot hide in the global norm
+    kept = np.repeat(maskA == 1, T)
+    num = np.linalg.norm(got[kept].astype(np.float64) - want[kept], axis=1)
+    den = np.linalg.norm(want[kept], axis=1) + 1e-30
+    assert (num / den).max() <= 2 * TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("R,kin,kout,frac", [(300, 136, 264, 0.5), (1000, 128, 128, 1.0), (70, 64, 72, 0.0),
                                              (5000, 256, 384, 0.3), (4096, 768, 768, 0.05), (130, 768, 256, 0.7)])
