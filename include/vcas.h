@@ -17,7 +17,8 @@
  *    and tensor base addresses 16-byte aligned.
  *  - The caller owns every buffer.  The library allocates no device memory;
  *    calls that need scratch take a `workspace` of at least
- *    vcas_workspace_bytes(shape) bytes, 16-byte aligned, contents don't matter.
+ *    vcas_workspace_bytes(shape) bytes, 16-byte aligned, on which
+ *    vcas_workspace_init has run once; the rest of its contents don't matter.
  *    bf16 tensors must be smaller than 2 GiB each and K_in, K_out <= 8184
  *    (buffer-addressing limits of the GEMM kernels).
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
@@ -93,6 +94,17 @@ const char *vcas_status_string(vcas_status s);
 /* Bytes of scratch the calls below need for this shape (host query; 0 on a
  * bad shape). */
 size_t vcas_workspace_bytes(const vcas_shape *shape);
+
+/*
+ * Zeroes the workspace's control words, its first 8 KiB (a small fill kernel on
+ * `stream`, so the call may be captured in a graph).  Must run once after the
+ * buffer is allocated and before vcas_linear_backward or vcas_variance_probe
+ * first use it: the launch that fuses the row norms with SampleA and SampleW
+ * (Sec. 4.1, 4.2) counts finished workgroups there to find the last one.  Every
+ * call leaves the words zero again, so one initialisation lasts as long as the
+ * buffer; it is needed again only after a call was aborted mid-flight.
+ */
+vcas_status vcas_workspace_init(const vcas_shape *shape, void *workspace, void *stream);
 
 /*
  * Squared row norms, the ||.||_2^2 factors of Eq. 3 and the ||G_i||_F of

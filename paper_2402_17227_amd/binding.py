@@ -17,7 +17,7 @@ VCAS_F32, VCAS_BF16 = 0, 1
 STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: "VCAS_EWORKSPACE", 5: "VCAS_EHIP"}
 
 EXPORTS = [
-    "vcas_status_string", "vcas_workspace_bytes", "vcas_row_norms", "vcas_keep_probs",
+    "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
     "vcas_linear_backward", "vcas_variance_probe", "vcas_profile_begin", "vcas_profile_end",
 ]
@@ -125,11 +125,17 @@ def vcas_workspace_bytes(shape: Shape) -> int:
     return int(lib().vcas_workspace_bytes(C.byref(shape)))
 
 
+def vcas_workspace_init(shape: Shape, workspace):
+    _check(lib().vcas_workspace_init(C.byref(shape), _ptr(workspace), _stream()), "vcas_workspace_init")
+
+
 def make_workspace(shape: Shape, device="cuda") -> torch.Tensor:
     nbytes = vcas_workspace_bytes(shape)
     if nbytes == 0:
         raise VcasError("bad shape")
-    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(lib().vcas_workspace_init(C.byref(shape), _ptr(ws), _stream()), "vcas_workspace_init")
+    return ws
 
 
 def vcas_row_norms(shape: Shape, G, X, sample_mask, gsq, xsq, gnorm):

@@ -34,6 +34,10 @@ vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const 
                       uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st);
 vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
                            int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st);
+bool plan_fused_fits(int N, int T);
+vcas_status plan_fused(const void *G, int K_out, const void *X, int K_in, int dtype, int N, int T, double budget_a,
+                       double budget_w, int token_sampling, const vcas_rng &rng, float *uniforms, uint32_t *ticket,
+                       const vcas_plan &pl, hipStream_t st);
 // gemm_bf16.hip / gemm_f32.hip
 int wgrad_tiles_bf16(int K_out, int K_in);
 int wgrad_tiles_f32(int K_out, int K_in);
@@ -47,10 +51,9 @@ vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const f
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
                       const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st);
 
-// Split-K slices of the weight gradient: about one and a half workgroups per
-// CU (a second one hides the first one's waits; more splits cost reduction traffic), at most 8 (the last-arriving workgroup of a tile reads every partial,
-// so that tail grows with the split count), and never so many that a slice at
-// full length R would have fewer than 4 contraction steps.
+// Split-K slices of the weight gradient: about one and a half workgroups per CU (a second one
+// hides the first one's waits; more splits cost reduction traffic), at most 8, and never so many that a slice at full length R would have fewer than 2 (bf16) or 8 (fp32)
+// contraction steps.
 int wgrad_split(const vcas_shape *s)
 {
     const bool bf = s->dtype == VCAS_BF16;
@@ -177,13 +180,25 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
     // are zeroed afterwards).  Large layers: a second launch that skips dropped samples' rows.
     const bool together = (int64_t)R * s.K_in * elem_bytes(s.dtype) <= ((int64_t)16 << 20);
     float *uw = token_sampling ? u : nullptr;
-    if (together)
-        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
-    else
-        VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
-    VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+    // Small layers with short vectors, everything on one stream: norms, SampleA and SampleW in
+    // ONE launch (the workgroup that finishes its rows last does the two samplers).  With a side
+    // stream the samplers stay separate launches: SampleW then runs beside dX instead of before it.
+    const bool forked = side && side != st;
+    const bool fused = together && !forked && plan_fused_fits(s.N, s.T);
+    if (fused) {
+        uint32_t *ticket = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(workspace) +
+                                                        workspace_layout(&s).control);
+        VCAS_TRY(plan_fused(G, s.K_out, X, s.K_in, s.dtype, s.N, s.T, (double)s.N * rho, (double)R * rho * nu,
+                            token_sampling, rng, u, ticket, pl, st));
+    } else {
+        if (together)
+            VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
+        else
+            VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
+        VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+    }
     hipStream_t ws = st;   // stream of the weight-gradient half
-    if (side && side != st) {
+    if (forked) {
         hipEvent_t ev = fork_event();
         if (!ev || hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(side, ev, 0) != hipSuccess)
             return VCAS_EHIP;
@@ -192,8 +207,9 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
     // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
     if (!together) VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, uw, ws));
-    VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
-                       token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
+    if (!fused)
+        VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
+                           token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
     if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, ws));
     return VCAS_OK;
 }
@@ -221,6 +237,20 @@ size_t vcas_workspace_bytes(const vcas_shape *shape)
 {
     if (check_shape(shape) != VCAS_OK) return 0;
     return workspace_layout(shape).total;
+}
+
+vcas_status vcas_workspace_init(const vcas_shape *shape, void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!aligned16(workspace)) return VCAS_EINVAL;
+    const WorkspaceLayout w = workspace_layout(shape);
+    uint32_t *control = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(workspace) + w.control);
+    const int words = (int)((w.partials - w.control) / 4);
+    // a fill kernel rather than hipMemsetAsync, so that the call may be captured in a graph
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((words + 255) / 256), dim3(256), 0, as_stream(stream), control,
+                       (size_t)words);
+    return launch_status();
 }
 
 vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X, const uint8_t *sample_mask,

@@ -50,21 +50,24 @@ inline vcas_status check_gemm_limits(const vcas_shape *s)
 inline int elem_bytes(int dtype) { return dtype == VCAS_BF16 ? 2 : 4; }
 
 // ---- workspace layout -------------------------------------------------------
-// splits * K_out * K_in fp32: split-K partial tiles of the weight gradient,
-// then two K_out*K_in fp32 matrices and 32 doubles for the variance probe,
-// then R floats: the SampleW uniforms of vcas_linear_backward
+// kPlanTicketBytes of control words (the ticket counters of the fused planning
+// kernel), zero between calls; then splits * K_out * K_in fp32: split-K partial tiles of
+// the weight gradient, then two K_out*K_in fp32 matrices and 32 doubles for the
+// variance probe, then R floats: the SampleW uniforms of vcas_linear_backward
 
 struct WorkspaceLayout {
-    size_t partials, probe_exact, probe_draw, probe_acc, uniforms, total;
+    size_t control, partials, probe_exact, probe_draw, probe_acc, uniforms, total;
 };
 
+constexpr size_t kPlanTicketBytes = 8192;   // 33 counters, one 128-byte line each, rounded up
 int wgrad_split(const vcas_shape *s);   // host: number of split-K slices for this shape
 
 inline WorkspaceLayout workspace_layout(const vcas_shape *s)
 {
     WorkspaceLayout w;
     size_t mat = (size_t)s->K_out * s->K_in * sizeof(float);
-    w.partials = 0;
+    w.control = 0;
+    w.partials = kPlanTicketBytes;
     w.probe_exact = w.partials + mat * (size_t)wgrad_split(s);
     w.probe_draw = w.probe_exact + mat;
     w.probe_acc = w.probe_draw + mat;

@@ -1,48 +1,14 @@
 // Row-norm kernels: squared 2-norms of the rows of G and X (the factors of
 // Eq. 3 and the per-sample Frobenius norms of Sec. 4.1 of the VCAS paper).
 // HBM-bound: every element is read once, one fp32 per row is written.
-//
-// Summation order (fixed, independent of the launch): 16-byte group j of a row
-// belongs to lane j mod 64; a lane folds its elements in ascending k with
-// acc = fma(v, v, acc); lanes are combined by exchange steps 32,16,8,4,2,1.
-#include "common.hpp"
+#include "rowsum.hpp"
 
 namespace vcas {
 
-template <bool BF16>
-__device__ __forceinline__ float fold16(const uint4 &c, float acc)
-{
-    if constexpr (BF16) {
-        acc = __builtin_fmaf(bf16_lo(c.x), bf16_lo(c.x), acc);
-        acc = __builtin_fmaf(bf16_hi(c.x), bf16_hi(c.x), acc);
-        acc = __builtin_fmaf(bf16_lo(c.y), bf16_lo(c.y), acc);
-        acc = __builtin_fmaf(bf16_hi(c.y), bf16_hi(c.y), acc);
-        acc = __builtin_fmaf(bf16_lo(c.z), bf16_lo(c.z), acc);
-        acc = __builtin_fmaf(bf16_hi(c.z), bf16_hi(c.z), acc);
-        acc = __builtin_fmaf(bf16_lo(c.w), bf16_lo(c.w), acc);
-        acc = __builtin_fmaf(bf16_hi(c.w), bf16_hi(c.w), acc);
-    } else {
-        float a = __uint_as_float(c.x), b = __uint_as_float(c.y), d = __uint_as_float(c.z), e = __uint_as_float(c.w);
-        acc = __builtin_fmaf(a, a, acc);
-        acc = __builtin_fmaf(b, b, acc);
-        acc = __builtin_fmaf(d, d, acc);
-        acc = __builtin_fmaf(e, e, acc);
-    }
-    return acc;
-}
-
 // One wavefront per row; CH 16-byte groups per lane are in flight at once.
 // Rows of samples whose sample_keep byte is 0 are not read and get 0.
-// If `uniforms` is given, the launch also draws the Philox uniform of every row
-// for sampler `stream_id` (they do not depend on the data; the arithmetic hides
-// under the memory stream).
-struct UniformJob {
-    float *uniforms;   // null: no job
-    uint64_t seed;
-    uint32_t layer, stream_id, draw;
-    const uint32_t *draw_offset;
-};
-
+// If a UniformJob is given, the launch also draws the Philox uniform of every
+// row for that sampler (the arithmetic hides under the memory stream).
 template <bool BF16, int CH>
 __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
                                                         int T, const uint8_t *__restrict__ sample_keep,
@@ -61,20 +27,7 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict_
             if (lane == 0) out[row] = 0.0f;
             continue;
         }
-        const uint4 *p = A + row * groups_per_row;
-        float acc = 0.0f;
-        for (int base = 0; base < groups_per_row; base += 64 * CH) {
-            uint4 v[CH];
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                int g = base + lane + 64 * j;
-                v[j] = g < groups_per_row ? p[g] : make_uint4(0u, 0u, 0u, 0u);
-            }
-            // a zero group leaves acc unchanged (fma(0,0,acc) == acc for acc >= +0)
-#pragma unroll
-            for (int j = 0; j < CH; ++j) acc = fold16<BF16>(v[j], acc);
-        }
-        acc = wave_exchange_sum(acc);
+        const float acc = wave_row_sumsq<BF16, CH>(A + row * groups_per_row, groups_per_row);
         if (lane == 0) out[row] = acc;
     }
 }
@@ -101,19 +54,7 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
         const bool second = w >= R;
         const int64_t row = second ? w - R : w;
         const int groups = second ? groups_b : groups_a;
-        const uint4 *p = (second ? B : A) + row * groups;
-        float acc = 0.0f;
-        for (int base = 0; base < groups; base += 64 * CH) {
-            uint4 v[CH];
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                int g = base + lane + 64 * j;
-                v[j] = g < groups ? p[g] : make_uint4(0u, 0u, 0u, 0u);
-            }
-#pragma unroll
-            for (int j = 0; j < CH; ++j) acc = fold16<BF16>(v[j], acc);
-        }
-        acc = wave_exchange_sum(acc);
+        const float acc = wave_row_sumsq<BF16, CH>((second ? B : A) + row * groups, groups);
         if (lane == 0) (second ? out_b : out_a)[row] = acc;
     }
 }

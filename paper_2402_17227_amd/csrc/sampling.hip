@@ -3,7 +3,7 @@
 // Philox Bernoulli masks, kept-row compaction, and the two small elementwise
 // steps (leverage scores, per-row scale).  All vectors are at most R floats,
 // so these kernels are latency-bound, not bandwidth-bound.
-#include "common.hpp"
+#include "rowsum.hpp"
 
 namespace vcas {
 
@@ -276,13 +276,13 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
     }
 }
 
-// SampleA for N <= 1024 with every intermediate in LDS or registers.
-__global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__restrict__ gsq, int N, int T,
-                                                              double budget, uint64_t seed, uint32_t layer,
-                                                              uint32_t draw, const uint32_t *__restrict__ draw_offset,
-                                                              float *__restrict__ gnorm, float *__restrict__ p,
-                                                              uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
-                                                              int32_t *__restrict__ cntA)
+// SampleA for N <= 1024 with every intermediate in LDS or registers (one workgroup of 1024).
+__device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gsq, int N, int T, double budget,
+                                                    uint64_t seed, uint32_t layer, uint32_t draw,
+                                                    const uint32_t *__restrict__ draw_offset,
+                                                    float *__restrict__ gnorm, float *__restrict__ p,
+                                                    uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
+                                                    int32_t *__restrict__ cntA)
 {
     __shared__ float gn[1024];
     __shared__ uint8_t mk[1024];
@@ -311,17 +311,25 @@ __global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__res
     compact_block(mk, N, idxA, cntA);
 }
 
-// SampleW for R <= 1024*E.
+__global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__restrict__ gsq, int N, int T,
+                                                              double budget, uint64_t seed, uint32_t layer,
+                                                              uint32_t draw, const uint32_t *__restrict__ draw_offset,
+                                                              float *__restrict__ gnorm, float *__restrict__ p,
+                                                              uint8_t *__restrict__ maskA, int32_t *__restrict__ idxA,
+                                                              int32_t *__restrict__ cntA)
+{
+    sampler_a_fast_body(gsq, N, T, budget, seed, layer, draw, draw_offset, gnorm, p, maskA, idxA, cntA);
+}
+
+// SampleW for R <= 1024*E (one workgroup of 1024).
 template <int E>
-__global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__restrict__ gsq,
-                                                              float *__restrict__ xsq, int zero_dropped_xsq,
-                                                              const float *__restrict__ p,
-                                                              const uint8_t *__restrict__ maskA,
-                                                              const float *__restrict__ u, int N, int T, double budget,
-                                                              int token_sampling, float *__restrict__ score,
-                                                              float *__restrict__ q, uint8_t *__restrict__ maskW,
-                                                              float *__restrict__ scaleW, int32_t *__restrict__ idxW,
-                                                              int32_t *__restrict__ cntW)
+__device__ __forceinline__ void sampler_w_fast_body(const float *__restrict__ gsq, float *__restrict__ xsq,
+                                                    int zero_dropped_xsq, const float *__restrict__ p,
+                                                    const uint8_t *__restrict__ maskA, const float *__restrict__ u,
+                                                    int N, int T, double budget, int token_sampling,
+                                                    float *__restrict__ score, float *__restrict__ q,
+                                                    uint8_t *__restrict__ maskW, float *__restrict__ scaleW,
+                                                    int32_t *__restrict__ idxW, int32_t *__restrict__ cntW)
 {
     __shared__ uint8_t mk[1024 * E];
     const int tid = threadIdx.x;
@@ -371,6 +379,21 @@ __global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__res
     }
     __syncthreads();
     compact_block(mk, R, idxW, cntW);
+}
+
+template <int E>
+__global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__restrict__ gsq,
+                                                              float *__restrict__ xsq, int zero_dropped_xsq,
+                                                              const float *__restrict__ p,
+                                                              const uint8_t *__restrict__ maskA,
+                                                              const float *__restrict__ u, int N, int T, double budget,
+                                                              int token_sampling, float *__restrict__ score,
+                                                              float *__restrict__ q, uint8_t *__restrict__ maskW,
+                                                              float *__restrict__ scaleW, int32_t *__restrict__ idxW,
+                                                              int32_t *__restrict__ cntW)
+{
+    sampler_w_fast_body<E>(gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW,
+                           scaleW, idxW, cntW);
 }
 
 // SampleA: ||G_i||_F from gsq, p, Bernoulli mask over samples, kept list.
