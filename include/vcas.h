@@ -197,6 +197,28 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
                                  void *stream, void *side_stream);
 
 /*
+ * The two halves of vcas_linear_backward as calls of their own, for callers
+ * that schedule them apart (e.g. the weight gradients of a block of layers on a
+ * second stream while the chain of activation gradients goes on).
+ * vcas_backward_data: row norms of G, p, SampleA mask and kept list (Sec. 4.1),
+ * dX (Eq. 1, upper line; dX may be null); on small layers also the row norms of
+ * X and the SampleW uniforms, which do not depend on SampleA.  Fills gsq, gnorm,
+ * p, maskA, idxA, cntA of *plan.
+ * vcas_backward_weight: must be ordered after vcas_backward_data with the same
+ * shape, G, X, rho, rng, token_sampling, plan and workspace (same stream, or an
+ * event).  Row norms of X on kept samples if not taken yet, leverage scores, q,
+ * SampleW mask, scale (Sec. 4.2), dW (may be null).  Fills the remaining fields
+ * of *plan.  Together the two calls compute bit for bit what
+ * vcas_linear_backward computes.
+ */
+vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const void *X, const void *W,
+                               double rho, const vcas_rng *rng, int32_t token_sampling,
+                               const vcas_plan *plan, void *dX, void *workspace, void *stream);
+vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho,
+                                 double nu, const vcas_rng *rng, int32_t token_sampling,
+                                 const vcas_plan *plan, float *dW, void *workspace, void *stream);
+
+/*
  * Variance probe for the adaptive keep ratios (Sec. 4.1 variance, Eq. 3, and
  * the Monte-Carlo lines of Alg. 1) over M mask draws, draw j using
  * rng.draw = base->draw + j.  out[4] (device, fp64):

@@ -19,7 +19,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_variance_probe", "vcas_profile_begin", "vcas_profile_end",
+    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_weight", "vcas_variance_probe", "vcas_profile_begin", "vcas_profile_end",
 ]
 
 
@@ -181,6 +181,21 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
     _check(lib().vcas_linear_backward(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.c_double(nu),
                                       C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
                                       _ptr(dW), _ptr(workspace), _stream(), side), "vcas_linear_backward")
+
+
+def vcas_backward_data(shape: Shape, G, X, W, rho: float, rng: Rng, token_sampling: bool, plan: Plan, dX, workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_backward_data(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.byref(rng),
+                                    C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX), _ptr(workspace),
+                                    _stream()), "vcas_backward_data")
+
+
+def vcas_backward_weight(shape: Shape, G, X, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dW,
+                         workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_backward_weight(C.byref(shape), _ptr(G), _ptr(X), C.c_double(rho), C.c_double(nu),
+                                      C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dW),
+                                      _ptr(workspace), _stream()), "vcas_backward_weight")
 
 
 def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M: int, plan: Plan, out, workspace):

@@ -169,49 +169,82 @@ static hipEvent_t fork_event()
     return ev;
 }
 
+// Small layers: the row norms of X do not wait for SampleA; they are taken for every row in the
+// same launch as those of G (one launch and one dependency fewer; rows of dropped samples are
+// zeroed afterwards).  Large layers: a second launch that skips dropped samples' rows.
+static bool norms_together(const vcas_shape &s)
+{
+    return (int64_t)s.N * s.T * s.K_in * elem_bytes(s.dtype) <= ((int64_t)16 << 20);
+}
+
+static float *uniforms_of(const vcas_shape &s, void *workspace)
+{
+    return reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + workspace_layout(&s).uniforms);
+}
+
+// Data half: row norms of G (and of X, with the SampleW uniforms, on small layers), SampleA, dX.
+static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
+                             const vcas_rng &rng, int token_sampling, const vcas_plan &pl, void *dX, void *workspace,
+                             hipStream_t st)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
+    if (norms_together(s))
+        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
+    else
+        VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
+    VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+    // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
+    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
+    return VCAS_OK;
+}
+
+// Weight half, after the data half of the same layer and draw: row norms of X on kept samples
+// (large layers), SampleW, dW.
+static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X, double rho, double nu,
+                               const vcas_rng &rng, int token_sampling, const vcas_plan &pl, float *dW,
+                               void *workspace, hipStream_t st)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    float *u = uniforms_of(s, workspace);
+    const bool together = norms_together(s);
+    if (!together)
+        VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u,
+                                         token_sampling ? u : nullptr, st));
+    VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
+                       token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
+    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+    return VCAS_OK;
+}
+
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                                         double nu, const vcas_rng &rng, int token_sampling, const vcas_plan &pl,
                                         void *dX, float *dW, void *workspace, hipStream_t st, hipStream_t side)
 {
     const int64_t R = (int64_t)s.N * s.T;
-    float *u = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + workspace_layout(&s).uniforms);
-    // Small layers: the row norms of X do not wait for SampleA; they are taken for every row in
-    // the same launch as those of G (one launch and one dependency fewer; rows of dropped samples
-    // are zeroed afterwards).  Large layers: a second launch that skips dropped samples' rows.
-    const bool together = (int64_t)R * s.K_in * elem_bytes(s.dtype) <= ((int64_t)16 << 20);
-    float *uw = token_sampling ? u : nullptr;
+    const bool forked = side && side != st;
     // Small layers with short vectors, everything on one stream: norms, SampleA and SampleW in
     // ONE launch (the workgroup that finishes its rows last does the two samplers).  With a side
     // stream the samplers stay separate launches: SampleW then runs beside dX instead of before it.
-    const bool forked = side && side != st;
-    const bool fused = together && !forked && plan_fused_fits(s.N, s.T);
-    if (fused) {
-        uint32_t *ticket = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(workspace) +
-                                                        workspace_layout(&s).control);
+    if (!forked && norms_together(s) && plan_fused_fits(s.N, s.T)) {
+        uint32_t *tickets = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(workspace) +
+                                                         workspace_layout(&s).control);
         VCAS_TRY(plan_fused(G, s.K_out, X, s.K_in, s.dtype, s.N, s.T, (double)s.N * rho, (double)R * rho * nu,
-                            token_sampling, rng, u, ticket, pl, st));
-    } else {
-        if (together)
-            VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
-        else
-            VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
-        VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+                            token_sampling, rng, uniforms_of(s, workspace), tickets, pl, st));
+        if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
+        if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+        return VCAS_OK;
     }
-    hipStream_t ws = st;   // stream of the weight-gradient half
-    if (forked) {
-        hipEvent_t ev = fork_event();
-        if (!ev || hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(side, ev, 0) != hipSuccess)
-            return VCAS_EHIP;
-        ws = side;
+    if (!forked) {
+        VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, dX, workspace, st));
+        return weight_half(s, G, X, rho, nu, rng, token_sampling, pl, dW, workspace, st);
     }
-    // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
+    // The weight half needs SampleA's outcome but not dX: order it after SampleA, beside dX.
+    VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, nullptr, workspace, st));
+    hipEvent_t ev = fork_event();
+    if (!ev || hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(side, ev, 0) != hipSuccess) return VCAS_EHIP;
     if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
-    if (!together) VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u, uw, ws));
-    if (!fused)
-        VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
-                           token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, ws));
-    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, ws));
-    return VCAS_OK;
+    return weight_half(s, G, X, rho, nu, rng, token_sampling, pl, dW, workspace, side);
 }
 
 }  // namespace vcas
@@ -341,6 +374,34 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
         return VCAS_EINVAL;
     return linear_backward_impl(*shape, G, X, W, rho, nu, *rng, token_sampling, *plan, dX, dW, workspace,
                                 as_stream(stream), as_stream(side_stream));
+}
+
+vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
+                               const vcas_rng *rng, int32_t token_sampling, const vcas_plan *plan, void *dX,
+                               void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
+    if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (dX && !W) return VCAS_ENULL;
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!ratio_ok(rho)) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || !aligned16(workspace))
+        return VCAS_EINVAL;
+    return data_half(*shape, G, X, W, rho, *rng, token_sampling, *plan, dX, workspace, as_stream(stream));
+}
+
+vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,
+                                 const vcas_rng *rng, int32_t token_sampling, const vcas_plan *plan, float *dW,
+                                 void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
+    if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!ratio_ok(rho) || !ratio_ok(nu)) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(X) || (dW && !aligned16(dW)) || !aligned16(workspace)) return VCAS_EINVAL;
+    return weight_half(*shape, G, X, rho, nu, *rng, token_sampling, *plan, dW, workspace, as_stream(stream));
 }
 
 vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,

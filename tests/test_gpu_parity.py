@@ -311,6 +311,33 @@ def test_results_are_reproducible(vb):
     assert np.array_equal(a[0]["idxW"], b[0]["idxW"])
 
 
+@pytest.mark.parametrize("spec", [
+    workloads.LayerSpec("halves_small", BF16, 8, 128, 768, 264, 0.5, 0.5, layer=3, seed=7, gen_seed=8, token_sigma=0.5),
+    workloads.LayerSpec("halves_f32", F32, 6, 50, 72, 136, 0.6, 0.4, layer=1, seed=2, gen_seed=3, token_sigma=0.5),
+    # rows of X too many bytes for the joint norm launch: the weight half takes the X norms itself
+    workloads.LayerSpec("halves_large", BF16, 12, 300, 4096, 64, 0.5, 0.5, layer=5, seed=9, gen_seed=1, token_sigma=0.5),
+], ids=lambda s: s.name)
+def test_data_and_weight_halves_equal_the_whole(vb, spec):
+    """vcas_backward_data + vcas_backward_weight give the bits of vcas_linear_backward (Sec. 4.1, 4.2)."""
+    from tests.gpu_util import run_layer_gpu, to_device, plan_to_numpy, from_device
+    G, X, W = workloads.make_layer(spec)
+    whole_plan, whole_dX, whole_dW = run_layer_gpu(spec, G, X, W, draw=3)
+    shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+    g, x, w = (to_device(a, spec.dtype) for a in (G, X, W))
+    plan = vb.Plan.allocate(spec.N, spec.T)
+    ws = vb.make_workspace(shape)
+    dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda")
+    dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
+    rng = vb.Rng(spec.seed, spec.layer, 3)
+    vb.vcas_backward_data(shape, g, x, w, spec.rho, rng, True, plan, dX, ws)
+    vb.vcas_backward_weight(shape, g, x, spec.rho, spec.nu, rng, True, plan, dW, ws)
+    torch.cuda.synchronize()
+    halves = plan_to_numpy(plan)
+    for k, v in whole_plan.items():
+        assert np.array_equal(np.asarray(v), np.asarray(halves[k])), k
+    assert np.array_equal(from_device(dX), whole_dX) and np.array_equal(from_device(dW), whole_dW)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_variance_probe_matches_oracle(vb, dtype):
     spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)
