@@ -1,0 +1,127 @@
+"""Parity at the full sizes of the benchmark configurations, launched the way bench.py launches:
+vcas_linear_backward captured in a HIP graph, weight-gradient half on a side stream, draw index
+read from device memory.  The sampling plan is compared bit for bit with the oracle's; dX and dW
+are compared on entries drawn at random (the oracle computes them one by one), and on properties
+that hold everywhere (rows of dropped samples are zero, nothing is left unwritten)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from workloads import BF16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vb():
+    from paper_2402_17227_amd import binding
+    binding.lib()
+    return binding
+
+
+def _cases():
+    specs = workloads.config("bert_base")
+    by_shape = {}
+    for s in specs:
+        by_shape.setdefault((s.K_in, s.K_out), []).append(s)
+    out = []
+    # BERT-base: one layer of each shape from the top (rho near 1), the middle and the bottom (rho 0.3)
+    for shape, ls in sorted(by_shape.items()):
+        out += [ls[0], ls[len(ls) // 2], ls[-1]]
+    for cfg in ("bert_large", "vit_b16", "gpt2_medium"):
+        by_shape = {}
+        for s in workloads.config(cfg):
+            by_shape.setdefault((s.K_in, s.K_out), []).append(s)
+        for shape, ls in sorted(by_shape.items()):
+            out.append(ls[len(ls) // 2])
+    return out
+
+
+@pytest.mark.parametrize("spec", _cases(), ids=lambda s: s.name)
+def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
+    from tests.gpu_util import to_device, plan_to_numpy, compare_plan, rel_l2
+    G, X, W = workloads.make_layer(spec)
+    shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+    g, x, w = (to_device(a, spec.dtype) for a in (G, X, W))
+    plan = vb.Plan.allocate(spec.N, spec.T)
+    ws = vb.make_workspace(shape)
+    dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda")
+    dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
+    counter = torch.zeros(1, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def step():
+        main = torch.cuda.current_stream()
+        counter.add_(1)
+        side.wait_stream(main)
+        vb.vcas_linear_backward(shape, g, x, w, spec.rho, spec.nu, vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()),
+                                True, plan, dX, dW, ws, side)
+        main.wait_stream(side)
+
+    step()                                   # draw 1, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    dX.fill_(float("nan"))
+    dW.fill_(float("nan"))
+    graph.replay()                           # draw 2
+    graph.replay()                           # draw 3
+    torch.cuda.synchronize()
+    draw = int(counter.item())
+    assert draw == 3
+
+    want = oracle.sampling_plan(G, X, spec.dtype, spec.N, spec.T, spec.rho, spec.nu, spec.seed, spec.layer, draw)
+    got = plan_to_numpy(plan)
+    compare_plan(got, want)
+
+    # properties that hold everywhere
+    assert bool(torch.isfinite(dX).all()) and bool(torch.isfinite(dW).all())
+    dropped_rows = torch.from_numpy(np.repeat(want.maskA == 0, spec.T)).cuda()
+    assert bool((dX[dropped_rows] == 0).all())
+
+    # entries drawn at random, computed one by one by the oracle (Eq. 1 upper line; Sec. 4.2)
+    rs = np.random.default_rng(spec.layer + 17)
+    n = 4096
+    kept_rows = np.nonzero(np.repeat(want.maskA == 1, spec.T))[0]
+    if kept_rows.size:
+        rows = rs.choice(kept_rows, n)
+        cols = rs.integers(0, spec.K_in, n)
+        ref = oracle.dgrad_at(G, W, spec.dtype, spec.T, want.p, want.maskA, rows, cols)
+        val = dX[torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()].float().cpu().numpy()
+        assert rel_l2(val, ref) <= 1e-2
+        # no single entry off by more than bf16 rounding plus accumulation noise at the row's scale
+        scale = np.sqrt(np.mean(ref ** 2))
+        assert np.max(np.abs(val - ref) / (np.abs(ref) + scale)) <= 2e-2
+    orow = rs.integers(0, spec.K_out, n)
+    kcol = rs.integers(0, spec.K_in, n)
+    ref = oracle.wgrad_at(G, X, spec.dtype, want.scaleW, orow, kcol)
+    val = dW[torch.from_numpy(orow).cuda(), torch.from_numpy(kcol).cuda()].cpu().numpy()
+    assert rel_l2(val, ref) <= 1e-2
+    scale = np.sqrt(np.mean(ref ** 2))
+    assert np.max(np.abs(val - ref) / (np.abs(ref) + scale)) <= 2e-2
+
+
+def test_variance_probe_at_vit_size_with_eight_draws(vb):
+    """Config 4's probe: N=64, T=197, M=8 draws (Alg. 1's Monte-Carlo lines, Eq. 3)."""
+    from tests.gpu_util import to_device
+    base = workloads.config("vit_b16")[0]
+    spec = workloads.LayerSpec("vit_probe", BF16, base.N, base.T, 768, 768, base.rho, base.nu, layer=7, seed=11,
+                               gen_seed=5, sample_sigma=base.sample_sigma, token_sigma=base.token_sigma)
+    G, X, W = workloads.make_layer(spec)
+    M = 8
+    shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+    plan = vb.Plan.allocate(spec.N, spec.T)
+    ws = vb.make_workspace(shape)
+    out = torch.full((4,), float("nan"), dtype=torch.float64, device="cuda")
+    vb.vcas_variance_probe(shape, to_device(G, BF16), to_device(X, BF16), spec.rho, spec.nu,
+                           vb.Rng(spec.seed, spec.layer, 100), M, plan, out, ws)
+    torch.cuda.synchronize()
+    want = oracle.variance_probe(G, X, BF16, spec.N, spec.T, spec.rho, spec.nu, spec.seed, spec.layer, 100, M)
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[:2], want[:2], rtol=1e-9)
+    np.testing.assert_allclose(got[2:], want[2:], rtol=3e-2)
