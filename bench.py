@@ -66,6 +66,23 @@ def _sample_blocks(specs):
     return {blocks[0], blocks[len(blocks) // 2], blocks[-1]}
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary of this workload
+    (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size); None
+    if no summary covers it.  The counters cannot be read from inside this process."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = [p.strip() for p in line.strip().strip("|").split("|")]
+        if len(parts) >= 2 and parts[0] == f"traffic_bytes_per_launch {kernel}":
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +93,9 @@ def main():
     ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
     ap.add_argument("--side-streams", type=int, default=1, help="streams the weight-gradient halves rotate over")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
+    ap.add_argument("--counters-pass", action="store_true",
+                    help="for a rocprofv3 --pmc run: the sampled steps only, launched eagerly, then one plain 256 MiB "
+                         "device copy whose known size calibrates FETCH_SIZE / WRITE_SIZE; prints no result line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -119,6 +139,14 @@ def main():
     # ---- timed region: K steps of the whole path --------------------------------
     step()                                       # eager once: one-time kernel attribute set-up
     torch.cuda.synchronize()
+    if args.counters_pass:
+        for i in range(args.steps):
+            step()
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        return
     if args.eager:
         run_step = step
     else:                                        # the ~580 launches of a step as one HIP graph
@@ -158,7 +186,7 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
     achieved = flops / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": None, "avg_launch_us": avg_ms * 1e3,
+                "frac": achieved / peak, "traffic": measured_traffic(args.workload, name), "avg_launch_us": avg_ms * 1e3,
                 "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
 
     # ---- dense yardsticks at the same shapes -------------------------------------

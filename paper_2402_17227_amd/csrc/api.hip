@@ -39,12 +39,13 @@ vcas_status plan_fused(const void *G, int K_out, const void *X, int K_in, int dt
                        double budget_w, int token_sampling, const vcas_rng &rng, float *uniforms, uint32_t *ticket,
                        const vcas_plan &pl, hipStream_t st);
 // gemm_bf16.hip / gemm_f32.hip
-int wgrad_tiles_bf16(int K_out, int K_in);
+int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens);
+int wgrad_tiles_bf16(int K_out, int K_in, int tile);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, int64_t expected_rows, hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
+                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
                        hipStream_t st);
 vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                       const int32_t *cntA, void *dX, hipStream_t st);
@@ -52,12 +53,11 @@ vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const f
                       const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st);
 
 // Split-K slices of the weight gradient: about one and a half workgroups per CU (a second one
-// hides the first one's waits; more splits cost reduction traffic), at most 8, and never so many that a slice at full length R would have fewer than 2 (bf16) or 8 (fp32)
-// contraction steps.
-int wgrad_split(const vcas_shape *s)
+// hides the first one's waits; more splits cost reduction traffic), at most 8, and never so many
+// that a slice at full length R would have fewer than 2 (bf16) or 8 (fp32) contraction steps.
+static int wgrad_split_for(const vcas_shape *s, int tiles)
 {
     const bool bf = s->dtype == VCAS_BF16;
-    const int tiles = bf ? wgrad_tiles_bf16(s->K_out, s->K_in) : wgrad_tiles_f32(s->K_out, s->K_in);
     const int64_t R = (int64_t)s->N * s->T;
     const int64_t steps = (R + (bf ? 63 : 15)) / (bf ? 64 : 16);
     int64_t want = (384 + tiles - 1) / tiles;
@@ -66,6 +66,13 @@ int wgrad_split(const vcas_shape *s)
     if (want > 8) want = 8;
     if (want < 1) want = 1;
     return (int)want;
+}
+
+// The most slices any tile choice for this shape uses: sizes the partial-tile area of the workspace.
+int wgrad_split(const vcas_shape *s)
+{
+    return wgrad_split_for(s, s->dtype == VCAS_BF16 ? wgrad_tiles_bf16(s->K_out, s->K_in, 128)
+                                                    : wgrad_tiles_f32(s->K_out, s->K_in));
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t n)
@@ -135,16 +142,21 @@ static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void
                                 : dgrad_f32(s, G, W, p, idxA, cntA, dX, st);
 }
 
+// expected_tokens: how many tokens the caller expects SampleW to keep (R if unknown); it only
+// steers the tile choice.
 static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
                                   const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
-                                  hipStream_t st)
+                                  int64_t expected_tokens, hipStream_t st)
 {
     const WorkspaceLayout w = workspace_layout(&s);
     unsigned char *base = static_cast<unsigned char *>(workspace);
     float *partials = reinterpret_cast<float *>(base + w.partials);
-    const int splits = wgrad_split(&s);
-    return s.dtype == VCAS_BF16 ? wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, splits, st)
-                                : wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, splits, st);
+    if (s.dtype != VCAS_BF16)
+        return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split(&s), st);
+    const int64_t R = (int64_t)s.N * s.T;
+    const int tile = wgrad_tile_bf16(s.K_out, s.K_in, expected_tokens > 0 && expected_tokens < R ? expected_tokens : R);
+    const int splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile));
+    return wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, tile, splits, st);
 }
 
 static bool plan_complete(const vcas_plan *pl)
@@ -213,7 +225,9 @@ static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X
                                          token_sampling ? u : nullptr, st));
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
                        token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
-    if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+    if (dW)
+        VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
+                                (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));
     return VCAS_OK;
 }
 
@@ -232,7 +246,9 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
         VCAS_TRY(plan_fused(G, s.K_out, X, s.K_in, s.dtype, s.N, s.T, (double)s.N * rho, (double)R * rho * nu,
                             token_sampling, rng, uniforms_of(s, workspace), tickets, pl, st));
         if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, (int64_t)((double)R * rho + 0.5), st));
-        if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
+        if (dW)
+            VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
+                                    (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));
         return VCAS_OK;
     }
     if (!forked) {
@@ -356,7 +372,7 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
     if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
     if (!aligned16(G) || !aligned16(X) || !aligned16(dW) || !aligned16(workspace)) return VCAS_EINVAL;
-    return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, as_stream(stream));
+    return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, 0, as_stream(stream));
 }
 
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,

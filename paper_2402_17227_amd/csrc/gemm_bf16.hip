@@ -780,7 +780,18 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
 
 // ---------------------------------------------------------- host launchers
 
-int wgrad_tiles_bf16(int K_out, int K_in) { return ((K_out + 127) / 128) * ((K_in + 127) / 128); }
+// Tile edge of the bf16 weight-gradient GEMM: 128, unless dW has so few 128x128 tiles that filling
+// the chip takes many split-K slices, whose fp32 partial tiles then cost more HBM traffic than
+// the operands (BERT-base: 3 to 8 slices, partials 2 to 4 times dW), and few enough tokens are
+// expected that the matrix cores are not the limit: then 64x64 tiles, four times as many, with a
+// quarter of the slices (1000 kept tokens, 768x3072: 24 vs 28 us and no partials at all).
+int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens)
+{
+    const int tiles128 = ((K_out + 127) / 128) * ((K_in + 127) / 128);
+    return tiles128 <= 160 && expected_tokens <= 2048 ? 64 : 128;
+}
+
+int wgrad_tiles_bf16(int K_out, int K_in, int tile) { return ((K_out + tile - 1) / tile) * ((K_in + tile - 1) / tile); }
 
 template <typename Kern>
 static bool allow_lds(Kern kern, size_t bytes)
@@ -833,17 +844,18 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, st);
 }
 
-vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
-                       hipStream_t st)
+template <int BM, int BN, int WM, int WN, int OCC>
+static vcas_status launch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
+                                const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
+                                hipStream_t st)
 {
-    constexpr int BM = 128, BN = 128, WM = 2, WN = 2, MIN_STEPS = 2;
+    constexpr int MIN_STEPS = 2;
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
     const int tiles = ((s.K_out + BM - 1) / BM) * tiles_n;
     if (splits > 8) splits = 8;
     const size_t lds = 2 * (BM + BN) * 128;
-    auto kern = wgrad_bf16_kernel<BM, BN, WM, WN, 2>;
+    auto kern = wgrad_bf16_kernel<BM, BN, WM, WN, OCC>;
     static bool allowed = false;
     if (!allowed) {
         if (!allow_lds(kern, lds)) return VCAS_EHIP;
@@ -851,10 +863,20 @@ vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const 
     }
     const int grid = (tiles * splits + 7) / 8 * 8;
     launch_timed(1, kern, dim3(grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
-                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out,
-                       tiles_n, tiles, splits, MIN_STEPS);
+                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
+                 tiles, splits, MIN_STEPS);
     if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
+}
+
+// tile: 64 or 128 (wgrad_tile_bf16); splits: as sized by the caller for that tile
+vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
+                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
+                       hipStream_t st)
+{
+    if (tile == 64)
+        return launch_wgrad<64, 64, 2, 1, 2>(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
+    return launch_wgrad<128, 128, 2, 2, 2>(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
 }
 
 }  // namespace vcas
