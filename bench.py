@@ -178,15 +178,23 @@ def main():
     (dg_ms, dg_n), (wg_ms, wg_n) = vb.vcas_profile_end()
     dg_avg, dg_total = dg_ms / max(dg_n, 1), dg_ms / reps
     wg_avg, wg_total = wg_ms / max(wg_n, 1), wg_ms / reps
-    if dg_total >= wg_total:
-        name, avg_ms, flops = "dgrad_bf16_kernel", dg_avg, kept_rows / len(layers)
-    else:
-        name, avg_ms, flops = "wgrad_bf16_kernel", wg_avg, kept_toks / len(layers)
     bf16 = specs[0].dtype == workloads.BF16
+    e = 2 if bf16 else 4
+    sfx = "bf16" if bf16 else "f32"
+    # algorithmic HBM bytes per launch: kept operand rows once, W resp. dW once, all of dX (zeros included)
+    dg_bytes = sum(int(l.plan.cntA.item()) * l.spec.T * l.spec.K_out * e + l.spec.K_in * l.spec.K_out * e
+                   + l.spec.R * l.spec.K_in * e for l in layers) / len(layers)
+    wg_bytes = sum(int(l.plan.cntW.item()) * (l.spec.K_out + l.spec.K_in) * e + 4 * l.spec.K_in * l.spec.K_out
+                   for l in layers) / len(layers)
+    if dg_total >= wg_total:
+        name, avg_ms, flops, alg_bytes = f"dgrad_{sfx}_kernel", dg_avg, kept_rows / len(layers), dg_bytes
+    else:
+        name, avg_ms, flops, alg_bytes = f"wgrad_{sfx}_kernel", wg_avg, kept_toks / len(layers), wg_bytes
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
     achieved = flops / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": measured_traffic(args.workload, name), "avg_launch_us": avg_ms * 1e3,
+                "frac": achieved / peak, "traffic": measured_traffic(args.workload, name),
+                "algorithmic_bytes": alg_bytes, "avg_launch_us": avg_ms * 1e3,
                 "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
 
     # ---- dense yardsticks at the same shapes -------------------------------------
