@@ -12,26 +12,39 @@ namespace vcas {
 // the neighbours-first tree, then the 16 group sums by the same kind of tree.
 // Every thread returns the totals.  `bufd` / `bufi` are 16 values of LDS each;
 // calls must alternate buffers or be separated by a barrier.
-__device__ __forceinline__ void block_sum_pair_1024(double v, int c, double *bufd, int *bufi, double &sum_v, int &sum_c)
+// `c_wave` is the wavefront's count, already the same in all its lanes.
+__device__ __forceinline__ void block_totals_1024(double v, int c_wave, double *bufd, int *bufi, double &sum_v,
+                                                  int &sum_c)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     v = wave_exchange_sum(v);
-    c = wave_sum_int(c);
     if (lane == 0) {
         bufd[wave] = v;
-        bufi[wave] = c;
+        bufi[wave] = c_wave;
     }
     __syncthreads();
-    double wd[16];
-    int total = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        wd[i] = bufd[i];
-        total += bufi[i];
-    }
-    sum_v = tree16(wd);
-    sum_c = total;
+    // every 16-lane row holds the 16 partials, one per lane, and adds them by the same tree
+    // (quad swaps, then the two mirrors) instead of every lane reading and adding all 16
+    double w = bufd[lane & 15];
+    int c = bufi[lane & 15];
+    w = w + dpp_move<0xB1>(w);
+    w = w + dpp_move<0x4E>(w);
+    w = w + dpp_move<0x141>(w);
+    w = w + dpp_move<0x140>(w);
+    c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);
+    c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);
+    c += __builtin_amdgcn_update_dpp(0, c, 0x141, 0xF, 0xF, true);
+    c += __builtin_amdgcn_update_dpp(0, c, 0x140, 0xF, 0xF, true);
+    sum_v = read_lane(w, 0);
+    sum_c = __builtin_amdgcn_readlane(c, 0);
 }
+
+__device__ __forceinline__ void block_sum_pair_1024(double v, int c, double *bufd, int *bufi, double &sum_v, int &sum_c)
+{
+    block_totals_1024(v, wave_sum_int(c), bufd, bufi, sum_v, sum_c);
+}
+
+__device__ __forceinline__ int ballot_count(bool c) { return __builtin_popcountll(__ballot(c)); }
 
 // prob_i = min(1, c * score_i), sum prob = min(budget, #positive scores).
 // c is found by rounds: every not-yet-fixed entry that the current c pushes to
@@ -218,16 +231,16 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
     __shared__ double sd[2][16];
     __shared__ int si[2][16];
     double part = 0.0;
-    int cnt = 0;
+    int cnt = 0;   // per wavefront, from ballots (scalar work, beside the vector sums)
 #pragma unroll
-    for (int j = 0; j < E; ++j)
-        if (a[j] > 0.0f) {
-            part += (double)a[j];
-            ++cnt;
-        }
+    for (int j = 0; j < E; ++j) {
+        const bool pos = a[j] > 0.0f;
+        if (pos) part += (double)a[j];
+        cnt += ballot_count(pos);
+    }
     double S;
     int nonzero;
-    block_sum_pair_1024(part, cnt, sd[0], si[0], S, nonzero);
+    block_totals_1024(part, cnt, sd[0], si[0], S, nonzero);
     if (budget >= (double)nonzero) {
 #pragma unroll
         for (int j = 0; j < E; ++j) prob[j] = a[j] > 0.0f ? 1.0f : 0.0f;
@@ -247,18 +260,16 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
         part = 0.0;
         cnt = 0;
 #pragma unroll
-        for (int j = 0; j < E; ++j)
-            if (a[j] > 0.0f && !((fixed >> j) & 1u)) {
-                if (c * (double)a[j] >= 1.0) {
-                    fixed |= 1u << j;
-                    ++cnt;
-                } else {
-                    part += (double)a[j];
-                }
-            }
+        for (int j = 0; j < E; ++j) {
+            const bool open = a[j] > 0.0f && !((fixed >> j) & 1u);
+            const bool cap = open && c * (double)a[j] >= 1.0;
+            if (cap) fixed |= 1u << j;
+            if (open && !cap) part += (double)a[j];
+            cnt += ballot_count(cap);
+        }
         double S_next;
         int newly;
-        block_sum_pair_1024(part, cnt, sd[flip], si[flip], S_next, newly);
+        block_totals_1024(part, cnt, sd[flip], si[flip], S_next, newly);
         flip ^= 1;
         if (newly == 0) break;
         ncap += newly;
@@ -276,6 +287,59 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
     }
 }
 
+// Ascending list of the kept indices and their count for the register layout of the fused
+// samplers: element j of thread tid is index tid + 1024 j, so ascending order is j, then
+// wavefront, then lane.  Every wavefront counts its kept lanes per j with a ballot; the first
+// wavefront turns the 16 E counts into bases; a lane's position is its base plus the kept lanes
+// below it.
+template <int E>
+__device__ __forceinline__ void compact_regs(const bool (&m)[E], int32_t *__restrict__ idx,
+                                             int32_t *__restrict__ count)
+{
+    constexpr int CNT = 16 * E, PER = (CNT + 63) / 64;
+    __shared__ int counts[CNT + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint64_t b[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) b[j] = __ballot(m[j]);
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) counts[j * 16 + wave] = __builtin_popcountll(b[j]);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // lane L owns counts PER*L .. PER*L+PER-1; exclusive prefix of all of them, in place
+        int c[PER], mine = 0;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            c[q] = PER * lane + q < CNT ? counts[PER * lane + q] : 0;
+            mine += c[q];
+        }
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += up;
+        }
+        int run = incl - mine;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            if (PER * lane + q < CNT) counts[PER * lane + q] = run;
+            run += c[q];
+        }
+        if (lane == 63) counts[CNT] = incl;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const int base = counts[j * 16 + wave];
+        const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(b[j] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b[j], 0u));
+        if (m[j]) idx[base + below] = (int)threadIdx.x + 1024 * j;
+    }
+    if (threadIdx.x == 0) *count = counts[CNT];
+}
+
 // SampleA for N <= 1024 with every intermediate in LDS or registers (one workgroup of 1024).
 __device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gsq, int N, int T, double budget,
                                                     uint64_t seed, uint32_t layer, uint32_t draw,
@@ -285,7 +349,6 @@ __device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gs
                                                     int32_t *__restrict__ cntA)
 {
     __shared__ float gn[1024];
-    __shared__ uint8_t mk[1024];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (draw_offset) draw += *draw_offset;
     for (int i = wave; i < N; i += 16) {
@@ -296,19 +359,67 @@ __device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gs
         if (lane == 0) gn[i] = __builtin_sqrtf(acc);
     }
     __syncthreads();
+    if (N <= 64) {
+        // Every entry lies in the first 64 summation slots: the other fifteen group sums are +0
+        // and x + 0 = x, so the first wavefront does the rounds alone, with no LDS and no barriers.
+        if (wave != 0) return;
+        const float a = lane < N ? gn[lane] : 0.0f;
+        const bool pos = a > 0.0f;
+        double S = wave_exchange_sum(pos ? (double)a : 0.0);
+        const int nonzero = ballot_count(pos);
+        float pr = 0.0f;
+        if (budget >= (double)nonzero) {
+            pr = pos ? 1.0f : 0.0f;
+        } else {
+            bool fixed = false;
+            int ncap = 0;
+            double c = 0.0;
+            for (;;) {
+                const double rem = budget - (double)ncap;
+                if (!(S > 0.0) || !(rem > 0.0)) {
+                    c = 0.0;
+                    break;
+                }
+                c = rem / S;
+                const bool open = pos && !fixed;
+                const bool cap = open && c * (double)a >= 1.0;
+                fixed = fixed || cap;
+                const int newly = ballot_count(cap);
+                const double S_next = wave_exchange_sum(open && !cap ? (double)a : 0.0);
+                if (newly == 0) break;
+                ncap += newly;
+                S = S_next;
+            }
+            if (fixed) pr = 1.0f;
+            else if (pos) {
+                pr = (float)(c * (double)a);
+                pr = pr < 1.0f ? pr : 1.0f;
+            }
+        }
+        bool m = false;
+        if (lane < N) {
+            m = philox_uniform(seed, layer, 0u, draw, (uint32_t)lane) < pr;
+            gnorm[lane] = a;
+            p[lane] = pr;
+            maskA[lane] = m ? 1 : 0;
+        }
+        const uint64_t kept = __ballot(m);
+        const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+        if (m) idxA[below] = lane;
+        if (lane == 0) *cntA = __builtin_popcountll(kept);
+        return;
+    }
     float a[1], pr[1];
     a[0] = tid < N ? gn[tid] : 0.0f;
     keep_probs_regs<1>(a, budget, pr);
-    uint8_t m = 0;
+    bool m[1] = {false};
     if (tid < N) {
-        m = philox_uniform(seed, layer, 0u, draw, (uint32_t)tid) < pr[0] ? 1 : 0;
+        m[0] = philox_uniform(seed, layer, 0u, draw, (uint32_t)tid) < pr[0];
         gnorm[tid] = a[0];
         p[tid] = pr[0];
-        maskA[tid] = m;
+        maskA[tid] = m[0] ? 1 : 0;
     }
-    mk[tid] = m;
-    __syncthreads();
-    compact_block(mk, N, idxA, cntA);
+    compact_regs<1>(m, idxA, cntA);
 }
 
 __global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__restrict__ gsq, int N, int T,
@@ -331,7 +442,6 @@ __device__ __forceinline__ void sampler_w_fast_body(const float *__restrict__ gs
                                                     uint8_t *__restrict__ maskW, float *__restrict__ scaleW,
                                                     int32_t *__restrict__ idxW, int32_t *__restrict__ cntW)
 {
-    __shared__ uint8_t mk[1024 * E];
     const int tid = threadIdx.x;
     const int R = N * T;
     float a[E], qv[E], pinv_src[E], uu[E];
@@ -365,20 +475,19 @@ __device__ __forceinline__ void sampler_w_fast_body(const float *__restrict__ gs
 #pragma unroll
         for (int j = 0; j < E; ++j) qv[j] = keepA[j] ? 1.0f : 0.0f;
     }
+    bool m[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const int t = tid + 1024 * j;
-        uint8_t m = 0;
+        m[j] = false;
         if (t < R) {
-            m = token_sampling ? (uu[j] < qv[j] ? 1 : 0) : (keepA[j] ? 1 : 0);
+            m[j] = token_sampling ? uu[j] < qv[j] : keepA[j] != 0;
             q[t] = qv[j];
-            maskW[t] = m;
-            scaleW[t] = m ? 1.0f / (pinv_src[j] * qv[j]) : 0.0f;
+            maskW[t] = m[j] ? 1 : 0;
+            scaleW[t] = m[j] ? 1.0f / (pinv_src[j] * qv[j]) : 0.0f;
         }
-        mk[t] = m;
     }
-    __syncthreads();
-    compact_block(mk, R, idxW, cntW);
+    compact_regs<E>(m, idxW, cntW);
 }
 
 template <int E>
