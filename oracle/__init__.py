@@ -296,3 +296,71 @@ def variance_probe(G, X, dtype: int, N: int, T: int, rho: float, nu: float,
         out[2] += sq_diff(wgrad(G, X, dtype, planA.scaleW), exact) / M
         out[3] += sq_diff(wgrad(G, X, dtype, plan.scaleW), exact) / M
     return out
+
+
+# ---- adaptive keep ratios (Sec. 5, Alg. 1, App. D) ---------------------------------------------
+
+def sparsity_ratio(gnorm, s: float) -> float:
+    """Eq. 4: smallest fraction n/N of the largest sample norms that holds the share s of their sum."""
+    gnorm = _check(gnorm, F32)
+    fn = _L().orc_sparsity_ratio
+    fn.restype = C.c_float
+    return float(fn(_p(gnorm), C.c_int(gnorm.size), C.c_double(s)))
+
+
+def grad_stats_update(grad, stride: int, i: int, mean, sqmean) -> None:
+    """App. D's running mean / running square mean over every stride-th gradient entry, in place."""
+    grad = _check(np.asarray(grad).reshape(-1), F32)
+    assert mean.dtype == np.float32 and sqmean.dtype == np.float32 and mean.size == sqmean.size
+    assert (mean.size - 1) * stride < grad.size
+    _L().orc_grad_stats_update(_p(grad), C.c_int64(mean.size), C.c_int64(stride), C.c_int(i), _p(mean), _p(sqmean))
+
+
+def grad_stats_variance(mean, sqmean, M: int) -> float:
+    fn = _L().orc_grad_stats_variance
+    fn.restype = C.c_double
+    return float(fn(_p(_check(mean, F32)), _p(_check(sqmean, F32)), C.c_int64(mean.size), C.c_int(M)))
+
+
+def sq_diff_strided(a, b, m: int, stride: int) -> float:
+    fn = _L().orc_sq_diff_strided
+    fn.restype = C.c_double
+    a = _check(np.asarray(a).reshape(-1), F32)
+    b = _check(np.asarray(b).reshape(-1), F32)
+    return float(fn(_p(a), _p(b), C.c_int64(m), C.c_int64(stride)))
+
+
+@dataclass
+class ControllerParams:
+    """Alg. 1's inputs.  beta < 1 is the paper's setting (0.95)."""
+    alpha: float = 0.01
+    beta: float = 0.95
+    tau_act: float = 0.025
+    tau_w: float = 0.025
+    nu_min: float = 1.0 / 1024.0
+
+
+def controller_update(prm: ControllerParams, s: float, nu, V_s: float, V_act: float, V_w, V_s_layer,
+                      p_minus, p_plus):
+    """One update of Alg. 1 (the lines after the Monte-Carlo loops).  Layers are ordered from the
+    input (index 0) to the output; p_minus / p_plus are Eq. 4 evaluated, per layer, at s - alpha and
+    s + alpha inside the loops and averaged (App. D).  Returns (s', rho', nu').
+
+    Eq. 5: s' = s + alpha * sign(V_act - tau_act * V_s), sign(0) = +1, kept inside [0, 1].
+    Eq. 4: rho'_l = max_{j <= l} p_j(s'), with p_j(s') taken from the side s actually moved to.
+    Eq. 7 as printed multiplies nu_l by beta^{sign(.)}, which with beta < 1 lowers the keep ratio when
+    the variance is too high; the reading taken here raises it: nu'_l = nu_l * beta^{-sign(V_w,l -
+    tau_w V_s,l)}, kept inside [nu_min, 1]."""
+    up = (V_act - prm.tau_act * V_s) >= 0.0
+    s_new = min(1.0, max(0.0, s + (prm.alpha if up else -prm.alpha)))
+    p = np.asarray(p_plus if up else p_minus, np.float64)
+    rho = np.maximum.accumulate(p)
+    rho = np.minimum(1.0, rho)
+    nu = np.asarray(nu, np.float64).copy()
+    V_w = np.asarray(V_w, np.float64)
+    V_s_layer = np.asarray(V_s_layer, np.float64)
+    for l in range(nu.size):
+        too_high = (V_w[l] - prm.tau_w * V_s_layer[l]) >= 0.0
+        nu[l] = nu[l] / prm.beta if too_high else nu[l] * prm.beta
+        nu[l] = min(1.0, max(prm.nu_min, nu[l]))
+    return s_new, rho, nu

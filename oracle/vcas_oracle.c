@@ -450,3 +450,75 @@ double orc_sq_diff(const double *a, const double *b, int64_t n)
     }
     return v;
 }
+
+/* ------------------------------------------- adaptive keep ratios (Sec. 5) */
+
+static int cmp_desc(const void *a, const void *b)
+{
+    float x = *(const float *)a, y = *(const float *)b;
+    return (x < y) - (x > y);
+}
+
+/* Eq. 4: the gradient-norm sparsity of a layer at level s,
+ *   p(s) = min { n/N : sum of the n LARGEST norms >= s * sum of all norms },  n >= 1.
+ * The paper does not say "largest"; a sparsity measure needs the norms in
+ * descending order.  Sums run in fp64 over the sorted sequence, one after the
+ * other, so the last prefix equals the total and n = N always qualifies. */
+float orc_sparsity_ratio(const float *gnorm, int N, double s)
+{
+    float *v = (float *)malloc(sizeof(float) * (size_t)N);
+    memcpy(v, gnorm, sizeof(float) * (size_t)N);
+    qsort(v, (size_t)N, sizeof(float), cmp_desc);
+    double total = 0.0;
+    for (int i = 0; i < N; ++i) total += (double)v[i];
+    const double target = s * total;
+    double prefix = 0.0;
+    int n = N;
+    for (int i = 0; i < N; ++i) {
+        prefix += (double)v[i];
+        if (prefix >= target) {
+            n = i + 1;
+            break;
+        }
+    }
+    free(v);
+    return (float)n / (float)N;
+}
+
+/* Running mean and running mean of squares of a strided subset of a gradient
+ * (App. D keeps exactly these two tensors for the SGD variance V_s): after the
+ * call with 1-based index i they hold the statistics of gradients 1..i.
+ *   mean   <- mean   + (x   - mean)   / i
+ *   sqmean <- sqmean + (x*x - sqmean) / i        (fp32, each operation rounded) */
+void orc_grad_stats_update(const float *grad, int64_t m, int64_t stride, int i, float *mean, float *sqmean)
+{
+    const float fi = (float)i;
+    for (int64_t j = 0; j < m; ++j) {
+        const float x = grad[j * stride];
+        const float d = x - mean[j];
+        mean[j] = mean[j] + d / fi;
+        const float xx = x * x;
+        const float e = xx - sqmean[j];
+        sqmean[j] = sqmean[j] + e / fi;
+    }
+}
+
+/* Alg. 1's V_s from the two running tensors of M gradients:
+ *   1/(M-1) sum_i ||g_i - gbar||^2 = M/(M-1) sum_j (sqmean_j - mean_j^2),  fp64. */
+double orc_grad_stats_variance(const float *mean, const float *sqmean, int64_t m, int M)
+{
+    double v = 0.0;
+    for (int64_t j = 0; j < m; ++j) v += (double)sqmean[j] - (double)mean[j] * (double)mean[j];
+    return v * (double)M / (double)(M - 1);
+}
+
+/* ||a - b||^2 over the same strided subset (Alg. 1's V_act line on the kept parameters). */
+double orc_sq_diff_strided(const float *a, const float *b, int64_t m, int64_t stride)
+{
+    double v = 0.0;
+    for (int64_t j = 0; j < m; ++j) {
+        const double d = (double)a[j * stride] - (double)b[j * stride];
+        v += d * d;
+    }
+    return v;
+}
