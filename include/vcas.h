@@ -234,6 +234,61 @@ vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const vo
                                 double *out, void *workspace, void *stream);
 
 /*
+ * Adaptive keep ratios (Sec. 5).  One update of Alg. 1 needs, besides the probe
+ * above: Eq. 4's gradient-norm sparsity of every layer at s - alpha and
+ * s + alpha, the SGD variance V_s from the running mean and running mean of
+ * squares that App. D keeps on a subset of the parameters, the squared
+ * difference of V_act on the same subset, and the update rules themselves.
+ *
+ * vcas_sparsity_ratio: Eq. 4, p(s) = min{ n/N : the n largest of gnorm[N] sum to
+ * at least s times the sum of all }, n >= 1 (the paper leaves "largest" unsaid;
+ * fp64 sums over the norms in descending order).  s: HOST array of ns <= 8 levels
+ * in [0,1]; p: device [ns].  N <= 1024.
+ */
+vcas_status vcas_sparsity_ratio(const float *gnorm, int32_t N, const double *s, int32_t ns, float *p,
+                                void *stream);
+
+/*
+ * App. D's running statistics over entries 0, stride, 2*stride, ... of a
+ * gradient (m entries): after the call with index i = 1, 2, ... `mean` and
+ * `sqmean` (device [m], zero before i = 1) hold the mean and the mean of squares
+ * of the first i gradients (fp32: mean += (x - mean)/i, sqmean += (x*x - sqmean)/i).
+ * vcas_grad_stats_variance: Alg. 1's V_s = 1/(M-1) sum_i ||g_i - gbar||^2
+ * = M/(M-1) sum_j (sqmean_j - mean_j^2), fp64, into out[0] (device).
+ * vcas_sq_diff_strided: out[0] = (accumulate ? out[0] : 0) + weight * sum over
+ * the same subset of (a - b)^2 (Alg. 1's V_act line on the kept parameters).
+ */
+vcas_status vcas_grad_stats_update(const float *grad, int64_t m, int64_t stride, int32_t i, float *mean,
+                                   float *sqmean, void *stream);
+vcas_status vcas_grad_stats_variance(const float *mean, const float *sqmean, int64_t m, int32_t M,
+                                     double *out, void *stream);
+vcas_status vcas_sq_diff_strided(const float *a, const float *b, int64_t m, int64_t stride, double weight,
+                                 int32_t accumulate, double *out, void *stream);
+
+/*
+ * The update rules of Alg. 1, HOST arithmetic on HOST pointers (nothing is
+ * launched).  Layers 0..L-1 run from the input to the output.
+ *   Eq. 5: *s += alpha * sign(V_act - tau_act * V_s), sign(0) = +1, kept in [0,1];
+ *   Eq. 4: rho[l] = max_{j <= l} p_j, with p_j = p_plus[j] if s went up, else
+ *          p_minus[j] (App. D: both sides are measured inside the loops);
+ *   Eq. 7: nu[l] *= beta^{-sign(V_w[l] - tau_w * V_s_layer[l])}, kept in [nu_min, 1].
+ *          As printed (beta^{+sign}, beta < 1) the rule would lower the keep ratio
+ *          when the variance is too high; the sign is read so that it raises it.
+ * Requires 0 < beta < 1, alpha > 0, 0 < nu_min <= 1.
+ */
+typedef struct {
+    double alpha;   /* step of s                         */
+    double beta;    /* multiplier of nu, in (0,1)         */
+    double tau_act; /* tolerated V_act / V_s              */
+    double tau_w;   /* tolerated V_w,l / V_s,l            */
+    double nu_min;  /* floor of the token keep ratio      */
+} vcas_controller_params;
+
+vcas_status vcas_controller_update(const vcas_controller_params *prm, int32_t L, double *s, double *rho,
+                                   double *nu, double V_s, double V_act, const double *V_w,
+                                   const double *V_s_layer, const double *p_minus, const double *p_plus);
+
+/*
  * Profiling aid, not part of the method: between vcas_profile_begin and
  * vcas_profile_end every dgrad / wgrad GEMM launch (Eq. 1 upper line resp.
  * Sec. 4.2's grad_W) is bracketed by HIP events stamped by the kernel's own

@@ -19,7 +19,8 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_weight", "vcas_variance_probe", "vcas_profile_begin", "vcas_profile_end",
+    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
+    "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
 ]
 
 
@@ -203,6 +204,46 @@ def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M:
     _check(lib().vcas_variance_probe(C.byref(shape), _ptr(G), _ptr(X), C.c_double(rho), C.c_double(nu),
                                      C.byref(base), C.c_int32(M), C.byref(ptrs), _ptr(out), _ptr(workspace),
                                      _stream()), "vcas_variance_probe")
+
+
+def vcas_sparsity_ratio(gnorm, levels, p):
+    """levels: host sequence of at most 8 values of s; p: device float tensor of that length."""
+    arr = (C.c_double * len(levels))(*[float(v) for v in levels])
+    _check(lib().vcas_sparsity_ratio(_ptr(gnorm), C.c_int32(gnorm.numel()), arr, C.c_int32(len(levels)), _ptr(p),
+                                     _stream()), "vcas_sparsity_ratio")
+
+
+def vcas_grad_stats_update(grad, m: int, stride: int, i: int, mean, sqmean):
+    _check(lib().vcas_grad_stats_update(_ptr(grad), C.c_int64(m), C.c_int64(stride), C.c_int32(i), _ptr(mean),
+                                        _ptr(sqmean), _stream()), "vcas_grad_stats_update")
+
+
+def vcas_grad_stats_variance(mean, sqmean, M: int, out):
+    _check(lib().vcas_grad_stats_variance(_ptr(mean), _ptr(sqmean), C.c_int64(mean.numel()), C.c_int32(M), _ptr(out),
+                                          _stream()), "vcas_grad_stats_variance")
+
+
+def vcas_sq_diff_strided(a, b, m: int, stride: int, weight: float, accumulate: bool, out):
+    _check(lib().vcas_sq_diff_strided(_ptr(a), _ptr(b), C.c_int64(m), C.c_int64(stride), C.c_double(weight),
+                                      C.c_int32(1 if accumulate else 0), _ptr(out), _stream()), "vcas_sq_diff_strided")
+
+
+class ControllerParams(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("beta", C.c_double), ("tau_act", C.c_double), ("tau_w", C.c_double),
+                ("nu_min", C.c_double)]
+
+
+def vcas_controller_update(prm: ControllerParams, s: float, nu, V_s: float, V_act: float, V_w, V_s_layer, p_minus,
+                           p_plus):
+    """Host arithmetic only.  Returns (s', rho' list, nu' list)."""
+    L = len(nu)
+    vec = lambda v: (C.c_double * L)(*[float(x) for x in v])
+    s_io = C.c_double(s)
+    rho, nu_io = (C.c_double * L)(), vec(nu)
+    _check(lib().vcas_controller_update(C.byref(prm), C.c_int32(L), C.byref(s_io), rho, nu_io, C.c_double(V_s),
+                                        C.c_double(V_act), vec(V_w), vec(V_s_layer), vec(p_minus), vec(p_plus)),
+           "vcas_controller_update")
+    return s_io.value, list(rho), list(nu_io)
 
 
 def vcas_profile_begin():
