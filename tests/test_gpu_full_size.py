@@ -38,6 +38,7 @@ def _cases():
             by_shape.setdefault((s.K_in, s.K_out), []).append(s)
         for shape, ls in sorted(by_shape.items()):
             out.append(ls[len(ls) // 2])
+    out += [s for s in workloads.config("bert_base_fused_qkv") if s.name.endswith(".b5.qkv")]   # 768 -> 2304
     return out
 
 

@@ -71,13 +71,16 @@ def make_layer(spec: LayerSpec):
 
 
 def _stack(name, dtype, N, T, hidden, ffn, blocks, rho_top, rho_bottom, nu,
-           sample_sigma, token_sigma, gen_seed=0, seed=0):
+           sample_sigma, token_sigma, gen_seed=0, seed=0, fused_qkv=False):
     """Encoder-style stack: per block Q, K, V, out-proj (h->h), FFN up (h->ffn),
     FFN down (ffn->h).  Block `blocks-1` is the top (nearest the loss); the data
     keep ratio is interpolated linearly from rho_top there to rho_bottom at
-    block 0, and is shared by the six linears of a block."""
+    block 0, and is shared by the six linears of a block.  fused_qkv: the three
+    projections as one h->3h linear under a single SampleA mask."""
     shapes = [("q", hidden, hidden), ("k", hidden, hidden), ("v", hidden, hidden),
               ("o", hidden, hidden), ("up", hidden, ffn), ("down", ffn, hidden)]
+    if fused_qkv:
+        shapes = [("qkv", hidden, 3 * hidden)] + shapes[3:]
     out = []
     for b in range(blocks):
         f = b / (blocks - 1) if blocks > 1 else 1.0
@@ -97,6 +100,8 @@ def config(name: str):
                           sample_sigma=1.0)]
     if name == "bert_base":
         ls = _stack("bert_base", BF16, 32, 128, 768, 3072, 12, 1.0, 0.3, 0.5, 1.0, 0.5)
+    elif name == "bert_base_fused_qkv":
+        ls = _stack("bert_base_fused_qkv", BF16, 32, 128, 768, 3072, 12, 1.0, 0.3, 0.5, 1.0, 0.5, fused_qkv=True)
     elif name == "bert_large":
         ls = _stack("bert_large", BF16, 32, 512, 1024, 4096, 24, 1.0, 0.25, 0.4, 1.0, 0.5)
     elif name == "vit_b16":
@@ -112,7 +117,7 @@ def config(name: str):
     return sorted(ls, key=lambda s: -s.layer)
 
 
-CONFIG_NAMES = ["single_fp32", "bert_base", "bert_large", "vit_b16", "gpt2_medium"]
+CONFIG_NAMES = ["single_fp32", "bert_base", "bert_large", "vit_b16", "gpt2_medium", "bert_base_fused_qkv"]
 
 
 def small_cases():
