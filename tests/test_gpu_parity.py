@@ -338,6 +338,44 @@ def test_data_and_weight_halves_equal_the_whole(vb, spec):
     assert np.array_equal(from_device(dX), whole_dX) and np.array_equal(from_device(dW), whole_dW)
 
 
+def test_chained_layers_keep_dropped_samples_dropped(vb):
+    """Three linears in a row, each layer's dX (kept rows scaled, dropped rows zero) serving as the G of
+    the layer below (Sec. 3: the activation gradient grows sparser layer by layer, rho_l monotone).  Each
+    layer is compared with the oracle on the very tensor the GPU fed it, and the kept sets must nest:
+    a sample dropped above has zero norm below, hence p = 0 and no token of it is ever kept."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    N, T, K = 24, 40, 136
+    rhos, nu = [0.8, 0.6, 0.4], 0.5                      # top layer first
+    rng = np.random.default_rng(7)
+    top = workloads.LayerSpec("chain", BF16, N, T, K, K, rhos[0], nu, layer=0, seed=3, gen_seed=21, token_sigma=0.5)
+    G_host, _, _ = workloads.make_layer(top)
+    g = to_device(G_host, BF16)
+    shape = vb.shape_of(N, T, K, K, BF16)
+    kept_above = np.ones(N, bool)
+    for l, rho in enumerate(rhos):
+        X_host = workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32))
+        W_host = workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32))
+        x, w = to_device(X_host, BF16), to_device(W_host, BF16)
+        plan = vb.Plan.allocate(N, T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dW = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
+        vb.vcas_linear_backward(shape, g, x, w, rho, nu, vb.Rng(3, l, 0), True, plan, dX, dW, ws)
+        torch.cuda.synchronize()
+        G_fed = g.view(torch.int16).cpu().numpy().view(np.uint16)          # what this layer actually got
+        want, want_dX, want_dW = oracle.linear_backward(G_fed, X_host, W_host, BF16, N, T, rho, nu, 3, l, 0)
+        got = plan_to_numpy(plan)
+        compare_plan(got, want)
+        assert rel_l2(from_device(dX), want_dX) <= TOL[BF16] and rel_l2(from_device(dW), want_dW) <= TOL[BF16]
+        kept = got["maskA"].astype(bool)
+        assert not np.any(kept & ~kept_above)                              # nested kept sets
+        assert np.all(got["p"][~kept_above] == 0) and np.all(got["gnorm"][~kept_above] == 0)
+        assert np.all(got["q"][np.repeat(~kept_above, T)] == 0)
+        kept_above = kept
+        g = dX                                                             # Jacobian of the identity in between
+    assert kept_above.sum() < N                                            # something was dropped on the way
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_variance_probe_matches_oracle(vb, dtype):
     spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)
