@@ -778,6 +778,201 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
         }
 }
 
+// The 128x128 weight-gradient kernel for layers with many kept tokens.  Same split-K protocol
+// and epilogue as above, different data path: X goes straight into LDS (LDS-direct loads, as in
+// dgrad), G passes through registers only to be multiplied by the per-token scale and is written
+// as it came, 16 bytes per lane; both tiles lie in LDS as [64 tokens][128 columns] with the
+// 16-byte slots swizzled by wswz, and both MFMA operands are transposed on the way out by
+// ds_read_b64_tr_b16.  No v_perm transposes, half the staging registers.  A thread handles four
+// consecutive kept tokens (one 16-byte index load); they occupy LDS rows 4 apart, which is fine
+// because both tiles use the same row order and the contraction does not care about it.
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_kernel(
+    const uint16_t *__restrict__ G, const uint16_t *__restrict__ X, const float *__restrict__ row_scale,
+    const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW, float *__restrict__ dW,
+    float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles, int splits, int min_steps)
+{
+    static_assert(BM == 128 && BN == 128 && WM * WN == 4, "four wavefronts, 16 slots per tile row");
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_TILE = BK * BM * 2, STAGE = A_TILE + BK * BN * 2, PITCH = 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int total = tiles * splits;
+    const int id = xcd_remap(blockIdx.x, total);
+    if (id >= total) return;
+    const int split = id / tiles, tile = id % tiles;
+    int tile_o, tile_c;
+    panel_order<4>(tile, tiles / tiles_n, tiles_n, tile_o, tile_c);
+    const int o0 = tile_o * BM, c0 = tile_c * BN;
+
+    const int64_t cnt = min((int64_t)max(*cntW, 0), R);
+    const int steps_all = (int)((cnt + BK - 1) / BK);
+    int per;
+    const int active = wgrad_active_splits(steps_all, splits, min_steps, per);
+    if (split >= active) return;
+    const int s_begin = split * per, s_end = min(steps_all, s_begin + per);
+    const int steps = s_end - s_begin;
+    const int64_t k_end = min(cnt, (int64_t)s_end * BK);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, slot = lane & 15;        // row within a 4-row load, 16-byte slot
+    const int k_first = 16 * wave + 4 * grp;            // this thread's tokens of a step: k_first + j, j < 4
+    // token k_first + j lives in LDS row 16*wave + 4*j + grp
+    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
+    const __amdgpu_buffer_rsrc_t rsrcI = make_rsrc(idxW, (uint32_t)(R * 4));
+    const __amdgpu_buffer_rsrc_t rsrcS = make_rsrc(row_scale, (uint32_t)(R * 4));
+    const i32x4 descX = raw_descriptor(X, (uint32_t)(R * K_in * 2));
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const uint32_t g_pitch = (uint32_t)K_out * 2u, x_pitch = (uint32_t)K_in * 2u;
+    const int g_col = o0 + slot * 8;
+    const bool g_inside = g_col < K_out;
+    // column piece of X that lands in LDS slot `slot` of row r: slot ^ wswz(r); r & 3 == grp for all four rows
+    const int x_col = c0 + ((slot ^ wswz(grp)) * 8);
+    const bool x_inside = x_col < K_in;
+
+    struct Tokens {
+        int32_t tok[4];
+    };
+    auto fetch_tokens = [&](int step) {
+        const int64_t k0 = (int64_t)(s_begin + step) * BK + k_first;
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcI, k0 < k_end ? (int)(k0 * 4) : (int)kOutside, 0, 0);
+        Tokens t;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int32_t r = (int32_t)v[j];
+            t.tok[j] = (k0 + j < k_end && (uint32_t)r < (uint32_t)R) ? r : -1;
+        }
+        return t;
+    };
+    auto fetch_scales = [&](const Tokens &t, float (&sc)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            sc[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                  rsrcS, t.tok[j] >= 0 ? t.tok[j] * 4 : (int)kOutside, 0, 0));
+    };
+    uint4 g_regs[4];
+    auto load_g = [&](const Tokens &t) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            g_regs[j] = buffer_load16(rsrcG, (t.tok[j] >= 0 && g_inside)
+                                                 ? __umul24((uint32_t)t.tok[j], g_pitch) + (uint32_t)g_col * 2u
+                                                 : kOutside, 0u);
+    };
+    auto issue_x = [&](int stage, const Tokens &t) {
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + A_TILE + wave * 16 * PITCH);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            lds_direct_load16(descX, dst + j * 4 * PITCH,
+                              (t.tok[j] >= 0 && x_inside) ? __umul24((uint32_t)t.tok[j], x_pitch) + (uint32_t)x_col * 2u
+                                                          : kOutside, 0u);
+    };
+    auto stage_g = [&](int stage, const float (&sc)[4]) {
+        unsigned char *tileA = smem + stage * STAGE;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = 16 * wave + 4 * j + grp;
+            const uint32_t *r = reinterpret_cast<const uint32_t *>(&g_regs[j]);
+            uint4 o;
+            o.x = pack_bf16(bf16_lo(r[0]) * sc[j], bf16_hi(r[0]) * sc[j]);
+            o.y = pack_bf16(bf16_lo(r[1]) * sc[j], bf16_hi(r[1]) * sc[j]);
+            o.z = pack_bf16(bf16_lo(r[2]) * sc[j], bf16_hi(r[2]) * sc[j]);
+            o.w = pack_bf16(bf16_lo(r[3]) * sc[j], bf16_hi(r[3]) * sc[j]);
+            *reinterpret_cast<uint4 *>(tileA + row * PITCH + ((slot ^ wswz(row)) << 4)) = o;
+        }
+    };
+
+    const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    const int blk = lane >> 4, sl = lane & 15;
+    // fragment of 32 columns x 16 tokens of a [64][128] tile: two transposing reads
+    auto frag = [&](const unsigned char *t, int col0, int ks) {
+        bf16x4 half[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = ks * 16 + (blk >> 1) * 8 + e * 4 + (sl >> 2);
+            const int col = col0 + (blk & 1) * 16 + (sl & 3) * 4;
+            const unsigned char *src = t + k * PITCH + (((col >> 3) ^ wswz(k)) << 4) + (col & 7) * 2;
+            half[e] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(src));
+        }
+        return __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto compute = [&](int stage) {
+        const unsigned char *tileA = smem + stage * STAGE;
+        const unsigned char *tileB = tileA + A_TILE;
+        constexpr int KS = BK / 16;
+        bf16x8 a[KS][TM], b[KS][TN];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[ks][i] = frag(tileA, wm0 + i * 32, ks);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) b[ks][i] = frag(tileB, wn0 + i * 32, ks);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+        // fragment reads of two k-slices, then each slice's MFMAs with the reads of the slice after next
+        constexpr int RD = 2 * (TM + TN), MM = TM * TN;
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+            if (ks + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+        }
+    };
+
+    // prologue: step 0 into stage 0, tokens of step 1 known
+    Tokens tok_cur = fetch_tokens(0), tok_next = fetch_tokens(1);
+    float sc_cur[4];
+    fetch_scales(tok_cur, sc_cur);
+    load_g(tok_cur);
+    issue_x(0, tok_cur);
+    stage_g(0, sc_cur);
+    for (int s = 0; s < steps; ++s) {
+        wait_loads_outstanding<0>();          // this wavefront's part of X(s) has landed
+        asm volatile("" ::: "memory");
+        __syncthreads();                       // tile s complete; tile s-1 no longer read
+        __builtin_amdgcn_sched_barrier(0);
+        // step s+1 on its way while step s is on the matrix cores (past the end: zeros); the
+        // scaled G(s+1) goes to LDS once the MFMAs of the step are issued
+        const Tokens tok_after = fetch_tokens(s + 2);
+        float sc_next[4];
+        fetch_scales(tok_next, sc_next);
+        load_g(tok_next);
+        issue_x((s + 1) & 1, tok_next);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(s & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage_g((s + 1) & 1, sc_next);
+        tok_next = tok_after;
+    }
+    wait_loads_outstanding<0>();
+
+    const int lane32 = lane & 31;
+    float *dst = active == 1 ? dW : partials + (int64_t)split * K_out * K_in;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int o = o0 + wm0 + i * 32 + acc_row(v);
+            if (o >= K_out) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = c0 + wn0 + j * 32 + lane32;
+                if (c < K_in) dst[(int64_t)o * K_in + c] = acc[i][j][v];
+            }
+        }
+}
+
 // ---------------------------------------------------------- host launchers
 
 // Tile edge of the bf16 weight-gradient GEMM: 128, unless dW has so few 128x128 tiles that filling
@@ -869,6 +1064,30 @@ static vcas_status launch_wgrad(const vcas_shape &s, const void *G, const void *
     return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
 }
 
+static vcas_status launch_wgrad_dma(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
+                                    const int32_t *idxW, const int32_t *cntW, float *dW, float *partials,
+                                    int splits, hipStream_t st)
+{
+    constexpr int BM = 128, BN = 128, MIN_STEPS = 2;
+    const int64_t R = (int64_t)s.N * s.T;
+    const int tiles_n = (s.K_in + BN - 1) / BN;
+    const int tiles = ((s.K_out + BM - 1) / BM) * tiles_n;
+    if (splits > 8) splits = 8;
+    const size_t lds = 2 * (BM + BN) * 128;
+    auto kern = wgrad_bf16_dma_kernel<BM, BN, 2, 2>;
+    static bool allowed = false;
+    if (!allowed) {
+        if (!allow_lds(kern, lds)) return VCAS_EHIP;
+        allowed = true;
+    }
+    const int grid = (tiles * splits + 7) / 8 * 8;
+    launch_timed(1, kern, dim3(grid), dim3(256), lds, st, static_cast<const uint16_t *>(G),
+                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
+                 tiles, splits, MIN_STEPS);
+    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
+}
+
 // tile: 64 or 128 (wgrad_tile_bf16); splits: as sized by the caller for that tile
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
@@ -876,7 +1095,7 @@ vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const 
 {
     if (tile == 64)
         return launch_wgrad<64, 64, 2, 1, 2>(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
-    return launch_wgrad<128, 128, 2, 2, 2>(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
+    return launch_wgrad_dma(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
 }
 
 }  // namespace vcas
