@@ -5,18 +5,21 @@
 // matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
 //
 // Tiling: a workgroup of WM x WN wavefronts owns a BM x BN output tile and
-// walks the contraction in steps of 64.  Operand tiles live in LDS as
-// [row][64 k] bf16 (128 bytes per row, 16-byte slots XOR-swizzled so that both
-// the fragment reads and the transposing writes spread over all banks), double
-// buffered: the global loads of step i+1 are in flight while step i is on the
-// matrix cores.
+// walks the contraction in steps of 64, operand tiles double (or deeper)
+// buffered in LDS.  An MFMA lane needs 8 consecutive contraction values of one
+// row/column, but W (for dgrad) and both G and X (for wgrad) are stored with
+// the contraction index as the slow dimension.  Two ways of getting them there:
 //
-// W (for dgrad) and both G and X (for wgrad) are stored with the contraction
-// index as the slow dimension, while an MFMA lane needs 8 consecutive
-// contraction values of one row/column.  The loaders therefore read 4 rows x 8
-// columns per thread with coalesced 16-byte loads, transpose the 4x8 block in
-// registers (v_perm_b32) and write 8-byte pieces to the [column][k] LDS tile.
-// wgrad multiplies the G block by the per-token scale on the way (the scale
+//  * LDS-direct (dgrad, and the 128x128 wgrad): buffer loads write straight
+//    into LDS; an operand that lies "the wrong way" stays as it is in memory,
+//    [64 k][columns], and ds_read_b64_tr_b16 transposes it on the way out.
+//  * register-staged (the 64x64 wgrad for small dW): 4 rows x 8 columns per
+//    thread with coalesced 16-byte loads, transposed in registers (v_perm_b32)
+//    and written as 8-byte pieces to a [column][64 k] tile whose 16-byte slots
+//    are XOR-swizzled so that fragment reads and transposing writes spread
+//    over all banks.
+//
+// wgrad multiplies G by the per-token scale before it reaches LDS (the scale
 // lies on the contraction axis and cannot go into the epilogue); dgrad's
 // per-row 1/p goes into the epilogue.
 #include <type_traits>
