@@ -203,7 +203,9 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
  * vcas_backward_data: row norms of G, p, SampleA mask and kept list (Sec. 4.1),
  * dX (Eq. 1, upper line; dX may be null); on small layers also the row norms of
  * X and the SampleW uniforms, which do not depend on SampleA.  Fills gsq, gnorm,
- * p, maskA, idxA, cntA of *plan.
+ * p, maskA, idxA, cntA of *plan; the score and q arrays of *plan carry
+ * intermediate values (square roots of the row norms) to the weight call and
+ * must be left alone until it has run: one weight call per data call.
  * vcas_backward_weight: must be ordered after vcas_backward_data with the same
  * shape, G, X, rho, rng, token_sampling, plan and workspace (same stream, or an
  * event).  Row norms of X on kept samples if not taken yet, leverage scores, q,

@@ -14,8 +14,9 @@ KernelTimer &kernel_timer()
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
                       hipStream_t st);
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st);
-vcas_status row_sumsq_with_uniforms(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
-                                    const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st);
+vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K, int T, const uint8_t *keep,
+                                      float *xsq, const float *gsq, const float *p, float *score, const vcas_rng &rng,
+                                      uint32_t stream_id, float *uniforms, hipStream_t st);
 // sampling.hip
 vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st);
 vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32_t stream_id, uint8_t *mask,
@@ -30,10 +31,11 @@ vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_
                       uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st);
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
 vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
-                      const float *u, int N, int T, double budget, int token_sampling, float *score, float *q,
-                      uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st);
+                      const float *u, int N, int T, double budget, int token_sampling, int prepared, float *score,
+                      float *q, uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st);
 vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
-                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st);
+                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, float *root_g,
+                           float *root_x, hipStream_t st);
 bool plan_fused_fits(int N, int T);
 vcas_status plan_fused(const void *G, int K_out, const void *X, int K_in, int dtype, int N, int T, double budget_a,
                        double budget_w, int token_sampling, const vcas_rng &rng, float *uniforms, uint32_t *ticket,
@@ -201,8 +203,10 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
+    // together: the square roots SampleW needs travel in the plan's score and q arrays until
+    // SampleW overwrites them with their final contents
     if (norms_together(s))
-        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, st));
+        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, pl.score, pl.q, st));
     else
         VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
@@ -221,10 +225,11 @@ static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X
     float *u = uniforms_of(s, workspace);
     const bool together = norms_together(s);
     if (!together)
-        VCAS_TRY(row_sumsq_with_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, rng, 1u,
-                                         token_sampling ? u : nullptr, st));
+        VCAS_TRY(row_sumsq_scores_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, pl.gsq, pl.p, pl.score, rng, 1u,
+                                           token_sampling ? u : nullptr, st));
+    // what the norm passes have left in score and q: roots (together) or the scores themselves
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
-                       token_sampling, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
+                       token_sampling, together ? 1 : 2, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
     if (dW)
         VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
                                 (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));

@@ -9,10 +9,14 @@ namespace vcas {
 // Rows of samples whose sample_keep byte is 0 are not read and get 0.
 // If a UniformJob is given, the launch also draws the Philox uniform of every
 // row for that sampler (the arithmetic hides under the memory stream).
+// If a ScoreJob is given (A is X, SampleA is done), the row's SampleW score
+// ((1/p_i) * sqrt(gsq_t)) * sqrt(xsq_t) is written as well, 0 on dropped samples:
+// the square roots and the division then run on every CU instead of in the one
+// workgroup of the sampler.
 template <bool BF16, int CH>
 __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
                                                         int T, const uint8_t *__restrict__ sample_keep,
-                                                        float *__restrict__ out, UniformJob job)
+                                                        float *__restrict__ out, UniformJob job, ScoreJob sj)
 {
     if (job.uniforms) {
         const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
@@ -23,12 +27,24 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict_
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     for (int64_t row = wave; row < R; row += nwaves) {
-        if (sample_keep && sample_keep[row / T] == 0) {
-            if (lane == 0) out[row] = 0.0f;
+        const int64_t i = row / T;
+        if (sample_keep && sample_keep[i] == 0) {
+            if (lane == 0) {
+                out[row] = 0.0f;
+                if (sj.score) sj.score[row] = 0.0f;
+            }
             continue;
         }
+        float s1 = 0.0f;
+        if (sj.score) {
+            const float inv = 1.0f / sj.p[i];
+            s1 = inv * __builtin_sqrtf(sj.gsq[row]);
+        }
         const float acc = wave_row_sumsq<BF16, CH>(A + row * groups_per_row, groups_per_row);
-        if (lane == 0) out[row] = acc;
+        if (lane == 0) {
+            out[row] = acc;
+            if (sj.score) sj.score[row] = s1 * __builtin_sqrtf(acc);
+        }
     }
 }
 
@@ -40,7 +56,8 @@ template <bool BF16, int CH>
 __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__restrict__ A, int groups_a,
                                                              float *__restrict__ out_a, const uint4 *__restrict__ B,
                                                              int groups_b, float *__restrict__ out_b, int64_t R,
-                                                             UniformJob job)
+                                                             UniformJob job, float *__restrict__ root_a,
+                                                             float *__restrict__ root_b)
 {
     if (job.uniforms) {
         const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
@@ -55,7 +72,12 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
         const int64_t row = second ? w - R : w;
         const int groups = second ? groups_b : groups_a;
         const float acc = wave_row_sumsq<BF16, CH>((second ? B : A) + row * groups, groups);
-        if (lane == 0) (second ? out_b : out_a)[row] = acc;
+        if (lane == 0) {
+            (second ? out_b : out_a)[row] = acc;
+            // the square roots SampleW multiplies, taken here by many workgroups (null: not wanted)
+            float *root = second ? root_b : root_a;
+            if (root) root[row] = __builtin_sqrtf(acc);
+        }
     }
 }
 
@@ -76,7 +98,7 @@ __global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restric
 
 template <bool BF16>
 static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, const uint8_t *keep, float *out,
-                                    const UniformJob &job, hipStream_t st)
+                                    const UniformJob &job, const ScoreJob &sj, hipStream_t st)
 {
     const int groups = K / (BF16 ? 8 : 4);
     const int need = (groups + 63) / 64;
@@ -84,7 +106,7 @@ static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, cons
     const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
     const uint4 *a = static_cast<const uint4 *>(A);
 #define VCAS_LAUNCH_CH(C) \
-    hipLaunchKernelGGL((row_sumsq_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, R, groups, T, keep, out, job)
+    hipLaunchKernelGGL((row_sumsq_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, R, groups, T, keep, out, job, sj)
     if (need <= 1) VCAS_LAUNCH_CH(1);
     else if (need <= 2) VCAS_LAUNCH_CH(2);
     else if (need <= 3) VCAS_LAUNCH_CH(3);
@@ -99,22 +121,26 @@ vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const u
                       hipStream_t st)
 {
     const UniformJob none = {nullptr, 0, 0, 0, 0, nullptr};
-    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, none, st)
-                              : launch_row_sumsq<false>(A, R, K, T, keep, out, none, st);
+    const ScoreJob no_score = {nullptr, nullptr, nullptr};
+    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, none, no_score, st)
+                              : launch_row_sumsq<false>(A, R, K, T, keep, out, none, no_score, st);
 }
 
-// row norms plus the uniforms of sampler `stream_id` in one launch
-vcas_status row_sumsq_with_uniforms(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
-                                    const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st)
+// row norms of X on kept samples, the SampleW scores and the uniforms of sampler `stream_id`
+// (null: none) in one launch
+vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K, int T, const uint8_t *keep,
+                                      float *xsq, const float *gsq, const float *p, float *score, const vcas_rng &rng,
+                                      uint32_t stream_id, float *uniforms, hipStream_t st)
 {
     const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
-    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(A, R, K, T, keep, out, job, st)
-                              : launch_row_sumsq<false>(A, R, K, T, keep, out, job, st);
+    const ScoreJob sj = {gsq, p, score};
+    return dtype == VCAS_BF16 ? launch_row_sumsq<true>(X, R, K, T, keep, xsq, job, sj, st)
+                              : launch_row_sumsq<false>(X, R, K, T, keep, xsq, job, sj, st);
 }
 
 template <bool BF16>
 static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void *B, int K_b, float *out_b, int64_t R,
-                               const UniformJob &job, hipStream_t st)
+                               const UniformJob &job, float *root_a, float *root_b, hipStream_t st)
 {
     const int ga = K_a / (BF16 ? 8 : 4), gb = K_b / (BF16 ? 8 : 4);
     const int need = ((ga > gb ? ga : gb) + 63) / 64;
@@ -123,7 +149,7 @@ static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void 
     const uint4 *a = static_cast<const uint4 *>(A), *b = static_cast<const uint4 *>(B);
 #define VCAS_LAUNCH_CH(C)                                                                                         \
     hipLaunchKernelGGL((row_sumsq_pair_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, ga, out_a, b, gb, out_b, \
-                       R, job)
+                       R, job, root_a, root_b)
     if (need <= 2) VCAS_LAUNCH_CH(2);
     else if (need <= 4) VCAS_LAUNCH_CH(4);
     else VCAS_LAUNCH_CH(8);
@@ -132,13 +158,15 @@ static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void 
 }
 
 // gsq of every row of G, xsq of EVERY row of X (the caller zeroes the rows of dropped samples
-// later) and the uniforms of sampler `stream_id`, one launch
+// later), their square roots (root_g, root_x; null: not wanted) and the uniforms of sampler
+// `stream_id`, one launch
 vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
-                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, hipStream_t st)
+                           int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, float *root_g,
+                           float *root_x, hipStream_t st)
 {
     const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
-    return dtype == VCAS_BF16 ? launch_pair<true>(G, K_out, gsq, X, K_in, xsq, R, job, st)
-                              : launch_pair<false>(G, K_out, gsq, X, K_in, xsq, R, job, st);
+    return dtype == VCAS_BF16 ? launch_pair<true>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, st)
+                              : launch_pair<false>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, st);
 }
 
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st)

@@ -62,4 +62,12 @@ struct UniformJob {
     const uint32_t *draw_offset;
 };
 
+// SampleW scores of the rows of X, written by the pass that takes their norms
+// once SampleA is done: score_t = ((1/p_i) * sqrt(gsq_t)) * sqrt(xsq_t).
+struct ScoreJob {
+    const float *gsq;   // row norms of G, squared
+    const float *p;     // SampleA keep probabilities, one per sample
+    float *score;       // null: no job
+};
+
 }  // namespace vcas

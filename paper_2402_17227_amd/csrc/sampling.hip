@@ -230,12 +230,17 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
 {
     __shared__ double sd[2][16];
     __shared__ int si[2][16];
+    // w[j]: the score, as the fp64 summand it is, while element j is open (positive and not yet
+    // fixed at one), +0 otherwise.  Adding +0 leaves a sum of non-negative terms as it is and
+    // c * 0 never reaches one, so a round is one multiply, compare, select and add per element.
+    double w[E];
     double part = 0.0;
     int cnt = 0;   // per wavefront, from ballots (scalar work, beside the vector sums)
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const bool pos = a[j] > 0.0f;
-        if (pos) part += (double)a[j];
+        w[j] = pos ? (double)a[j] : 0.0;
+        part += w[j];
         cnt += ballot_count(pos);
     }
     double S;
@@ -246,7 +251,6 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
         for (int j = 0; j < E; ++j) prob[j] = a[j] > 0.0f ? 1.0f : 0.0f;
         return;
     }
-    uint32_t fixed = 0;   // bit j: element j is fixed at one
     int ncap = 0;
     double c = 0.0;
     int flip = 1;
@@ -261,10 +265,9 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
         cnt = 0;
 #pragma unroll
         for (int j = 0; j < E; ++j) {
-            const bool open = a[j] > 0.0f && !((fixed >> j) & 1u);
-            const bool cap = open && c * (double)a[j] >= 1.0;
-            if (cap) fixed |= 1u << j;
-            if (open && !cap) part += (double)a[j];
+            const bool cap = c * w[j] >= 1.0;
+            w[j] = cap ? 0.0 : w[j];
+            part += w[j];
             cnt += ballot_count(cap);
         }
         double S_next;
@@ -278,10 +281,13 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         float p = 0.0f;
-        if ((fixed >> j) & 1u) p = 1.0f;
-        else if (a[j] > 0.0f) {
-            p = (float)(c * (double)a[j]);
-            p = p < 1.0f ? p : 1.0f;
+        if (a[j] > 0.0f) {
+            if (w[j] == 0.0) {
+                p = 1.0f;   // fixed at one in some round
+            } else {
+                p = (float)(c * w[j]);
+                p = p < 1.0f ? p : 1.0f;
+            }
         }
         prob[j] = p;
     }
@@ -432,59 +438,105 @@ __global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__res
     sampler_a_fast_body(gsq, N, T, budget, seed, layer, draw, draw_offset, gnorm, p, maskA, idxA, cntA);
 }
 
-// SampleW for R <= 1024*E (one workgroup of 1024).
+// What the caller has already left in the score and q arrays when SampleW starts.
+enum : int {
+    kFromSquares = 0,   // nothing: scores come from gsq, xsq and p
+    kRootsGiven = 1,    // score[t] = sqrt(gsq[t]), q[t] = sqrt(xsq[t]) for every row
+    kScoresGiven = 2,   // score[t] is final (0 on dropped samples, whose xsq is 0 already)
+};
+
+// t / T for t * T < 2^32 with a multiplier the wavefront computes once (T > 1):
+// t * (floor(2^32 / T) + 1) / 2^32 = t / T + t * e / 2^32 with 0 < e <= 1, and
+// t / 2^32 < 1 / T keeps the sum below the next integer.
+__device__ __forceinline__ int sample_of(int t, int T, uint32_t magic)
+{
+    return T > 1 ? (int)__umulhi((uint32_t)t, magic) : t;
+}
+
+// SampleW for R <= 1024*E (one workgroup of 1024).  The whole vector is this one
+// workgroup's arithmetic, so everything per sample (1/p_i, the keep byte) is
+// computed once into LDS when N <= 1024, and the square roots come from the
+// many-workgroup norm pass when the caller says so (`prepared`).
 template <int E>
 __device__ __forceinline__ void sampler_w_fast_body(const float *__restrict__ gsq, float *__restrict__ xsq,
                                                     int zero_dropped_xsq, const float *__restrict__ p,
                                                     const uint8_t *__restrict__ maskA, const float *__restrict__ u,
-                                                    int N, int T, double budget, int token_sampling,
+                                                    int N, int T, double budget, int token_sampling, int prepared,
                                                     float *__restrict__ score, float *__restrict__ q,
                                                     uint8_t *__restrict__ maskW, float *__restrict__ scaleW,
                                                     int32_t *__restrict__ idxW, int32_t *__restrict__ cntW)
 {
+    __shared__ float p_of[1024], pinv_of[1024];
+    __shared__ uint8_t keep_of[1024];
     const int tid = threadIdx.x;
     const int R = N * T;
-    float a[E], qv[E], pinv_src[E], uu[E];
-    uint8_t keepA[E];
+    const bool table = N <= 1024;
+    const uint32_t magic = T > 1 ? (uint32_t)(0x100000000ull / (uint32_t)T) + 1u : 0u;
+    // Every load of the vectors first, with no condition on a loaded value in between, so that
+    // they are all in flight together (rows past the end re-read the last row and are ignored).
+    float a[E], rx[E], qv[E], uu[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const int t = min(tid + 1024 * j, R - 1);
+        uu[j] = token_sampling ? u[t] : 0.0f;
+        if (prepared == kFromSquares) {
+            a[j] = gsq[t];
+            rx[j] = xsq[t];
+        } else {
+            a[j] = score[t];
+            rx[j] = prepared == kRootsGiven ? q[t] : 0.0f;
+        }
+    }
+    if (table) {
+        if (tid < N) {
+            const float pi = p[tid];
+            const uint8_t k = maskA[tid];
+            p_of[tid] = pi;
+            keep_of[tid] = k;
+            pinv_of[tid] = k ? 1.0f / pi : 0.0f;
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const int t = tid + 1024 * j;
-        a[j] = 0.0f;
-        pinv_src[j] = 1.0f;
-        uu[j] = 2.0f;
-        keepA[j] = 0;
-        if (t < R) {
-            const int i = t / T;
-            keepA[j] = maskA[i];
-            pinv_src[j] = p[i];
-            const float g = gsq[t], x = xsq[t];
-            if (token_sampling) uu[j] = u[t];
-            if (keepA[j]) {
-                const float inv = 1.0f / pinv_src[j];
-                const float s1 = inv * __builtin_sqrtf(g);
-                a[j] = s1 * __builtin_sqrtf(x);
+        if (t >= R) {
+            a[j] = 0.0f;
+            uu[j] = 2.0f;
+        } else if (prepared != kScoresGiven) {
+            const int i = sample_of(t, T, magic);
+            const bool keep = table ? keep_of[i] != 0 : maskA[i] != 0;
+            const float rg = prepared == kRootsGiven ? a[j] : __builtin_sqrtf(a[j]);
+            const float rxx = prepared == kRootsGiven ? rx[j] : __builtin_sqrtf(rx[j]);
+            a[j] = 0.0f;
+            if (keep) {
+                const float inv = table ? pinv_of[i] : 1.0f / p[i];
+                const float s1 = inv * rg;
+                a[j] = s1 * rxx;
             } else if (zero_dropped_xsq) {
                 xsq[t] = 0.0f;
             }
             score[t] = a[j];
         }
     }
-    if (token_sampling) {
-        keep_probs_regs<E>(a, budget, qv);
-    } else {
-#pragma unroll
-        for (int j = 0; j < E; ++j) qv[j] = keepA[j] ? 1.0f : 0.0f;
-    }
+    if (token_sampling) keep_probs_regs<E>(a, budget, qv);
     bool m[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const int t = tid + 1024 * j;
         m[j] = false;
         if (t < R) {
-            m[j] = token_sampling ? uu[j] < qv[j] : keepA[j] != 0;
+            const int i = sample_of(t, T, magic);
+            const float pi = table ? p_of[i] : p[i];
+            if (token_sampling) {
+                m[j] = uu[j] < qv[j];
+            } else {
+                m[j] = table ? keep_of[i] != 0 : maskA[i] != 0;
+                qv[j] = m[j] ? 1.0f : 0.0f;
+            }
             q[t] = qv[j];
             maskW[t] = m[j] ? 1 : 0;
-            scaleW[t] = m[j] ? 1.0f / (pinv_src[j] * qv[j]) : 0.0f;
+            scaleW[t] = m[j] ? 1.0f / (pi * qv[j]) : 0.0f;
         }
     }
     compact_regs<E>(m, idxW, cntW);
@@ -496,13 +548,13 @@ __global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__res
                                                               const float *__restrict__ p,
                                                               const uint8_t *__restrict__ maskA,
                                                               const float *__restrict__ u, int N, int T, double budget,
-                                                              int token_sampling, float *__restrict__ score,
-                                                              float *__restrict__ q, uint8_t *__restrict__ maskW,
-                                                              float *__restrict__ scaleW, int32_t *__restrict__ idxW,
-                                                              int32_t *__restrict__ cntW)
+                                                              int token_sampling, int prepared,
+                                                              float *__restrict__ score, float *__restrict__ q,
+                                                              uint8_t *__restrict__ maskW, float *__restrict__ scaleW,
+                                                              int32_t *__restrict__ idxW, int32_t *__restrict__ cntW)
 {
-    sampler_w_fast_body<E>(gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW,
-                           scaleW, idxW, cntW);
+    sampler_w_fast_body<E>(gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, prepared, score, q,
+                           maskW, scaleW, idxW, cntW);
 }
 
 // SampleA: ||G_i||_F from gsq, p, Bernoulli mask over samples, kept list.
@@ -548,20 +600,20 @@ __global__ __launch_bounds__(1024) void sampler_w_kernel(const float *__restrict
                                                          int zero_dropped_xsq, const float *__restrict__ p,
                                                          const uint8_t *__restrict__ maskA,
                                                          const float *__restrict__ u, int N, int T, double budget,
-                                                         int token_sampling, float *__restrict__ score,
-                                                         float *__restrict__ q, uint8_t *__restrict__ maskW,
-                                                         float *__restrict__ scaleW, int32_t *__restrict__ idxW,
-                                                         int32_t *__restrict__ cntW)
+                                                         int token_sampling, int prepared,
+                                                         float *__restrict__ score, float *__restrict__ q,
+                                                         uint8_t *__restrict__ maskW, float *__restrict__ scaleW,
+                                                         int32_t *__restrict__ idxW, int32_t *__restrict__ cntW)
 {
     const int tid = threadIdx.x;
     const int R = N * T;
-    for (int t = tid; t < R; t += 1024) {
+    for (int t = tid; t < R && prepared != kScoresGiven; t += 1024) {
         const int i = t / T;
         float s = 0.0f;
         if (maskA[i]) {
             const float inv = 1.0f / p[i];
-            const float a = inv * __builtin_sqrtf(gsq[t]);
-            s = a * __builtin_sqrtf(xsq[t]);
+            const float a = inv * (prepared == kRootsGiven ? score[t] : __builtin_sqrtf(gsq[t]));
+            s = a * (prepared == kRootsGiven ? q[t] : __builtin_sqrtf(xsq[t]));
         } else if (zero_dropped_xsq) {
             xsq[t] = 0.0f;
         }
@@ -660,12 +712,13 @@ vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *
 }
 
 vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
-                      const float *u, int N, int T, double budget, int token_sampling, float *score, float *q,
-                      uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st)
+                      const float *u, int N, int T, double budget, int token_sampling, int prepared, float *score,
+                      float *q, uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st)
 {
     const int64_t R = (int64_t)N * T;
-#define VCAS_SAMPLER_W_ARGS \
-    gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, score, q, maskW, scaleW, idxW, cntW
+#define VCAS_SAMPLER_W_ARGS                                                                                      \
+    gsq, xsq, zero_dropped_xsq, p, maskA, u, N, T, budget, token_sampling, prepared, score, q, maskW, scaleW, idxW, \
+        cntW
     if (R <= 4096)
         hipLaunchKernelGGL(sampler_w_fast_kernel<4>, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
     else if (R <= 16384)
