@@ -360,7 +360,15 @@ __device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gs
     for (int i = wave; i < N; i += 16) {
         const float *row = gsq + (int64_t)i * T;
         float acc = 0.0f;
-        for (int t = lane; t < T; t += 64) acc = acc + row[t];
+        // eight loads in flight, then added in ascending t as before (a lane's values past the
+        // end re-read the last one and count as +0, which leaves the sum as it is)
+        for (int t0 = lane; t0 < T; t0 += 512) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = row[min(t0 + 64 * k, T - 1)];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc = acc + (t0 + 64 * k < T ? v[k] : 0.0f);
+        }
         acc = wave_exchange_sum(acc);
         if (lane == 0) gn[i] = __builtin_sqrtf(acc);
     }
