@@ -267,6 +267,20 @@ def test_linear_backward_long_vectors(vb, N, T):
     assert rel_l2(dX, want_dX) <= TOL[BF16] and rel_l2(dW, want_dW) <= TOL[BF16]
 
 
+def test_linear_backward_long_vectors_with_a_large_x(vb):
+    # R > 16384 AND X above 16 MiB: the norms of X are taken after SampleA, on kept samples, by the
+    # launch that also writes the SampleW scores, and the long-vector SampleW kernel takes them as given
+    from tests.gpu_util import run_layer_gpu, compare_plan, rel_l2
+    spec = workloads.LayerSpec("long_x", BF16, 40, 500, 448, 72, 0.5, 0.5, layer=4, seed=13, gen_seed=3, token_sigma=0.5)
+    assert spec.N * spec.T * spec.K_in * 2 > 16 << 20
+    G, X, W = workloads.make_layer(spec)
+    got_plan, dX, dW = run_layer_gpu(spec, G, X, W, draw=1)
+    want_plan, want_dX, want_dW = oracle.linear_backward(G, X, W, spec.dtype, spec.N, spec.T, spec.rho, spec.nu,
+                                                         spec.seed, spec.layer, 1)
+    compare_plan(got_plan, want_plan)
+    assert rel_l2(dX, want_dX) <= TOL[BF16] and rel_l2(dW, want_dW) <= TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_keep_ratio_one_is_the_dense_backward(vb, dtype):
     from tests.gpu_util import run_layer_gpu, rel_l2
