@@ -169,6 +169,15 @@ def dgrad(G, W, dtype: int, N: int, T: int, p, maskA) -> np.ndarray:
     return out
 
 
+def dgrad_jacobian(G, W, J, dtype: int, N: int, T: int, p, maskA) -> np.ndarray:
+    """fp64 (SampleA(G) W) * J: the activation gradient passed through an elementwise layer whose
+    saved Jacobian is J [R, K_in] (App. A: the Hadamard product for non-linear layers such as ReLU)."""
+    J = _check(J, dtype)
+    out = dgrad(G, W, dtype, N, T, p, maskA)
+    assert J.shape == out.shape
+    return out * to_f64(J, dtype)
+
+
 def wgrad(G, X, dtype: int, scale) -> np.ndarray:
     """fp64 dW[K_out,K_in] = sum_t scale_t g_t x_t^T."""
     G, X = _check(G, dtype), _check(X, dtype)

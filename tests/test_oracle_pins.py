@@ -438,3 +438,36 @@ def test_config_one_runs_in_seconds_and_keeps_about_the_stated_fraction():
     dropped = np.repeat(plan.maskA == 0, spec.T)
     assert np.all(dX[dropped] == 0) and np.all(np.abs(dX[~dropped]).sum(axis=1) > 0)
     assert np.all(plan.scaleW[plan.maskW == 0] == 0) and np.all(plan.scaleW[plan.maskW == 1] >= 1)
+
+
+def test_jacobian_product_is_the_chain_rule_by_finite_differences():
+    """App. A: behind an elementwise layer h = phi(z) the activation gradient is (G W) * phi'(z).
+    Checked against central differences of L(z) = sum(G * (phi(z) W^T)) on a tiny case, all samples kept."""
+    rng = np.random.default_rng(4)
+    N, T, K_in, K_out = 2, 3, 5, 4
+    R = N * T
+    z = rng.standard_normal((R, K_in))
+    W = rng.standard_normal((K_out, K_in)).astype(np.float32)
+    G = rng.standard_normal((R, K_out)).astype(np.float32)
+    phi = np.tanh
+    J = (1.0 - np.tanh(z) ** 2).astype(np.float32)
+
+    def loss(zz):
+        return float(np.sum(G.astype(np.float64) * (phi(zz) @ W.astype(np.float64).T)))
+
+    want = np.zeros_like(z)
+    h = 1e-5
+    for r in range(R):
+        for k in range(K_in):
+            e = np.zeros_like(z)
+            e[r, k] = h
+            want[r, k] = (loss(z + e) - loss(z - e)) / (2 * h)
+    p = np.ones(N, np.float32)
+    got = oracle.dgrad_jacobian(G, W, J, oracle.F32, N, T, p, np.ones(N, np.uint8))
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=1e-7)
+    # J = 1 is the plain activation gradient; a dropped sample stays zero whatever J holds
+    ones = np.ones((R, K_in), np.float32)
+    mask = np.array([1, 0], np.uint8)
+    plain = oracle.dgrad(G, W, oracle.F32, N, T, p, mask)
+    assert np.array_equal(oracle.dgrad_jacobian(G, W, ones, oracle.F32, N, T, p, mask), plain)
+    assert np.all(oracle.dgrad_jacobian(G, W, J, oracle.F32, N, T, p, mask)[T:] == 0)
