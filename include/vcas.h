@@ -163,6 +163,19 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
                                const int32_t *idxA, const int32_t *cntA, void *dX, void *stream);
 
 /*
+ * The same through an elementwise layer below the linear one (App. A: for a
+ * non-linear layer such as ReLU the activation gradient is multiplied, entry by
+ * entry, by the Jacobian saved in the forward pass):
+ *   dX[r,:] = ((1/p[i]) * G[r,:] W) * J[r,:]   on rows of kept samples, 0 elsewhere.
+ * J [R,K_in], device, layer dtype, 16-byte aligned, read on kept rows only; the
+ * product is formed in fp32 before the one rounding to the layer dtype.  What
+ * comes out is the output gradient of the layer below the elementwise one.
+ */
+vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const void *W, const float *p,
+                                   const int32_t *idxA, const int32_t *cntA, const void *J, void *dX,
+                                   void *stream);
+
+/*
  * Sampled weight gradient (Sec. 4.2, grad_W = Gtilde^T X):
  *   dW[o,k] = sum over the *cntW rows t = idxW[.] of row_scale[t] G[t,o] X[t,k].
  * dW [K_out,K_in] fp32 is overwritten.  Needs the workspace (split-K partial
@@ -216,6 +229,11 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
 vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const void *X, const void *W,
                                double rho, const vcas_rng *rng, int32_t token_sampling,
                                const vcas_plan *plan, void *dX, void *workspace, void *stream);
+/* vcas_backward_data with the elementwise Jacobian J [R,K_in] of the layer below
+ * multiplied into dX (see vcas_sampled_dgrad_jac); dX, W and J are required. */
+vcas_status vcas_backward_data_jac(const vcas_shape *shape, const void *G, const void *X, const void *W,
+                                   const void *J, double rho, const vcas_rng *rng, int32_t token_sampling,
+                                   const vcas_plan *plan, void *dX, void *workspace, void *stream);
 vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho,
                                  double nu, const vcas_rng *rng, int32_t token_sampling,
                                  const vcas_plan *plan, float *dW, void *workspace, void *stream);

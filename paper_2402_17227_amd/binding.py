@@ -18,8 +18,8 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
-    "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
+    "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
+    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_data_jac", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
 ]
 
@@ -169,6 +169,11 @@ def vcas_sampled_dgrad(shape: Shape, G, W, p, idxA, cntA, dX):
                                     _stream()), "vcas_sampled_dgrad")
 
 
+def vcas_sampled_dgrad_jac(shape: Shape, G, W, p, idxA, cntA, J, dX):
+    _check(lib().vcas_sampled_dgrad_jac(C.byref(shape), _ptr(G), _ptr(W), _ptr(p), _ptr(idxA), _ptr(cntA), _ptr(J),
+                                        _ptr(dX), _stream()), "vcas_sampled_dgrad_jac")
+
+
 def vcas_sampled_wgrad(shape: Shape, G, X, row_scale, idxW, cntW, dW, workspace):
     _check(lib().vcas_sampled_wgrad(C.byref(shape), _ptr(G), _ptr(X), _ptr(row_scale), _ptr(idxW), _ptr(cntW),
                                     _ptr(dW), _ptr(workspace), _stream()), "vcas_sampled_wgrad")
@@ -189,6 +194,14 @@ def vcas_backward_data(shape: Shape, G, X, W, rho: float, rng: Rng, token_sampli
     _check(lib().vcas_backward_data(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.byref(rng),
                                     C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX), _ptr(workspace),
                                     _stream()), "vcas_backward_data")
+
+
+def vcas_backward_data_jac(shape: Shape, G, X, W, J, rho: float, rng: Rng, token_sampling: bool, plan: Plan, dX,
+                           workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_backward_data_jac(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), _ptr(J), C.c_double(rho),
+                                        C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
+                                        _ptr(workspace), _stream()), "vcas_backward_data_jac")
 
 
 def vcas_backward_weight(shape: Shape, G, X, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dW,

@@ -354,7 +354,8 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   const int32_t *__restrict__ idxA,
                                                                   const int32_t *__restrict__ cntA,
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
-                                                                  int K_out, int tiles_n)
+                                                                  int K_out, int tiles_n,
+                                                                  const uint16_t *__restrict__ J)
 {
     constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -563,10 +564,16 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                 const float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
                 const float send = odd ? mine_e : mine_o;
                 const float recv = dpp_move<0xB1>(send);
-                const uint32_t word = odd ? pack_bf16(recv, mine_o) : pack_bf16(mine_e, recv);
+                float lo = odd ? recv : mine_e, hi = odd ? mine_o : recv;
                 const int col = n0 + wn0 + j * 32 + (lane & 30);
-                if (dst >= 0 && col < K_in)
-                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = word;
+                if (dst >= 0 && col < K_in) {
+                    if (J) {   // elementwise Jacobian of the layer below (App. A), same layout as dX
+                        const uint32_t jw = *reinterpret_cast<const uint32_t *>(J + (int64_t)dst * K_in + col);
+                        lo = lo * bf16_lo(jw);
+                        hi = hi * bf16_hi(jw);
+                    }
+                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = pack_bf16(lo, hi);
+                }
             }
         }
 }
@@ -1000,7 +1007,7 @@ static bool allow_lds(Kern kern, size_t bytes)
 
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
-                                const int32_t *idxA, const int32_t *cntA, void *dX, hipStream_t st)
+                                const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
@@ -1015,14 +1022,15 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                 s.K_out, tiles_n);
+                 s.K_out, tiles_n, static_cast<const uint16_t *>(J));
     return launch_status();
 }
 
 // expected_rows: how many of the R rows the caller expects to be kept (R if unknown); it only
 // steers the tile choice, any count is computed correctly by every variant.
+// J: elementwise Jacobian [R, K_in] multiplied into dX, or null.
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, int64_t expected_rows, hipStream_t st)
+                       const int32_t *cntA, void *dX, const void *J, int64_t expected_rows, hipStream_t st)
 {
     // The loads into LDS run at about 40 bytes per clock and CU, so the largest tile that still
     // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 192 tiles up; else 128x128
@@ -1035,11 +1043,11 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, st);
-    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, st);
+    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, st);
+    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
-    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, st);
-    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, st);
+    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, st);
+    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, st);
 }
 
 template <int BM, int BN, int WM, int WN, int OCC>

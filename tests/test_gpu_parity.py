@@ -391,6 +391,85 @@ def test_chained_layers_keep_dropped_samples_dropped(vb):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N,T,kin,kout,frac", [(4, 40, 136, 264, 0.75), (9, 130, 768, 256, 0.5),
+                                               (17, 128, 2040, 136, 0.6),      # 128x128 tiles (bf16), ragged columns
+                                               (33, 125, 3080, 200, 1.0)])     # 256x256 tiles (bf16)
+def test_dgrad_through_an_elementwise_jacobian(vb, dtype, N, T, kin, kout, frac):
+    """App. A: dX = ((1/p) G W) * J on kept rows, zero rows for dropped samples (J holds NaN there:
+    it must not be read into the result)."""
+    rng = np.random.default_rng(N + kin)
+    R = N * T
+    g = rng.standard_normal((R, kout)).astype(np.float32)
+    w = (rng.standard_normal((kout, kin)) * 0.05).astype(np.float32)
+    p = rng.uniform(0.2, 1, N).astype(np.float32)
+    maskA = (rng.uniform(size=N) < frac).astype(np.uint8)
+    maskA[0] = 1
+    j = (rng.uniform(size=(R, kin)) < 0.6).astype(np.float32) * rng.uniform(0.5, 1.5, (R, kin)).astype(np.float32)
+    G, W, J = (workloads.f32_to_bf16_bits(a) if dtype == BF16 else a for a in (g, w, j))
+    idxA = np.nonzero(maskA)[0].astype(np.int32)
+    idx_buf = np.full(N, -1, np.int32)
+    idx_buf[:idxA.size] = idxA
+    shape = vb.shape_of(N, T, kin, kout, dtype)
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+    j_dev = _dev(J, dtype).clone()
+    j_dev[torch.from_numpy(np.repeat(maskA == 0, T)).cuda()] = float("nan")
+    dX = torch.full((R, kin), float("nan"), dtype=tdt, device="cuda")
+    vb.vcas_sampled_dgrad_jac(shape, _dev(G, dtype), _dev(W, dtype), _dev(p), _dev(idx_buf),
+                              _dev(np.array([idxA.size], np.int32)), j_dev, dX)
+    torch.cuda.synchronize()
+    from tests.gpu_util import from_device, rel_l2
+    got = from_device(dX)
+    want = oracle.dgrad_jacobian(G, W, J, dtype, N, T, p, maskA)
+    assert np.isfinite(got).all()
+    assert np.all(got[np.repeat(maskA == 0, T)] == 0)
+    assert np.all(got[want == 0] == 0)                    # ReLU-like zeros of J stay exact zeros
+    assert rel_l2(got, want) <= TOL[dtype]
+    for i in idxA[:3]:
+        rows = slice(i * T, (i + 1) * T)
+        assert rel_l2(got[rows], want[rows]) <= TOL[dtype]
+
+
+def test_chained_layers_through_relu_jacobians(vb):
+    """Two linears with an elementwise layer between them: the upper layer's data half writes
+    (dX * J) (vcas_backward_data_jac), which is the lower layer's G as it stands."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    N, T, K = 16, 48, 136
+    rng = np.random.default_rng(11)
+    top = workloads.LayerSpec("chain_j", BF16, N, T, K, K, 0.7, 0.5, layer=0, seed=5, gen_seed=2, token_sigma=0.5)
+    G_host, X_host, W_host = workloads.make_layer(top)
+    J_host = workloads.f32_to_bf16_bits((rng.uniform(size=(N * T, K)) < 0.5).astype(np.float32))
+    shape = vb.shape_of(N, T, K, K, BF16)
+    g, x, w, jac = (to_device(a, BF16) for a in (G_host, X_host, W_host, J_host))
+    plan = vb.Plan.allocate(N, T)
+    ws = vb.make_workspace(shape)
+    dX = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dW = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
+    vb.vcas_backward_data_jac(shape, g, x, w, jac, 0.7, vb.Rng(5, 0, 0), True, plan, dX, ws)
+    vb.vcas_backward_weight(shape, g, x, 0.7, 0.5, vb.Rng(5, 0, 0), True, plan, dW, ws)
+    torch.cuda.synchronize()
+    want, _, want_dW = oracle.linear_backward(G_host, X_host, W_host, BF16, N, T, 0.7, 0.5, 5, 0, 0)
+    compare_plan(plan_to_numpy(plan), want)
+    want_dX = oracle.dgrad_jacobian(G_host, W_host, J_host, BF16, N, T, want.p, want.maskA)
+    assert rel_l2(from_device(dX), want_dX) <= TOL[BF16] and rel_l2(from_device(dW), want_dW) <= TOL[BF16]
+    # the layer below takes that tensor as its G
+    X2 = workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32))
+    W2 = workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32))
+    plan2 = vb.Plan.allocate(N, T)
+    dX2 = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dW2 = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
+    vb.vcas_linear_backward(shape, dX, to_device(X2, BF16), to_device(W2, BF16), 0.5, 0.5, vb.Rng(5, 1, 0), True,
+                            plan2, dX2, dW2, ws)
+    torch.cuda.synchronize()
+    G2 = dX.view(torch.int16).cpu().numpy().view(np.uint16)
+    want2, want_dX2, want_dW2 = oracle.linear_backward(G2, X2, W2, BF16, N, T, 0.5, 0.5, 5, 1, 0)
+    got2 = plan_to_numpy(plan2)
+    compare_plan(got2, want2)
+    assert rel_l2(from_device(dX2), want_dX2) <= TOL[BF16] and rel_l2(from_device(dW2), want_dW2) <= TOL[BF16]
+    dropped = want.maskA == 0
+    assert np.all(got2["p"][dropped] == 0) and not np.any(got2["maskA"][dropped])
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
 def test_variance_probe_matches_oracle(vb, dtype):
     spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)
     G, X, W = workloads.make_layer(spec)
