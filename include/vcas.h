@@ -229,11 +229,26 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
 vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const void *X, const void *W,
                                double rho, const vcas_rng *rng, int32_t token_sampling,
                                const vcas_plan *plan, void *dX, void *workspace, void *stream);
-/* vcas_backward_data with the elementwise Jacobian J [R,K_in] of the layer below
- * multiplied into dX (see vcas_sampled_dgrad_jac); dX, W and J are required. */
-vcas_status vcas_backward_data_jac(const vcas_shape *shape, const void *G, const void *X, const void *W,
-                                   const void *J, double rho, const vcas_rng *rng, int32_t token_sampling,
-                                   const vcas_plan *plan, void *dX, void *workspace, void *stream);
+/*
+ * vcas_backward_data for a layer inside a stack of layers (Sec. 3: the
+ * activation gradient grows sparser layer by layer; App. A: elementwise layers
+ * in between multiply by their Jacobian).  Three additions, each optional:
+ *   J (null: none): elementwise Jacobian [R,K_in] of the layer below, multiplied
+ *     into dX as in vcas_sampled_dgrad_jac; needs dX.
+ *   kept_above (null: all): N bytes, device; 0 marks a sample that a layer above
+ *     has dropped.  Its rows of G are never read and count as zero, so it gets
+ *     p_i = 0 and stays dropped.  The maskA array of the upper layer's plan can
+ *     be passed as it is.
+ *   fill_dropped_rows: 0 leaves the rows of dX that belong to samples this layer
+ *     does not keep as they are (for a consumer that gets this layer's maskA as
+ *     its kept_above); otherwise they are written as zeros.
+ * The weight call that follows is vcas_backward_weight, unchanged: it reads rows
+ * of kept tokens only.
+ */
+vcas_status vcas_backward_data_chained(const vcas_shape *shape, const void *G, const void *X, const void *W,
+                                       const void *J, const uint8_t *kept_above, int32_t fill_dropped_rows,
+                                       double rho, const vcas_rng *rng, int32_t token_sampling,
+                                       const vcas_plan *plan, void *dX, void *workspace, void *stream);
 vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho,
                                  double nu, const vcas_rng *rng, int32_t token_sampling,
                                  const vcas_plan *plan, float *dW, void *workspace, void *stream);

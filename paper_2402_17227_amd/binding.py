@@ -19,7 +19,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_data_jac", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
+    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
 ]
 
@@ -196,12 +196,14 @@ def vcas_backward_data(shape: Shape, G, X, W, rho: float, rng: Rng, token_sampli
                                     _stream()), "vcas_backward_data")
 
 
-def vcas_backward_data_jac(shape: Shape, G, X, W, J, rho: float, rng: Rng, token_sampling: bool, plan: Plan, dX,
-                           workspace):
+def vcas_backward_data_chained(shape: Shape, G, X, W, J, kept_above, fill_dropped_rows: bool, rho: float, rng: Rng,
+                               token_sampling: bool, plan: Plan, dX, workspace):
+    """J, kept_above: device tensors or None."""
     ptrs = plan.ptrs()
-    _check(lib().vcas_backward_data_jac(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), _ptr(J), C.c_double(rho),
-                                        C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
-                                        _ptr(workspace), _stream()), "vcas_backward_data_jac")
+    _check(lib().vcas_backward_data_chained(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), _ptr(J), _ptr(kept_above),
+                                            C.c_int32(1 if fill_dropped_rows else 0), C.c_double(rho), C.byref(rng),
+                                            C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
+                                            _ptr(workspace), _stream()), "vcas_backward_data_chained")
 
 
 def vcas_backward_weight(shape: Shape, G, X, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dW,

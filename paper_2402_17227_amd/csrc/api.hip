@@ -35,7 +35,7 @@ vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const 
                       float *q, uint8_t *maskW, float *scaleW, int32_t *idxW, int32_t *cntW, hipStream_t st);
 vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
                            int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, float *root_g,
-                           float *root_x, hipStream_t st);
+                           float *root_x, int T, const uint8_t *keep_g, hipStream_t st);
 bool plan_fused_fits(int N, int T);
 vcas_status plan_fused(const void *G, int K_out, const void *X, int K_in, int dtype, int N, int T, double budget_a,
                        double budget_w, int token_sampling, const vcas_rng &rng, float *uniforms, uint32_t *ticket,
@@ -45,12 +45,13 @@ int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens);
 int wgrad_tiles_bf16(int K_out, int K_in, int tile);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, const void *J, int64_t expected_rows, hipStream_t st);
+                       const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
+                       hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
                        hipStream_t st);
 vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                      const int32_t *cntA, void *dX, const void *J, hipStream_t st);
+                      const int32_t *cntA, void *dX, const void *J, bool fill, hipStream_t st);
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
                       const int32_t *cntW, float *dW, float *partials, int splits, hipStream_t st);
 
@@ -136,13 +137,14 @@ __global__ __launch_bounds__(64) void sq_diff_final_kernel(const double *__restr
     *out += weight * s;
 }
 
-// J: elementwise Jacobian [R, K_in] in the layer dtype, multiplied into dX (null: none)
+// J: elementwise Jacobian [R, K_in] in the layer dtype, multiplied into dX (null: none);
+// fill: write zero rows for the samples that are not kept
 static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
-                                  const int32_t *idxA, const int32_t *cntA, void *dX, const void *J,
+                                  const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
                                   int64_t expected_rows, hipStream_t st)
 {
-    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, expected_rows, st)
-                                : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, st);
+    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, fill, expected_rows, st)
+                                : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, fill, st);
 }
 
 // expected_tokens: how many tokens the caller expects SampleW to keep (R if unknown); it only
@@ -198,21 +200,31 @@ static float *uniforms_of(const vcas_shape &s, void *workspace)
 }
 
 // Data half: row norms of G (and of X, with the SampleW uniforms, on small layers), SampleA, dX.
+// What a layer inside a stack adds to the data half (all optional).
+struct ChainArgs {
+    const void *J = nullptr;              // elementwise Jacobian multiplied into dX
+    const uint8_t *kept_above = nullptr;  // samples whose rows of G exist at all (the others count as zero)
+    bool fill = true;                     // write zero rows of dX for the samples that are not kept
+};
+
 static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
-                             const vcas_rng &rng, int token_sampling, const vcas_plan &pl, void *dX, const void *J,
-                             void *workspace, hipStream_t st)
+                             const vcas_rng &rng, int token_sampling, const vcas_plan &pl, void *dX,
+                             const ChainArgs &chain, void *workspace, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
     // together: the square roots SampleW needs travel in the plan's score and q arrays until
     // SampleW overwrites them with their final contents
     if (norms_together(s))
-        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, pl.score, pl.q, st));
+        VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, pl.score, pl.q, s.T,
+                                chain.kept_above, st));
     else
-        VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, nullptr, pl.gsq, st));
+        VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, chain.kept_above, pl.gsq, st));
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
     // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
-    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, J, (int64_t)((double)R * rho + 0.5), st));
+    if (dX)
+        VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill,
+                                (int64_t)((double)R * rho + 0.5), st));
     return VCAS_OK;
 }
 
@@ -251,21 +263,21 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
                                                          workspace_layout(&s).control);
         VCAS_TRY(plan_fused(G, s.K_out, X, s.K_in, s.dtype, s.N, s.T, (double)s.N * rho, (double)R * rho * nu,
                             token_sampling, rng, uniforms_of(s, workspace), tickets, pl, st));
-        if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, nullptr, (int64_t)((double)R * rho + 0.5), st));
+        if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, nullptr, true, (int64_t)((double)R * rho + 0.5), st));
         if (dW)
             VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
                                     (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));
         return VCAS_OK;
     }
     if (!forked) {
-        VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, dX, nullptr, workspace, st));
+        VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, dX, ChainArgs(), workspace, st));
         return weight_half(s, G, X, rho, nu, rng, token_sampling, pl, dW, workspace, st);
     }
     // The weight half needs SampleA's outcome but not dX: order it after SampleA, beside dX.
-    VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, nullptr, nullptr, workspace, st));
+    VCAS_TRY(data_half(s, G, X, W, rho, rng, token_sampling, pl, nullptr, ChainArgs(), workspace, st));
     hipEvent_t ev = fork_event();
     if (!ev || hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(side, ev, 0) != hipSuccess) return VCAS_EHIP;
-    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, nullptr, (int64_t)((double)R * rho + 0.5), st));
+    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, nullptr, true, (int64_t)((double)R * rho + 0.5), st));
     return weight_half(s, G, X, rho, nu, rng, token_sampling, pl, dW, workspace, side);
 }
 
@@ -367,7 +379,7 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
     VCAS_TRY(check_gemm_limits(shape));
     if (!G || !W || !p || !idxA || !cntA || !dX) return VCAS_ENULL;
     if (!aligned16(G) || !aligned16(W) || !aligned16(dX)) return VCAS_EINVAL;
-    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, nullptr, 0, as_stream(stream));
+    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, nullptr, true, 0, as_stream(stream));
 }
 
 vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const void *W, const float *p,
@@ -377,7 +389,7 @@ vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const
     VCAS_TRY(check_gemm_limits(shape));
     if (!G || !W || !p || !idxA || !cntA || !J || !dX) return VCAS_ENULL;
     if (!aligned16(G) || !aligned16(W) || !aligned16(J) || !aligned16(dX)) return VCAS_EINVAL;
-    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, J, 0, as_stream(stream));
+    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, J, true, 0, as_stream(stream));
 }
 
 vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X, const float *row_scale_,
@@ -420,21 +432,29 @@ vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const voi
     if (!ratio_ok(rho)) return VCAS_EINVAL;
     if (!aligned16(G) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || !aligned16(workspace))
         return VCAS_EINVAL;
-    return data_half(*shape, G, X, W, rho, *rng, token_sampling, *plan, dX, nullptr, workspace, as_stream(stream));
+    return data_half(*shape, G, X, W, rho, *rng, token_sampling, *plan, dX, ChainArgs(), workspace, as_stream(stream));
 }
 
-vcas_status vcas_backward_data_jac(const vcas_shape *shape, const void *G, const void *X, const void *W,
-                                   const void *J, double rho, const vcas_rng *rng, int32_t token_sampling,
-                                   const vcas_plan *plan, void *dX, void *workspace, void *stream)
+vcas_status vcas_backward_data_chained(const vcas_shape *shape, const void *G, const void *X, const void *W,
+                                       const void *J, const uint8_t *kept_above, int32_t fill_dropped_rows,
+                                       double rho, const vcas_rng *rng, int32_t token_sampling,
+                                       const vcas_plan *plan, void *dX, void *workspace, void *stream)
 {
     VCAS_TRY(check_shape(shape));
     VCAS_TRY(check_gemm_limits(shape));
-    if (!G || !X || !W || !J || !dX || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (!G || !X || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (dX && !W) return VCAS_ENULL;
+    if (J && !dX) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
     if (!ratio_ok(rho)) return VCAS_EINVAL;
-    if (!aligned16(G) || !aligned16(X) || !aligned16(W) || !aligned16(J) || !aligned16(dX) || !aligned16(workspace))
+    if (!aligned16(G) || !aligned16(X) || (W && !aligned16(W)) || (J && !aligned16(J)) || (dX && !aligned16(dX)) ||
+        !aligned16(workspace))
         return VCAS_EINVAL;
-    return data_half(*shape, G, X, W, rho, *rng, token_sampling, *plan, dX, J, workspace, as_stream(stream));
+    ChainArgs chain;
+    chain.J = J;
+    chain.kept_above = kept_above;
+    chain.fill = fill_dropped_rows != 0;
+    return data_half(*shape, G, X, W, rho, *rng, token_sampling, *plan, dX, chain, workspace, as_stream(stream));
 }
 
 vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,

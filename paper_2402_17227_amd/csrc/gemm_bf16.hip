@@ -355,7 +355,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   const int32_t *__restrict__ cntA,
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
                                                                   int K_out, int tiles_n,
-                                                                  const uint16_t *__restrict__ J)
+                                                                  const uint16_t *__restrict__ J, int fill_dropped)
 {
     constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -382,6 +382,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
 
     if ((int)blockIdx.x >= compute8) {
         // zero-fill duty: rows of the samples that are not in the kept list
+        if (!fill_dropped) return;
         const int z = blockIdx.x - compute8;
         const int64_t d0 = (int64_t)(z / tiles_n) * BM;
         const int n0 = (z % tiles_n) * BN;
@@ -439,17 +440,27 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
         const int col = n0 + ((lane % B_SLOTS) ^ wswz(krow)) * 8;
         b_off[j] = col < K_in ? ((uint32_t)krow * (uint32_t)K_in + (uint32_t)col) * 2u : kOutside;
     }
+    const int steps = (K_out + BK - 1) / BK;
+    // 16-byte pieces of a G row that the last step still owns (8 unless K_out is ragged).  The
+    // pieces behind them lie in the NEXT row of G: they meet zero rows of W, but zero times
+    // whatever that row holds (a NaN, an Inf, a row nobody has written) is not zero, so they are
+    // not fetched.
+    const int tail_pieces = (K_out - (steps - 1) * BK + 7) / 8;
     // the d-th of the LOADS loads of contraction step `step` into stage `stage`: G and W pieces alternate
     auto issue_nth = [&](int d, int stage, int step) {
         const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + wave * AI * 1024);
         const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + B_AT + wave * BI * 1024);
         const uint32_t kb = __builtin_amdgcn_readfirstlane(step * BK * 2);
         const uint32_t wb = __builtin_amdgcn_readfirstlane(step * BK * K_in * 2);
+        const int pieces = step == steps - 1 ? tail_pieces : 8;
         int seen = 0;
 #pragma unroll
         for (int j = 0; j < (AI > BI ? AI : BI); ++j) {
             if (j < AI) {
-                if (seen == d) lds_direct_load16(descG, a_dst + j * 1024, a_off[j], kb);
+                if (seen == d) {
+                    const int piece = (lane & 7) ^ swz((wave * AI + j) * 8 + (lane >> 3));
+                    lds_direct_load16(descG, a_dst + j * 1024, piece < pieces ? a_off[j] : kOutside, kb);
+                }
                 ++seen;
             }
             if (j < BI) {
@@ -458,8 +469,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
             }
         }
     };
-    const int steps = (K_out + BK - 1) / BK;
-    // prologue: steps 0 .. NS-2 in flight (a step past the end loads zeros and keeps the counts uniform)
+    // prologue: steps 0 .. NS-2 in flight (a step past the end fills a stage nobody reads and keeps the counts uniform)
 #pragma unroll
     for (int d = 0; d < NS - 1; ++d)
 #pragma unroll
@@ -1007,11 +1017,13 @@ static bool allow_lds(Kern kern, size_t bytes)
 
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
-                                const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, hipStream_t st)
+                                const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
+                                hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
-    const int64_t grid = tiles_n * ((R + BM - 1) / BM + 1) + 8;
+    // without zero-fill duty the ids past the compute tiles have nothing to do
+    const int64_t grid = tiles_n * ((R + BM - 1) / BM + (fill ? 1 : 0)) + 8;
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
     const size_t lds = NS * (BM + BN) * 128 + BM * 8;
     auto kern = dgrad_bf16_kernel<BM, BN, WM, WN, NS, OCC, SPQ>;
@@ -1022,15 +1034,17 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                 s.K_out, tiles_n, static_cast<const uint16_t *>(J));
+                 s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0);
     return launch_status();
 }
 
 // expected_rows: how many of the R rows the caller expects to be kept (R if unknown); it only
 // steers the tile choice, any count is computed correctly by every variant.
-// J: elementwise Jacobian [R, K_in] multiplied into dX, or null.
+// J: elementwise Jacobian [R, K_in] multiplied into dX, or null.  fill: write the zero rows of
+// dropped samples (false: leave them as they are).
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                       const int32_t *cntA, void *dX, const void *J, int64_t expected_rows, hipStream_t st)
+                       const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
+                       hipStream_t st)
 {
     // The loads into LDS run at about 40 bytes per clock and CU, so the largest tile that still
     // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 192 tiles up; else 128x128
@@ -1043,11 +1057,11 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, st);
-    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, st);
+    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, st);
+    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
-    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, st);
-    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, st);
+    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, st);
+    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, st);
 }
 
 template <int BM, int BN, int WM, int WN, int OCC>

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
                                                         const int32_t *__restrict__ idxA,
                                                         const int32_t *__restrict__ cntA, float *__restrict__ dX,
                                                         int N, int T, int K_in, int K_out, int tiles_n,
-                                                        const float *__restrict__ J)
+                                                        const float *__restrict__ J, int fill_dropped)
 {
     using namespace f32gemm;
     __shared__ __attribute__((aligned(16))) float As[2][TILE_FLOATS];
@@ -86,6 +86,7 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
     const int tid = threadIdx.x;
 
     if ((int)blockIdx.x >= compute8) {
+        if (!fill_dropped) return;
         const int z = blockIdx.x - compute8;
         const int64_t d0 = (int64_t)(z / tiles_n) * BM;
         const int n0 = (z % tiles_n) * BN;
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict_
 int wgrad_tiles_f32(int K_out, int K_in) { return ((K_out + 63) / 64) * ((K_in + 63) / 64); }
 
 vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
-                      const int32_t *cntA, void *dX, const void *J, hipStream_t st)
+                      const int32_t *cntA, void *dX, const void *J, bool fill, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + 63) / 64;
@@ -276,7 +277,7 @@ vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const f
     if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
     launch_timed(0, dgrad_f32_kernel, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const float *>(G),
                        static_cast<const float *>(W), p, idxA, cntA, static_cast<float *>(dX), s.N, s.T, s.K_in,
-                       s.K_out, tiles_n, static_cast<const float *>(J));
+                       s.K_out, tiles_n, static_cast<const float *>(J), fill ? 1 : 0);
     return launch_status();
 }
 

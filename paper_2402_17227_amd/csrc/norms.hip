@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict_
     }
 }
 
+// (keep_a, T: as sample_keep above, for the rows of A only.)
 // Row norms of two matrices with the same number of rows in one launch (G and X
 // of a layer when both are small enough that a second launch would cost more
 // than reading the rows of X that SampleA is about to drop): wavefronts
@@ -57,7 +58,8 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
                                                              float *__restrict__ out_a, const uint4 *__restrict__ B,
                                                              int groups_b, float *__restrict__ out_b, int64_t R,
                                                              UniformJob job, float *__restrict__ root_a,
-                                                             float *__restrict__ root_b)
+                                                             float *__restrict__ root_b, int T,
+                                                             const uint8_t *__restrict__ keep_a)
 {
     if (job.uniforms) {
         const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
@@ -71,7 +73,9 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
         const bool second = w >= R;
         const int64_t row = second ? w - R : w;
         const int groups = second ? groups_b : groups_a;
-        const float acc = wave_row_sumsq<BF16, CH>((second ? B : A) + row * groups, groups);
+        // rows of A that belong to samples with keep_a == 0 are not read and count as zero
+        const bool skip = !second && keep_a && keep_a[row / T] == 0;
+        const float acc = skip ? 0.0f : wave_row_sumsq<BF16, CH>((second ? B : A) + row * groups, groups);
         if (lane == 0) {
             (second ? out_b : out_a)[row] = acc;
             // the square roots SampleW multiplies, taken here by many workgroups (null: not wanted)
@@ -140,7 +144,8 @@ vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K
 
 template <bool BF16>
 static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void *B, int K_b, float *out_b, int64_t R,
-                               const UniformJob &job, float *root_a, float *root_b, hipStream_t st)
+                               const UniformJob &job, float *root_a, float *root_b, int T, const uint8_t *keep_a,
+                               hipStream_t st)
 {
     const int ga = K_a / (BF16 ? 8 : 4), gb = K_b / (BF16 ? 8 : 4);
     const int need = ((ga > gb ? ga : gb) + 63) / 64;
@@ -149,7 +154,7 @@ static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void 
     const uint4 *a = static_cast<const uint4 *>(A), *b = static_cast<const uint4 *>(B);
 #define VCAS_LAUNCH_CH(C)                                                                                         \
     hipLaunchKernelGGL((row_sumsq_pair_kernel<BF16, C>), dim3(blocks), dim3(256), 0, st, a, ga, out_a, b, gb, out_b, \
-                       R, job, root_a, root_b)
+                       R, job, root_a, root_b, T, keep_a)
     if (need <= 2) VCAS_LAUNCH_CH(2);
     else if (need <= 4) VCAS_LAUNCH_CH(4);
     else VCAS_LAUNCH_CH(8);
@@ -159,14 +164,15 @@ static vcas_status launch_pair(const void *A, int K_a, float *out_a, const void 
 
 // gsq of every row of G, xsq of EVERY row of X (the caller zeroes the rows of dropped samples
 // later), their square roots (root_g, root_x; null: not wanted) and the uniforms of sampler
-// `stream_id`, one launch
+// `stream_id`, one launch; keep_g (null: all): samples whose rows of G are read at all
 vcas_status row_sumsq_pair(const void *G, int K_out, float *gsq, const void *X, int K_in, float *xsq, int dtype,
                            int64_t R, const vcas_rng &rng, uint32_t stream_id, float *uniforms, float *root_g,
-                           float *root_x, hipStream_t st)
+                           float *root_x, int T, const uint8_t *keep_g, hipStream_t st)
 {
     const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
-    return dtype == VCAS_BF16 ? launch_pair<true>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, st)
-                              : launch_pair<false>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, st);
+    return dtype == VCAS_BF16
+               ? launch_pair<true>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, T, keep_g, st)
+               : launch_pair<false>(G, K_out, gsq, X, K_in, xsq, R, job, root_g, root_x, T, keep_g, st);
 }
 
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st)

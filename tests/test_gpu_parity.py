@@ -169,6 +169,35 @@ def test_dgrad_with_given_mask(vb, dtype, N, T, kin, kout, keep):
         assert rel_l2(got, want) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N,T,kin,kout", [(6, 40, 136, 136), (9, 64, 768, 200), (5, 33, 72, 72)])
+def test_dgrad_never_reads_rows_of_dropped_samples(vb, dtype, N, T, kin, kout):
+    """Rows of G that belong to dropped samples hold NaN: nothing of them may reach dX, not even through
+    the zero-padded tail of a ragged contraction (K_out not a multiple of the step), where a row's last
+    pieces are followed in memory by the next row."""
+    rng = np.random.default_rng(kin * 7 + kout)
+    R = N * T
+    g = rng.standard_normal((R, kout)).astype(np.float32)
+    w = (rng.standard_normal((kout, kin)) * 0.05).astype(np.float32)
+    p = rng.uniform(0.2, 1, N).astype(np.float32)
+    maskA = np.array([(i % 2) == 0 for i in range(N)], np.uint8)           # every kept sample has a dropped neighbour
+    G, W = (workloads.f32_to_bf16_bits(a) if dtype == BF16 else a for a in (g, w))
+    idxA = np.nonzero(maskA)[0].astype(np.int32)
+    idx_buf = np.full(N, -1, np.int32)
+    idx_buf[:idxA.size] = idxA
+    g_dev = _dev(G, dtype).clone()
+    g_dev[torch.from_numpy(np.repeat(maskA == 0, T)).cuda()] = float("nan")
+    shape = vb.shape_of(N, T, kin, kout, dtype)
+    dX = torch.full((R, kin), float("nan"), dtype=torch.bfloat16 if dtype == BF16 else torch.float32, device="cuda")
+    vb.vcas_sampled_dgrad(shape, g_dev, _dev(W, dtype), _dev(p), _dev(idx_buf), _dev(np.array([idxA.size], np.int32)), dX)
+    torch.cuda.synchronize()
+    from tests.gpu_util import from_device, rel_l2
+    got = from_device(dX)
+    assert np.isfinite(got).all()
+    assert np.all(got[np.repeat(maskA == 0, T)] == 0)
+    assert rel_l2(got, oracle.dgrad(G, W, dtype, N, T, p, maskA)) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("N,T,kin,kout,frac", [(17, 128, 2040, 136, 1.0),     # 128x128 tiles, ragged columns
                                                 (17, 128, 2040, 136, 0.6),
                                                 (33, 125, 3080, 200, 1.0),     # 256x256 tiles, ragged rows and columns
@@ -431,7 +460,7 @@ def test_dgrad_through_an_elementwise_jacobian(vb, dtype, N, T, kin, kout, frac)
 
 def test_chained_layers_through_relu_jacobians(vb):
     """Two linears with an elementwise layer between them: the upper layer's data half writes
-    (dX * J) (vcas_backward_data_jac), which is the lower layer's G as it stands."""
+    (dX * J) (vcas_backward_data_chained), which is the lower layer's G as it stands."""
     from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
     N, T, K = 16, 48, 136
     rng = np.random.default_rng(11)
@@ -444,7 +473,7 @@ def test_chained_layers_through_relu_jacobians(vb):
     ws = vb.make_workspace(shape)
     dX = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
     dW = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
-    vb.vcas_backward_data_jac(shape, g, x, w, jac, 0.7, vb.Rng(5, 0, 0), True, plan, dX, ws)
+    vb.vcas_backward_data_chained(shape, g, x, w, jac, None, True, 0.7, vb.Rng(5, 0, 0), True, plan, dX, ws)
     vb.vcas_backward_weight(shape, g, x, 0.7, 0.5, vb.Rng(5, 0, 0), True, plan, dW, ws)
     torch.cuda.synchronize()
     want, _, want_dW = oracle.linear_backward(G_host, X_host, W_host, BF16, N, T, 0.7, 0.5, 5, 0, 0)
@@ -467,6 +496,63 @@ def test_chained_layers_through_relu_jacobians(vb):
     assert rel_l2(from_device(dX2), want_dX2) <= TOL[BF16] and rel_l2(from_device(dW2), want_dW2) <= TOL[BF16]
     dropped = want.maskA == 0
     assert np.all(got2["p"][dropped] == 0) and not np.any(got2["maskA"][dropped])
+
+
+@pytest.mark.parametrize("dtype,K_in", [(BF16, 136), (F32, 72), (BF16, 4096)])
+def test_chained_layers_without_zero_fill(vb, dtype, K_in):
+    """A stack in its sparse form: no layer writes the rows of samples it drops (they keep the NaN they
+    were initialised with) and the layer below is told which samples exist (kept_above = the upper
+    layer's maskA), so it never reads them.  The oracle gets the same tensors with those rows zeroed.
+    K_in = 4096 takes the path that norms X after SampleA (X above 16 MiB)."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    N, T, K = (24, 90, 136) if K_in == 4096 else (24, 40, K_in)
+    K_out = K
+    rhos, nu = [0.8, 0.6, 0.4], 0.5
+    rng = np.random.default_rng(23)
+    top = workloads.LayerSpec("sparse_chain", dtype, N, T, K_out, K_out, rhos[0], nu, layer=0, seed=8, gen_seed=31,
+                              token_sigma=0.5)
+    G_host, _, _ = workloads.make_layer(top)
+    g = to_device(G_host, dtype)
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+    kept_above_dev = None
+    kept_above = np.ones(N, bool)
+    conv = (lambda a: workloads.f32_to_bf16_bits(a)) if dtype == BF16 else (lambda a: a)
+    for l, rho in enumerate(rhos):
+        k_in = K_in if l == 0 else K_out            # only the top layer is wide; its dX feeds a K_out-wide G below
+        k_out = K_out if l == 0 else (K_in if l == 1 else K_out)
+        shape = vb.shape_of(N, T, k_in, k_out, dtype)
+        X_host = conv(rng.standard_normal((N * T, k_in)).astype(np.float32))
+        W_host = conv((rng.standard_normal((k_out, k_in)) * 0.1).astype(np.float32))
+        J_host = conv((rng.uniform(size=(N * T, k_in)) < 0.7).astype(np.float32))
+        x, w, jac = (to_device(a, dtype) for a in (X_host, W_host, J_host))
+        plan = vb.Plan.allocate(N, T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full((N * T, k_in), float("nan"), dtype=tdt, device="cuda")
+        dW = torch.full((k_out, k_in), float("nan"), dtype=torch.float32, device="cuda")
+        r = vb.Rng(8, l, 0)
+        vb.vcas_backward_data_chained(shape, g, x, w, jac, kept_above_dev, False, rho, r, True, plan, dX, ws)
+        vb.vcas_backward_weight(shape, g, x, rho, nu, r, True, plan, dW, ws)
+        torch.cuda.synchronize()
+        G_fed = from_device(g).astype(np.float32)
+        assert np.isnan(G_fed[np.repeat(~kept_above, T)]).all() or kept_above.all()
+        G_fed[np.repeat(~kept_above, T)] = 0.0                             # what those rows stand for
+        G_fed = conv(G_fed)
+        want, _, want_dW = oracle.linear_backward(G_fed, X_host, W_host, dtype, N, T, rho, nu, 8, l, 0)
+        want_dX = oracle.dgrad_jacobian(G_fed, W_host, J_host, dtype, N, T, want.p, want.maskA)
+        got = plan_to_numpy(plan)
+        compare_plan(got, want)
+        kept = got["maskA"].astype(bool)
+        assert not np.any(kept & ~kept_above)
+        got_dX = from_device(dX)
+        kept_rows = np.repeat(kept, T)
+        assert np.isnan(got_dX[~kept_rows]).all()                          # untouched
+        assert np.isfinite(got_dX[kept_rows]).all()
+        if kept.any():
+            assert rel_l2(got_dX[kept_rows], want_dX[kept_rows]) <= TOL[dtype]
+        assert rel_l2(from_device(dW), want_dW) <= TOL[dtype]
+        kept_above, kept_above_dev = kept, plan.maskA
+        g = dX
+    assert kept_above.sum() < N
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
