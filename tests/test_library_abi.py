@@ -66,6 +66,19 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
                                     C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null, null) == 2
     assert lib.vcas_variance_probe(C.byref(good), fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
                                    C.c_int32(0), C.byref(plan), fake, fake, null) == 1
+    # the Jacobian and the stack variants: J is required where the name says so, needs a dX where it is
+    # optional, and is held to the same alignment as the other tensors
+    assert lib.vcas_sampled_dgrad_jac(C.byref(good), fake, fake, fake, fake, fake, null, fake, null) == 2
+    assert lib.vcas_sampled_dgrad_jac(C.byref(good), fake, fake, fake, fake, fake, C.c_void_p(0x1008), fake, null) == 1
+    chained = lib.vcas_backward_data_chained
+    assert chained(C.byref(good), fake, fake, fake, fake, null, C.c_int32(1), C.c_double(0.5), C.byref(rng),
+                   C.c_int32(1), C.byref(plan), null, fake, null) == 2           # J without dX
+    assert chained(C.byref(good), fake, fake, null, null, null, C.c_int32(1), C.c_double(0.5), C.byref(rng),
+                   C.c_int32(1), C.byref(plan), fake, fake, null) == 2           # dX without W
+    assert chained(C.byref(good), fake, fake, fake, null, null, C.c_int32(0), C.c_double(0.0), C.byref(rng),
+                   C.c_int32(1), C.byref(plan), fake, fake, null) == 1           # rho
+    assert chained(C.byref(good), fake, fake, fake, null, null, C.c_int32(0), C.c_double(0.5), C.byref(rng),
+                   C.c_int32(1), C.byref(plan), fake, null, null) == 4           # workspace
 
 
 def test_binding_refuses_to_run_without_the_library(vb, monkeypatch, tmp_path):
