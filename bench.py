@@ -105,6 +105,12 @@ def main():
     ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
     ap.add_argument("--side-streams", type=int, default=1, help="streams the weight-gradient halves rotate over")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
+    ap.add_argument("--stack", type=int, default=4, metavar="GROUP",
+                    help="the default launch: one vcas_backward_stack call per step (from the host, no graph), "
+                         "cross-stream dependencies once per GROUP layers, SampleW and dW on two side streams; "
+                         "0 = per-layer calls (see --graph-free options below)")
+    ap.add_argument("--graph", action="store_true",
+                    help="per-layer vcas_linear_backward calls captured in one HIP graph per step instead")
     ap.add_argument("--share-inputs", action="store_true",
                     help="layers of equal shape get copies of the same generated values (each layer still owns its "
                          "tensors in HBM); saves minutes of host-side generation on the 144-layer workloads")
@@ -136,16 +142,31 @@ def main():
     # every replay: each step first bumps the counter, every layer adds it to its draw.
     draw_counter = torch.zeros(1, dtype=torch.int32, device="cuda")
 
-    # Two streams: norms of G, SampleA and dX of every layer run in order on the main stream (the
-    # order a real backward pass imposes), each layer's weight-gradient half (norms of X, SampleW,
-    # dW) follows its SampleA on the side stream; the step ends when both have drained.
-    # The weight gradients of different layers do not depend on each other, so their halves rotate
-    # over a few side streams and may overlap one another as well.
+    # Norms of G, SampleA and dX of every layer run in order on the main stream (the order a real
+    # backward pass imposes); each layer's weight-gradient half (norms of X, SampleW, dW) depends on
+    # its SampleA only and runs beside that.  Default launch: vcas_backward_stack, which puts SampleW
+    # and dW on two side streams and pays the cross-stream waits once per group of layers.
+    # --graph: per-layer vcas_linear_backward calls, weight halves on side stream(s), one HIP
+    # graph per step.  The step ends when every stream has drained.
     sides = [] if args.one_stream else [torch.cuda.Stream() for _ in range(args.side_streams)]
+
+    stack = None
+    if args.graph or args.eager or args.one_stream or args.counters_pass:
+        args.stack = 0
+    if args.stack > 0:
+        stack = vb.make_stack([vb.layer_args(l.shape, l.G, l.X, l.W, l.spec.rho, l.spec.nu,
+                                             vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
+                                             l.plan, l.dX, l.dW, l.ws) for l in layers])
+        s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 
     def step():
         main = torch.cuda.current_stream()
         draw_counter.add_(1)
+        if stack is not None:
+            vb.vcas_backward_stack(stack, args.stack, s2, s3)
+            main.wait_stream(s2)
+            main.wait_stream(s3)
+            return
         for sd in sides:
             sd.wait_stream(main)
         for k, l in enumerate(layers):
@@ -167,9 +188,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         return
-    if args.eager:
+    if args.eager or stack is not None:
         run_step = step
-    else:                                        # the ~580 launches of a step as one HIP graph
+    else:                                        # the ~500 launches of a step as one HIP graph
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
@@ -256,7 +277,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "launch": ("eager" if args.eager else "hip_graph") + (", one stream" if args.one_stream else f", dW halves on {args.side_streams} side streams"),
+        "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
+                   if stack is not None else
+                   ("eager" if args.eager else "hip_graph") +
+                   (", one stream" if args.one_stream else f", dW halves on {args.side_streams} side streams")),
         "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,

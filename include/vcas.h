@@ -10,7 +10,7 @@
  *
  * Conventions that hold for every call:
  *  - Every pointer is a DEVICE pointer unless its comment says "host".
- *    Structs (vcas_shape, vcas_rng, vcas_plan) are read on the host.
+ *    Structs (vcas_shape, vcas_rng, vcas_plan, vcas_layer_args) are read on the host.
  *  - Tensors are dense row-major.  dtype VCAS_F32: float; VCAS_BF16: 16-bit
  *    bfloat16 bit patterns.  K_in and K_out must be multiples of 8 (one 16-byte
  *    vector of bf16; fp32 needs only a multiple of 4 but the same rule is kept),
@@ -208,6 +208,39 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
                                  double rho, double nu, const vcas_rng *rng, int32_t token_sampling,
                                  const vcas_plan *plan, void *dX, float *dW, void *workspace,
                                  void *stream, void *side_stream);
+
+/* One layer of a stack: the arguments of vcas_linear_backward (host struct). */
+typedef struct {
+    vcas_shape shape;
+    const void *G, *X, *W;
+    double rho, nu;
+    vcas_rng rng;
+    int32_t token_sampling;
+    vcas_plan plan;
+    void *dX;        /* may be null */
+    float *dW;       /* may be null */
+    void *workspace; /* of this layer's shape; layers must not share one */
+} vcas_layer_args;
+
+/*
+ * A stack of L layers in one call: computes, bit for bit, what calling
+ * vcas_linear_backward on layers[0], layers[1], ... computes, with the launches
+ * laid out over up to three streams so that a dependency between streams is
+ * paid once per group of layers instead of once per layer (on this hardware a
+ * cross-stream wait costs about as much as two small kernels):
+ *   stream          data halves (row norms of G, SampleA, dX) in layer order, as
+ *                   a backward pass imposes;
+ *   sampler_stream  for each group of `group` consecutive layers, after the
+ *                   group's last SampleA: row norms of X where still due, SampleW;
+ *   gemm_stream     after the group's SampleW: dW (and its split-K reduction).
+ * sampler_stream and gemm_stream may be the same stream, or null (= `stream`).
+ * layers: HOST array, read during the call only.  group >= 1.  The call joins
+ * nothing: results of the weight halves are complete when the streams they ran
+ * on have drained.  All streams at default priority.  Meant for eager launching;
+ * under graph capture it is correct but gains nothing over per-layer calls.
+ */
+vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_t group, void *stream,
+                                void *sampler_stream, void *gemm_stream);
 
 /*
  * The two halves of vcas_linear_backward as calls of their own, for callers

@@ -19,7 +19,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
+    "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
 ]
 
@@ -40,6 +40,13 @@ class Rng(C.Structure):
 class PlanPtrs(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("gsq", "gnorm", "p", "maskA", "idxA", "cntA", "xsq", "score", "q",
                                           "maskW", "idxW", "cntW", "scaleW")]
+
+
+class LayerArgs(C.Structure):
+    """vcas_layer_args"""
+    _fields_ = [("shape", Shape), ("G", C.c_void_p), ("X", C.c_void_p), ("W", C.c_void_p), ("rho", C.c_double),
+                ("nu", C.c_double), ("rng", Rng), ("token_sampling", C.c_int32), ("plan", PlanPtrs),
+                ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p)]
 
 
 _lib = None
@@ -187,6 +194,33 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
     _check(lib().vcas_linear_backward(C.byref(shape), _ptr(G), _ptr(X), _ptr(W), C.c_double(rho), C.c_double(nu),
                                       C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dX),
                                       _ptr(dW), _ptr(workspace), _stream(), side), "vcas_linear_backward")
+
+
+def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dX, dW,
+               workspace) -> LayerArgs:
+    """One entry of the array vcas_backward_stack takes (the tensors must stay alive while it is used)."""
+    a = LayerArgs()
+    a.shape = shape
+    a.G, a.X, a.W = _ptr(G), _ptr(X), _ptr(W)
+    a.rho, a.nu = rho, nu
+    a.rng = rng
+    a.token_sampling = 1 if token_sampling else 0
+    a.plan = plan.ptrs()
+    a.dX, a.dW, a.workspace = _ptr(dX), _ptr(dW), _ptr(workspace)
+    return a
+
+
+def make_stack(entries):
+    """A C array of LayerArgs from a list of them."""
+    return (LayerArgs * len(entries))(*entries)
+
+
+def vcas_backward_stack(stack, group: int, sampler_stream=None, gemm_stream=None):
+    """stack: what make_stack returned; streams: torch.cuda.Stream or None; runs on the current stream."""
+    s2 = C.c_void_p(sampler_stream.cuda_stream if sampler_stream is not None else 0)
+    s3 = C.c_void_p(gemm_stream.cuda_stream if gemm_stream is not None else 0)
+    _check(lib().vcas_backward_stack(stack, C.c_int32(len(stack)), C.c_int32(group), _stream(), s2, s3),
+           "vcas_backward_stack")
 
 
 def vcas_backward_data(shape: Shape, G, X, W, rho: float, rng: Rng, token_sampling: bool, plan: Plan, dX, workspace):

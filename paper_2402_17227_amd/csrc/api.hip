@@ -420,6 +420,63 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
                                 as_stream(stream), as_stream(side_stream));
 }
 
+vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_t group, void *stream,
+                                void *sampler_stream, void *gemm_stream)
+{
+    if (!layers) return VCAS_ENULL;
+    if (L <= 0 || group <= 0) return VCAS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    hipStream_t s2 = sampler_stream ? as_stream(sampler_stream) : st;
+    hipStream_t s3 = gemm_stream ? as_stream(gemm_stream) : s2;
+    for (int l = 0; l < L; ++l) {
+        const vcas_layer_args &a = layers[l];
+        VCAS_TRY(check_shape(&a.shape));
+        VCAS_TRY(check_gemm_limits(&a.shape));
+        if (!a.G || !a.X || !plan_complete(&a.plan)) return VCAS_ENULL;
+        if (a.dX && !a.W) return VCAS_ENULL;
+        if (!a.workspace) return VCAS_EWORKSPACE;
+        if (!ratio_ok(a.rho) || !ratio_ok(a.nu)) return VCAS_EINVAL;
+        if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
+            (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
+            return VCAS_EINVAL;
+    }
+    // two events per group, created on first use and kept
+    static std::vector<hipEvent_t> events;
+    const int groups = (L + group - 1) / group;
+    while ((int)events.size() < 2 * groups) {
+        hipEvent_t ev;
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return VCAS_EHIP;
+        events.push_back(ev);
+    }
+    for (int g = 0; g < groups; ++g) {
+        const int l0 = g * group, l1 = l0 + group < L ? l0 + group : L;
+        for (int l = l0; l < l1; ++l) {
+            const vcas_layer_args &a = layers[l];
+            VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
+                               a.workspace, st));
+        }
+        if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
+                         hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))
+            return VCAS_EHIP;
+        for (int l = l0; l < l1; ++l) {
+            const vcas_layer_args &a = layers[l];
+            VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr, a.workspace,
+                                 s2));
+        }
+        if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
+                         hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
+            return VCAS_EHIP;
+        for (int l = l0; l < l1; ++l) {
+            const vcas_layer_args &a = layers[l];
+            if (!a.dW) continue;
+            const int64_t R = (int64_t)a.shape.N * a.shape.T;
+            VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
+                                    (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5), s3));
+        }
+    }
+    return VCAS_OK;
+}
+
 vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
                                const vcas_rng *rng, int32_t token_sampling, const vcas_plan *plan, void *dX,
                                void *workspace, void *stream)

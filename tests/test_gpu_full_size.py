@@ -1,8 +1,9 @@
 """Parity at the full sizes of the benchmark configurations, launched the way bench.py launches:
-vcas_linear_backward captured in a HIP graph, weight-gradient half on a side stream, draw index
-read from device memory.  The sampling plan is compared bit for bit with the oracle's; dX and dW
-are compared on entries drawn at random (the oracle computes them one by one), and on properties
-that hold everywhere (rows of dropped samples are zero, nothing is left unwritten)."""
+vcas_backward_stack from the host, SampleW and dW on two side streams, draw index read from device
+memory (and, for one layer of each model, the graph-replay launch bench.py offers as --graph).
+The sampling plan is compared bit for bit with the oracle's; dX and dW are compared on entries
+drawn at random (the oracle computes them one by one), and on properties that hold everywhere
+(rows of dropped samples are zero, nothing is left unwritten)."""
 from __future__ import annotations
 
 import numpy as np
@@ -53,25 +54,39 @@ def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
     dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda")
     dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
     counter = torch.zeros(1, dtype=torch.int32, device="cuda")
-    side = torch.cuda.Stream()
+    rng = vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr())
+    if spec.name.endswith(".b5.o") or spec.name.endswith(".b11.o"):
+        # the graph launch: one side stream, the step captured once and replayed
+        side = torch.cuda.Stream()
 
-    def step():
-        main = torch.cuda.current_stream()
-        counter.add_(1)
-        side.wait_stream(main)
-        vb.vcas_linear_backward(shape, g, x, w, spec.rho, spec.nu, vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()),
-                                True, plan, dX, dW, ws, side)
-        main.wait_stream(side)
+        def step():
+            main = torch.cuda.current_stream()
+            counter.add_(1)
+            side.wait_stream(main)
+            vb.vcas_linear_backward(shape, g, x, w, spec.rho, spec.nu, rng, True, plan, dX, dW, ws, side)
+            main.wait_stream(side)
 
-    step()                                   # draw 1, eager
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        step()
-    dX.fill_(float("nan"))
-    dW.fill_(float("nan"))
-    graph.replay()                           # draw 2
-    graph.replay()                           # draw 3
+        step()                                   # draw 1, eager
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        dX.fill_(float("nan"))
+        dW.fill_(float("nan"))
+        graph.replay()                           # draw 2
+        graph.replay()                           # draw 3
+    else:
+        stack = vb.make_stack([vb.layer_args(shape, g, x, w, spec.rho, spec.nu, rng, True, plan, dX, dW, ws)])
+        s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+        for draw in (1, 2, 3):
+            main = torch.cuda.current_stream()
+            counter.add_(1)
+            if draw == 2:
+                dX.fill_(float("nan"))
+                dW.fill_(float("nan"))
+            vb.vcas_backward_stack(stack, 4, s2, s3)
+            main.wait_stream(s2)
+            main.wait_stream(s3)
     torch.cuda.synchronize()
     draw = int(counter.item())
     assert draw == 3

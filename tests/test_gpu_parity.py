@@ -555,6 +555,58 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
     assert kept_above.sum() < N
 
 
+@pytest.mark.parametrize("group,streams", [(1, 3), (2, 3), (3, 2), (5, 1)])
+def test_stack_of_layers_equals_layer_by_layer_calls(vb, group, streams):
+    """vcas_backward_stack lays the launches of several layers out over up to three streams; whatever the
+    grouping, every layer must come out bit for bit as from vcas_linear_backward, and as the oracle says."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    specs = [workloads.LayerSpec("st0", BF16, 8, 128, 768, 264, 0.5, 0.5, layer=0, seed=4, gen_seed=1, token_sigma=0.5),
+             workloads.LayerSpec("st1", F32, 6, 50, 72, 136, 0.6, 0.4, layer=1, seed=4, gen_seed=2, token_sigma=0.5),
+             workloads.LayerSpec("st2", BF16, 12, 300, 4096, 64, 0.5, 0.5, layer=2, seed=4, gen_seed=3, token_sigma=0.5),
+             workloads.LayerSpec("st3", BF16, 9, 33, 136, 200, 0.7, 0.5, layer=3, seed=4, gen_seed=4, token_sigma=0.5),
+             workloads.LayerSpec("st4", BF16, 16, 64, 256, 768, 1.0, 1.0, layer=4, seed=4, gen_seed=5, token_sigma=0.5)]
+    host, dev, refs, entries, outs = [], [], [], [], []
+    for sp in specs:
+        G, X, W = workloads.make_layer(sp)
+        shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+        g, x, w = (to_device(a, sp.dtype) for a in (G, X, W))
+        tdt = torch.bfloat16 if sp.dtype == BF16 else torch.float32
+        # reference: the per-layer call
+        plan_r = vb.Plan.allocate(sp.N, sp.T)
+        ws_r = vb.make_workspace(shape)
+        dX_r = torch.full((sp.R, sp.K_in), float("nan"), dtype=tdt, device="cuda")
+        dW_r = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
+        vb.vcas_linear_backward(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan_r, dX_r, dW_r, ws_r)
+        refs.append((plan_to_numpy(plan_r), dX_r, dW_r))
+        plan = vb.Plan.allocate(sp.N, sp.T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=tdt, device="cuda")
+        dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws))
+        outs.append((plan, dX, dW))
+        host.append((G, X, W))
+        dev.append((g, x, w, ws))
+    torch.cuda.synchronize()
+    stack = vb.make_stack(entries)
+    s2 = torch.cuda.Stream() if streams >= 2 else None
+    s3 = torch.cuda.Stream() if streams >= 3 else None
+    for _ in range(2):                                   # twice: the second call re-records the same events
+        vb.vcas_backward_stack(stack, group, s2, s3)
+    torch.cuda.synchronize()
+    for sp, (plan, dX, dW), (plan_r, dX_r, dW_r) in zip(specs, outs, refs):
+        got = plan_to_numpy(plan)
+        for key, val in plan_r.items():
+            assert np.array_equal(np.asarray(got[key]), np.asarray(val)), (sp.name, key)
+        assert torch.equal(dX.view(torch.int16) if dX.dtype == torch.bfloat16 else dX.view(torch.int32),
+                           dX_r.view(torch.int16) if dX_r.dtype == torch.bfloat16 else dX_r.view(torch.int32)), sp.name
+        assert torch.equal(dW.view(torch.int32), dW_r.view(torch.int32)), sp.name
+    sp = specs[2]
+    G, X, W = host[2]
+    want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 1)
+    compare_plan(plan_to_numpy(outs[2][0]), want)
+    assert rel_l2(from_device(outs[2][1]), want_dX) <= TOL[BF16] and rel_l2(from_device(outs[2][2]), want_dW) <= TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_variance_probe_matches_oracle(vb, dtype):
     spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)
