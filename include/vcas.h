@@ -238,6 +238,9 @@ typedef struct {
  * nothing: results of the weight halves are complete when the streams they ran
  * on have drained.  All streams at default priority.  Meant for eager launching;
  * under graph capture it is correct but gains nothing over per-layer calls.
+ * Every layer's arguments are checked before anything is launched.  The events
+ * that order the streams belong to the library and are shared by all calls:
+ * call it from one host thread at a time.
  */
 vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_t group, void *stream,
                                 void *sampler_stream, void *gemm_stream);

@@ -66,6 +66,24 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
                                     C.c_int32(1), C.byref(bad_plan), fake, fake, fake, null, null) == 2
     assert lib.vcas_variance_probe(C.byref(good), fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng),
                                    C.c_int32(0), C.byref(plan), fake, fake, null) == 1
+    # a stack of layers: the array itself, its length, the group size, and every entry's own arguments
+    stack_fn = lib.vcas_backward_stack
+    assert stack_fn(null, C.c_int32(3), C.c_int32(1), null, null, null) == 2
+    entry = vb.LayerArgs()
+    entry.shape = good
+    entry.G = entry.X = entry.W = entry.dX = entry.dW = entry.workspace = 0x1000
+    entry.rho, entry.nu = 0.5, 0.5
+    entry.rng = rng
+    entry.token_sampling = 1
+    entry.plan = plan
+    arr = (vb.LayerArgs * 2)(entry, entry)
+    assert stack_fn(arr, C.c_int32(0), C.c_int32(1), null, null, null) == 1
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(0), null, null, null) == 1
+    arr[1].workspace = 0
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 4      # nothing of layer 0 is launched either
+    arr[1].workspace = 0x1000
+    arr[1].nu = 1.5
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
     # the Jacobian and the stack variants: J is required where the name says so, needs a dX where it is
     # optional, and is held to the same alignment as the other tensors
     assert lib.vcas_sampled_dgrad_jac(C.byref(good), fake, fake, fake, fake, fake, null, fake, null) == 2
