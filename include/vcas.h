@@ -233,6 +233,8 @@ typedef struct {
  *   sampler_stream  for each group of `group` consecutive layers, after the
  *                   group's last SampleA: row norms of X where still due, SampleW;
  *   gemm_stream     after the group's SampleW: dW (and its split-K reduction).
+ * Towards the end of the stack the groups shrink (each takes half of the layers
+ * that are left), so that the side streams finish shortly after `stream`.
  * sampler_stream and gemm_stream may be the same stream, or null (= `stream`).
  * layers: HOST array, read during the call only.  group >= 1.  The call joins
  * nothing: results of the weight halves are complete when the streams they ran

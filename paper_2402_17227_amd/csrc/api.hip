@@ -440,16 +440,26 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
             (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
             return VCAS_EINVAL;
     }
+    // Groups of `group` layers; the last ones shrink (half of what is left), so that the side
+    // streams are not a whole group behind when the main stream reaches the end of the stack.
+    std::vector<int> first;
+    for (int l = 0; l < L;) {
+        first.push_back(l);
+        const int left = L - l;
+        const int n = left > 2 * group ? group : (left + 1) / 2;
+        l += n < 1 ? 1 : n;
+    }
+    first.push_back(L);
+    const int groups = (int)first.size() - 1;
     // two events per group, created on first use and kept
     static std::vector<hipEvent_t> events;
-    const int groups = (L + group - 1) / group;
     while ((int)events.size() < 2 * groups) {
         hipEvent_t ev;
         if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return VCAS_EHIP;
         events.push_back(ev);
     }
     for (int g = 0; g < groups; ++g) {
-        const int l0 = g * group, l1 = l0 + group < L ? l0 + group : L;
+        const int l0 = first[g], l1 = first[g + 1];
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
