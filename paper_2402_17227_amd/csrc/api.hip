@@ -207,15 +207,25 @@ struct ChainArgs {
     bool fill = true;                     // write zero rows of dX for the samples that are not kept
 };
 
+// Where the norms of X are taken: with those of G, before SampleA (one launch fewer, every row
+// read), or by the weight half, after SampleA (kept samples only; the norms of X then stay off the
+// stream that carries the dX chain).  Both give the same bits.
+enum XNorms { kXNormsByShape, kXNormsWithG, kXNormsAfterSampleA };
+
+static bool together_for(const vcas_shape &s, XNorms x)
+{
+    return x == kXNormsByShape ? norms_together(s) : x == kXNormsWithG;
+}
+
 static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                              const vcas_rng &rng, int token_sampling, const vcas_plan &pl, void *dX,
-                             const ChainArgs &chain, void *workspace, hipStream_t st)
+                             const ChainArgs &chain, void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
     // together: the square roots SampleW needs travel in the plan's score and q arrays until
     // SampleW overwrites them with their final contents
-    if (norms_together(s))
+    if (together_for(s, xnorms))
         VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, pl.score, pl.q, s.T,
                                 chain.kept_above, st));
     else
@@ -232,11 +242,11 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
 // (large layers), SampleW, dW.
 static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X, double rho, double nu,
                                const vcas_rng &rng, int token_sampling, const vcas_plan &pl, float *dW,
-                               void *workspace, hipStream_t st)
+                               void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *u = uniforms_of(s, workspace);
-    const bool together = norms_together(s);
+    const bool together = together_for(s, xnorms);
     if (!together)
         VCAS_TRY(row_sumsq_scores_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, pl.gsq, pl.p, pl.score, rng, 1u,
                                            token_sampling ? u : nullptr, st));
@@ -458,12 +468,14 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return VCAS_EHIP;
         events.push_back(ev);
     }
+    // with a stream of its own for the weight halves, the norms of X go there too
+    const XNorms xnorms = s2 != st ? kXNormsAfterSampleA : kXNormsByShape;
     for (int g = 0; g < groups; ++g) {
         const int l0 = first[g], l1 = first[g + 1];
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
-                               a.workspace, st));
+                               a.workspace, st, xnorms));
         }
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
                          hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))
@@ -471,7 +483,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr, a.workspace,
-                                 s2));
+                                 s2, xnorms));
         }
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
