@@ -109,6 +109,8 @@ def main():
                     help="the default launch: one vcas_backward_stack call per step (from the host, no graph), "
                          "cross-stream dependencies once per GROUP layers, SampleW and dW on two side streams; "
                          "0 = per-layer calls (see --graph-free options below)")
+    ap.add_argument("--rho", type=float, default=None, help="override every layer's data keep ratio (sweeps)")
+    ap.add_argument("--nu", type=float, default=None, help="override every layer's token keep ratio (sweeps)")
     ap.add_argument("--graph", action="store_true",
                     help="per-layer vcas_linear_backward calls captured in one HIP graph per step instead")
     ap.add_argument("--share-inputs", action="store_true",
@@ -129,6 +131,10 @@ def main():
     vb.lib()                                    # fails loudly if libvcas.so was not built
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     specs = workloads.config(args.workload)
+    if args.rho is not None or args.nu is not None:
+        import dataclasses
+        specs = [dataclasses.replace(sp, rho=args.rho if args.rho is not None else sp.rho,
+                                     nu=args.nu if args.nu is not None else sp.nu) for sp in specs]
     cache = {} if args.share_inputs else None
     layers = []
     for k, s in enumerate(specs):
