@@ -1,6 +1,6 @@
 // C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
 // launches on the caller's stream.  See include/vcas.h for the contract.
-#include "common.hpp"
+#include "sample_a_small.hpp"
 
 namespace vcas {
 
@@ -46,7 +46,7 @@ int wgrad_tiles_bf16(int K_out, int K_in, int tile);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
-                       hipStream_t st);
+                       const InlineSampleA *sample_a, hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
                        hipStream_t st);
@@ -143,7 +143,7 @@ static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void
                                   const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
                                   int64_t expected_rows, hipStream_t st)
 {
-    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, fill, expected_rows, st)
+    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, fill, expected_rows, nullptr, st)
                                 : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, fill, st);
 }
 
@@ -219,7 +219,8 @@ static bool together_for(const vcas_shape &s, XNorms x)
 
 static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                              const vcas_rng &rng, int token_sampling, const vcas_plan &pl, void *dX,
-                             const ChainArgs &chain, void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape)
+                             const ChainArgs &chain, void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape,
+                             bool sample_a_in_dgrad = false)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
@@ -230,11 +231,29 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
                                 chain.kept_above, st));
     else
         VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, chain.kept_above, pl.gsq, st));
-    VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
     // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
-    if (dX)
-        VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill,
-                                (int64_t)((double)R * rho + 0.5), st));
+    const int64_t rows_expected = (int64_t)((double)R * rho + 0.5);
+    if (sample_a_in_dgrad && dX && s.dtype == VCAS_BF16 && s.N <= 64 && R <= 4096) {
+        // one launch and its gap less on the chain row norms -> SampleA -> dX: the dgrad workgroups
+        // decide SampleA themselves.  Worth it only while the vector of row norms is short: every
+        // workgroup reads all of it (BERT-base, R = 4096: step 2.78 -> 2.70 ms; ViT, N = 64,
+        // R = 12608: 3.93 -> 4.44 ms)
+        InlineSampleA sa;
+        sa.gsq = pl.gsq;
+        sa.budget = (double)s.N * rho;
+        sa.seed = rng.seed;
+        sa.layer = rng.layer;
+        sa.draw = rng.draw;
+        sa.draw_offset = rng.draw_offset;
+        sa.gnorm = pl.gnorm;
+        sa.p = pl.p;
+        sa.maskA = pl.maskA;
+        sa.idxA = pl.idxA;
+        sa.cntA = pl.cntA;
+        return dgrad_bf16(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, &sa, st);
+    }
+    VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
+    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, st));
     return VCAS_OK;
 }
 
@@ -475,7 +494,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
-                               a.workspace, st, xnorms));
+                               a.workspace, st, xnorms, true));
         }
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
                          hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))

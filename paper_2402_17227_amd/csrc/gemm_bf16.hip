@@ -24,7 +24,7 @@
 // per-row 1/p goes into the epilogue.
 #include <type_traits>
 
-#include "common.hpp"
+#include "sample_a_small.hpp"
 
 namespace vcas {
 
@@ -355,7 +355,8 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   const int32_t *__restrict__ cntA,
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
                                                                   int K_out, int tiles_n,
-                                                                  const uint16_t *__restrict__ J, int fill_dropped)
+                                                                  const uint16_t *__restrict__ J, int fill_dropped,
+                                                                  InlineSampleA sa)
 {
     constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -372,9 +373,42 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
     // holds the kept-sample list, fetched together with the count instead of after it.
     int32_t *idx_staged = reinterpret_cast<int32_t *>(smem + (NS - 1) * STAGE);
     const int staged = min(N, kIdxStaged);
-    for (int j = threadIdx.x; j < staged; j += NT) idx_staged[j] = idxA[j];
-
-    const int cnt = min(max(*cntA, 0), N);
+    __shared__ float sa_norm[64], sa_p[64];
+    __shared__ int sa_count;
+    int cnt;
+    if (sa.gsq != nullptr) {
+        // SampleA decided here, by every workgroup for itself (N <= 64: a few microseconds of one
+        // wavefront's work on 4 N T bytes that sit in L2), instead of by a launch of its own in
+        // front of this one; the first workgroup writes the plan's fields for everybody else.
+        const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
+        if (T <= 128) sample_norms_batched<8, 2>(sa.gsq, wave_, NW, N, T, sa_norm);
+        else sample_norms_batched<4, 8>(sa.gsq, wave_, NW, N, T, sa_norm);
+        __syncthreads();
+        if (wave_ == 0) {
+            const uint32_t draw = sa.draw + (sa.draw_offset ? *sa.draw_offset : 0u);
+            const float a = lane_ < N ? sa_norm[lane_] : 0.0f;
+            const SampleADecision d = sample_a_wave(a, N, sa.budget, sa.seed, sa.layer, draw);
+            if (lane_ < N) sa_p[lane_] = d.pr;
+            if (d.keep) idx_staged[d.below] = lane_;
+            if (lane_ == 0) sa_count = d.count;
+            if (blockIdx.x == 0) {
+                if (lane_ < N) {
+                    sa.gnorm[lane_] = a;
+                    sa.p[lane_] = d.pr;
+                    sa.maskA[lane_] = d.keep ? 1 : 0;
+                }
+                if (d.keep) sa.idxA[d.below] = lane_;
+                if (lane_ == 0) *sa.cntA = d.count;
+            }
+        }
+        __syncthreads();
+        cnt = sa_count;
+        idxA = idx_staged;   // the kept list lives in LDS from here on (N <= 64 entries)
+        p = sa_p;
+    } else {
+        for (int j = threadIdx.x; j < staged; j += NT) idx_staged[j] = idxA[j];
+        cnt = min(max(*cntA, 0), N);
+    }
     const int64_t M = (int64_t)cnt * T;
     const int64_t R = (int64_t)N * T;
     const int compute = (int)((M + BM - 1) / BM) * tiles_n;
@@ -1018,7 +1052,7 @@ static bool allow_lds(Kern kern, size_t bytes)
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
                                 const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
-                                hipStream_t st)
+                                const InlineSampleA &sa, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
@@ -1034,7 +1068,7 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                 s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0);
+                 s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0, sa);
     return launch_status();
 }
 
@@ -1042,10 +1076,18 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
 // steers the tile choice, any count is computed correctly by every variant.
 // J: elementwise Jacobian [R, K_in] multiplied into dX, or null.  fill: write the zero rows of
 // dropped samples (false: leave them as they are).
+// sample_a (null: SampleA has been decided, p / idxA / cntA hold its outcome): the kernel decides
+// it itself from the row norms and writes the plan's SampleA fields; N <= 64 only.
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
-                       hipStream_t st)
+                       const InlineSampleA *sample_a, hipStream_t st)
 {
+    InlineSampleA sa = {};
+    sa.gsq = nullptr;
+    if (sample_a) {
+        if (s.N > 64) return VCAS_EINVAL;
+        sa = *sample_a;
+    }
     // The loads into LDS run at about 40 bytes per clock and CU, so the largest tile that still
     // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 192 tiles up; else 128x128
     // (two per CU) while more than 256 of them exist; else 64x128, twice as many workgroups with
@@ -1057,11 +1099,11 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, st);
-    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, st);
+    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
-    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, st);
-    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, st);
+    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
 }
 
 template <int BM, int BN, int WM, int WN, int OCC>

@@ -4,6 +4,7 @@
 // steps (leverage scores, per-row scale).  All vectors are at most R floats,
 // so these kernels are latency-bound, not bandwidth-bound.
 #include "rowsum.hpp"
+#include "sample_a_small.hpp"
 
 namespace vcas {
 
@@ -358,69 +359,22 @@ __device__ __forceinline__ void sampler_a_fast_body(const float *__restrict__ gs
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (draw_offset) draw += *draw_offset;
     for (int i = wave; i < N; i += 16) {
-        const float *row = gsq + (int64_t)i * T;
-        float acc = 0.0f;
-        // eight loads in flight, then added in ascending t as before (a lane's values past the
-        // end re-read the last one and count as +0, which leaves the sum as it is)
-        for (int t0 = lane; t0 < T; t0 += 512) {
-            float v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = row[min(t0 + 64 * k, T - 1)];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc = acc + (t0 + 64 * k < T ? v[k] : 0.0f);
-        }
-        acc = wave_exchange_sum(acc);
-        if (lane == 0) gn[i] = __builtin_sqrtf(acc);
+        const float norm = sample_norm_wave(gsq + (int64_t)i * T, T);
+        if (lane == 0) gn[i] = norm;
     }
     __syncthreads();
     if (N <= 64) {
-        // Every entry lies in the first 64 summation slots: the other fifteen group sums are +0
-        // and x + 0 = x, so the first wavefront does the rounds alone, with no LDS and no barriers.
+        // one wavefront decides (see sample_a_small.hpp)
         if (wave != 0) return;
         const float a = lane < N ? gn[lane] : 0.0f;
-        const bool pos = a > 0.0f;
-        double S = wave_exchange_sum(pos ? (double)a : 0.0);
-        const int nonzero = ballot_count(pos);
-        float pr = 0.0f;
-        if (budget >= (double)nonzero) {
-            pr = pos ? 1.0f : 0.0f;
-        } else {
-            bool fixed = false;
-            int ncap = 0;
-            double c = 0.0;
-            for (;;) {
-                const double rem = budget - (double)ncap;
-                if (!(S > 0.0) || !(rem > 0.0)) {
-                    c = 0.0;
-                    break;
-                }
-                c = rem / S;
-                const bool open = pos && !fixed;
-                const bool cap = open && c * (double)a >= 1.0;
-                fixed = fixed || cap;
-                const int newly = ballot_count(cap);
-                const double S_next = wave_exchange_sum(open && !cap ? (double)a : 0.0);
-                if (newly == 0) break;
-                ncap += newly;
-                S = S_next;
-            }
-            if (fixed) pr = 1.0f;
-            else if (pos) {
-                pr = (float)(c * (double)a);
-                pr = pr < 1.0f ? pr : 1.0f;
-            }
-        }
-        bool m = false;
+        const SampleADecision d = sample_a_wave(a, N, budget, seed, layer, draw);
         if (lane < N) {
-            m = philox_uniform(seed, layer, 0u, draw, (uint32_t)lane) < pr;
             gnorm[lane] = a;
-            p[lane] = pr;
-            maskA[lane] = m ? 1 : 0;
+            p[lane] = d.pr;
+            maskA[lane] = d.keep ? 1 : 0;
         }
-        const uint64_t kept = __ballot(m);
-        const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
-        if (m) idxA[below] = lane;
-        if (lane == 0) *cntA = __builtin_popcountll(kept);
+        if (d.keep) idxA[d.below] = lane;
+        if (lane == 0) *cntA = d.count;
         return;
     }
     float a[1], pr[1];
