@@ -381,11 +381,11 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
         // wavefront's work on 4 N T bytes that sit in L2), instead of by a launch of its own in
         // front of this one; the first workgroup writes the plan's fields for everybody else.
         const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
+        const uint32_t draw = sa.draw + (sa.draw_offset ? *sa.draw_offset : 0u);   // fetched beside the norms
         if (T <= 128) sample_norms_batched<8, 2>(sa.gsq, wave_, NW, N, T, sa_norm);
         else sample_norms_batched<4, 8>(sa.gsq, wave_, NW, N, T, sa_norm);
         __syncthreads();
         if (wave_ == 0) {
-            const uint32_t draw = sa.draw + (sa.draw_offset ? *sa.draw_offset : 0u);
             const float a = lane_ < N ? sa_norm[lane_] : 0.0f;
             const SampleADecision d = sample_a_wave(a, N, sa.budget, sa.seed, sa.layer, draw);
             if (lane_ < N) sa_p[lane_] = d.pr;
