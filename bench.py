@@ -95,6 +95,134 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def per_shape_report(args, specs, vb, to_device, workloads):
+    """One layer per distinct linear shape of the workload, at its largest and its smallest data
+    keep ratio: time of the whole sampled path for that layer, of the dense yardsticks, of the two
+    GEMM kernels (the library's kernel timer) and of the row-norm kernel over G.  Every figure is
+    the median of 50 event-bracketed replays (after 10 warm-ups) of a HIP graph that runs the
+    measured call once per copy of the layer, divided by the copies; 'cold' = the copies together
+    exceed the 256 MB last-level cache, 'warm' = the same copy every time."""
+    import torch
+    bf16 = specs[0].dtype == workloads.BF16
+    e = 2 if bf16 else 4
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    picked = {}
+    for sp in specs:
+        key = (sp.K_in, sp.K_out)
+        lo, hi = picked.get(key, (sp, sp))
+        picked[key] = (sp if sp.rho < lo.rho else lo, sp if sp.rho > hi.rho else hi)
+    rows = []
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def median_us(body, batch, reps=50, warm=10):
+        """Median time per unit of `body` (which enqueues `batch` units), replayed from a HIP graph so
+        that the host's launch cost stays out of it."""
+        body()                                   # eager once: one-time kernel attribute set-up
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            body()
+        for _ in range(warm):
+            graph.replay()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e3 / batch)
+        return sorted(out)[len(out) // 2]
+
+    for key, pair in picked.items():
+        for sp in dict.fromkeys(pair):           # one row if the workload has a single keep ratio
+            nbytes = (sp.R * (sp.K_in + sp.K_out) + sp.K_in * sp.K_out) * e
+            copies = max(2, min(16, -(-(640 << 20) // nbytes)))
+            first = Layer(sp, vb, to_device, workloads.make_layer)
+            ring = [first]
+            for _ in range(copies - 1):
+                c = Layer.__new__(Layer)
+                c.__dict__.update(first.__dict__)
+                c.G, c.X, c.W = first.G.clone(), first.X.clone(), first.W.clone()
+                c.dX, c.dW = torch.empty_like(first.dX), torch.empty_like(first.dW)
+                c.plan, c.ws = vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(first.shape)
+                ring.append(c)
+            for l in ring:
+                l.ones_p = torch.ones(sp.N, device="cuda")
+                l.iota_N = torch.arange(sp.N, dtype=torch.int32, device="cuda")
+                l.full_N = torch.full((1,), sp.N, dtype=torch.int32, device="cuda")
+                l.ones_R = torch.ones(sp.R, device="cuda")
+                l.iota_R = torch.arange(sp.R, dtype=torch.int32, device="cuda")
+                l.full_R = torch.full((1,), sp.R, dtype=torch.int32, device="cuda")
+                l.gsq = torch.empty(sp.R, device="cuda")
+                l.gnorm = torch.empty(sp.N, device="cuda")
+                l.dW_t = torch.empty((sp.K_out, sp.K_in), dtype=first.G.dtype, device="cuda")
+            def sampled(l):
+                cur = torch.cuda.current_stream()
+                side.wait_stream(cur)
+                vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 0), True,
+                                        l.plan, l.dX, l.dW, l.ws, side)
+                cur.wait_stream(side)
+
+            def dense_own(l):
+                vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.ones_p, l.iota_N, l.full_N, l.dX)
+                vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.ones_R, l.iota_R, l.full_R, l.dW, l.ws)
+
+            def dense_torch(l):
+                torch.matmul(l.G, l.W, out=l.dX)
+                torch.matmul(l.G.t(), l.X, out=l.dW_t)
+
+            def norms(l):
+                vb.vcas_row_norms(l.shape, l.G, None, None, l.gsq, None, l.gnorm)
+
+            def over(fn, layers_):
+                return lambda: [fn(l) for l in layers_]
+
+            n = len(ring)
+            t_cold = median_us(over(sampled, ring), n)
+            t_warm = median_us(over(sampled, [ring[0]] * n), n)
+            vb.vcas_profile_begin()
+            for _ in range(5):
+                over(sampled, ring)()
+            (dg_ms, dg_n), (wg_ms, wg_n) = vb.vcas_profile_end()
+            t_own = median_us(over(dense_own, ring), n)
+            t_torch = median_us(over(dense_torch, ring), n)
+            t_k1 = median_us(over(norms, ring), n)
+            cntA, cntW = int(ring[0].plan.cntA.item()), int(ring[0].plan.cntW.item())
+            dense = 4.0 * sp.R * sp.K_in * sp.K_out
+            dg_us, wg_us = dg_ms * 1e3 / max(dg_n, 1), wg_ms * 1e3 / max(wg_n, 1)
+            dg_tf = 2.0 * cntA * sp.T * sp.K_in * sp.K_out / dg_us / 1e6
+            wg_tf = 2.0 * cntW * sp.K_in * sp.K_out / wg_us / 1e6
+            k1_gbs = sp.R * sp.K_out * e / t_k1 / 1e3
+            rows.append(f"| {sp.K_in}→{sp.K_out} | {sp.rho:.2f} / {sp.nu:.2f} | {cntA}/{sp.N}, {cntW}/{sp.R} | "
+                        f"{(cntA * sp.T + cntW) / (2.0 * sp.R):.3f} | {t_cold:.0f} / {t_warm:.0f} | {t_own:.0f} | {t_torch:.0f} | "
+                        f"{t_torch / t_cold:.2f} | {dense / t_cold / 1e6:.0f} | {dg_us:.0f} µs, {dg_tf:.0f} ({100 * dg_tf / peak:.0f} %) | "
+                        f"{wg_us:.0f} µs, {wg_tf:.0f} ({100 * wg_tf / peak:.0f} %) | {t_k1:.1f} µs, {k1_gbs:.0f} ({100 * k1_gbs / 8000:.0f} %) |")
+            print(f"bench.py: {sp.name} done", file=sys.stderr, flush=True)
+            del ring, first
+            torch.cuda.empty_cache()
+    head = [f"# Per-shape timings: workload {args.workload} ({'bf16' if bf16 else 'f32'}, N={specs[0].N}, T={specs[0].T})", "",
+            f"Command: `python3 bench.py --workload {args.workload} --per-shape FILE`", "",
+            "One layer per distinct linear shape, at the workload's smallest and largest data keep ratio. "
+            "Each figure: median of 50 event-bracketed replays (after 10 warm-ups) of a HIP graph that holds the measured "
+            "call once per copy of the layer (2 to 16 copies, together above 640 MB, so no copy is still in a cache when its "
+            "turn comes: cold), divided by the number of copies; launch gaps between the calls are included, host time is not. "
+            "sampled = vcas_linear_backward (norms, both samplers, dX, dW; weight half on a side stream, joined after "
+            "every layer), warm = the same graph over one copy; dense = dX and dW at keep "
+            "ratio one without the sampling passes (this library, torch.matmul), cold; effective TFLOP/s = 4·R·K_in·K_out / "
+            "cold sampled time; GEMM columns = kernel-timer average per launch inside eagerly launched cold sampled calls, "
+            "algorithmic flops 2·cntA·T·K_in·K_out resp. 2·cntW·K_in·K_out, percentage of the 2.5 PFLOP/s bf16 "
+            "(157.3 TFLOP/s fp32) datasheet peak; G norms = vcas_row_norms over G only, R·K_out·e bytes, percentage of 8 TB/s.", "",
+            "| shape | ρ / ν | kept samples, tokens | kept flop fraction | sampled µs cold / warm | dense own µs | dense torch µs | "
+            "speedup vs torch | effective TFLOP/s | dgrad | wgrad | G norms GB/s |",
+            "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    with open(args.per_shape, "w") as f:
+        f.write("\n".join(head + rows) + "\n")
+    print("\n".join(rows), file=sys.stderr)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -116,6 +244,10 @@ def main():
     ap.add_argument("--share-inputs", action="store_true",
                     help="layers of equal shape get copies of the same generated values (each layer still owns its "
                          "tensors in HBM); saves minutes of host-side generation on the 144-layer workloads")
+    ap.add_argument("--per-shape", metavar="FILE", default=None,
+                    help="instead of the stack step: one layer per distinct linear shape (at the workload's largest and "
+                         "smallest data keep ratio), median of 50 event-timed calls after 10 warm-ups, inputs rotated "
+                         "over enough copies to defeat the caches; writes a markdown table to FILE and prints no result line")
     ap.add_argument("--counters-pass", action="store_true",
                     help="for a rocprofv3 --pmc run: the sampled steps only, launched eagerly, then one plain 256 MiB "
                          "device copy whose known size calibrates FETCH_SIZE / WRITE_SIZE; prints no result line")
@@ -135,6 +267,9 @@ def main():
         import dataclasses
         specs = [dataclasses.replace(sp, rho=args.rho if args.rho is not None else sp.rho,
                                      nu=args.nu if args.nu is not None else sp.nu) for sp in specs]
+    if args.per_shape:
+        per_shape_report(args, specs, vb, to_device, workloads)
+        return
     cache = {} if args.share_inputs else None
     layers = []
     for k, s in enumerate(specs):
