@@ -241,6 +241,10 @@ def main():
     ap.add_argument("--nu", type=float, default=None, help="override every layer's token keep ratio (sweeps)")
     ap.add_argument("--graph", action="store_true",
                     help="per-layer vcas_linear_backward calls captured in one HIP graph per step instead")
+    ap.add_argument("--xsq-cached", action="store_true",
+                    help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
+                         "pass would, vcas_row_norms over every row) and handed to the weight halves; not the default, "
+                         "which sweeps X inside the step")
     ap.add_argument("--share-inputs", action="store_true",
                     help="layers of equal shape get copies of the same generated values (each layer still owns its "
                          "tensors in HBM); saves minutes of host-side generation on the 144-layer workloads")
@@ -294,10 +298,17 @@ def main():
     stack = None
     if args.graph or args.eager or args.one_stream or args.counters_pass:
         args.stack = 0
+        if args.xsq_cached:
+            sys.exit("bench.py: --xsq-cached goes with the stack launch only")
     if args.stack > 0:
+        for l in layers:
+            l.xsq_forward = None
+            if args.xsq_cached:
+                l.xsq_forward = torch.empty(l.spec.R, dtype=torch.float32, device="cuda")
+                vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
         stack = vb.make_stack([vb.layer_args(l.shape, l.G, l.X, l.W, l.spec.rho, l.spec.nu,
                                              vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
-                                             l.plan, l.dX, l.dW, l.ws) for l in layers])
+                                             l.plan, l.dX, l.dW, l.ws, l.xsq_forward) for l in layers])
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 
     def step():
@@ -419,6 +430,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
+                   + (", row norms of X cached before the timed region" if args.xsq_cached else "")
                    if stack is not None else
                    ("eager" if args.eager else "hip_graph") +
                    (", one stream" if args.one_stream else f", dW halves on {args.side_streams} side streams")),

@@ -220,6 +220,7 @@ typedef struct {
     void *dX;        /* may be null */
     float *dW;       /* may be null */
     void *workspace; /* of this layer's shape; layers must not share one */
+    const float *xsq_forward; /* null, or the cached row norms of X: see vcas_backward_weight_cached */
 } vcas_layer_args;
 
 /*
@@ -290,6 +291,23 @@ vcas_status vcas_backward_data_chained(const vcas_shape *shape, const void *G, c
 vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const void *X, double rho,
                                  double nu, const vcas_rng *rng, int32_t token_sampling,
                                  const vcas_plan *plan, float *dW, void *workspace, void *stream);
+
+/*
+ * vcas_backward_weight for a caller that already has the squared row norms of X
+ * (the ||x_t||^2 of Eq. 3): X is an input of the forward pass, so its norms can
+ * be taken there, once, by vcas_row_norms (xsq of EVERY row, no sample_mask) and
+ * kept with the activations.  xsq_forward [R] is read instead of sweeping the
+ * kept rows of X again; everything else, and every bit of the results, is as in
+ * vcas_backward_weight (plan->xsq receives the norms with zeros on dropped
+ * samples, as there).  xsq_forward must not be plan->xsq.  Whatever the data
+ * call may have prepared for the weight call (on small layers it takes the norms
+ * of X beside those of G) is ignored; vcas_backward_stack skips that work for
+ * layers whose xsq_forward is set.
+ */
+vcas_status vcas_backward_weight_cached(const vcas_shape *shape, const void *G, const void *X,
+                                        const float *xsq_forward, double rho, double nu,
+                                        const vcas_rng *rng, int32_t token_sampling,
+                                        const vcas_plan *plan, float *dW, void *workspace, void *stream);
 
 /*
  * Variance probe for the adaptive keep ratios (Sec. 4.1 variance, Eq. 3, and

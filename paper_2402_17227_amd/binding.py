@@ -19,7 +19,8 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
-    "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
+    "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_backward_weight_cached",
+    "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
 ]
 
@@ -46,7 +47,7 @@ class LayerArgs(C.Structure):
     """vcas_layer_args"""
     _fields_ = [("shape", Shape), ("G", C.c_void_p), ("X", C.c_void_p), ("W", C.c_void_p), ("rho", C.c_double),
                 ("nu", C.c_double), ("rng", Rng), ("token_sampling", C.c_int32), ("plan", PlanPtrs),
-                ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p)]
+                ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p), ("xsq_forward", C.c_void_p)]
 
 
 _lib = None
@@ -197,7 +198,7 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
 
 
 def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dX, dW,
-               workspace) -> LayerArgs:
+               workspace, xsq_forward=None) -> LayerArgs:
     """One entry of the array vcas_backward_stack takes (the tensors must stay alive while it is used)."""
     a = LayerArgs()
     a.shape = shape
@@ -207,6 +208,7 @@ def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sam
     a.token_sampling = 1 if token_sampling else 0
     a.plan = plan.ptrs()
     a.dX, a.dW, a.workspace = _ptr(dX), _ptr(dW), _ptr(workspace)
+    a.xsq_forward = _ptr(xsq_forward)
     return a
 
 
@@ -246,6 +248,15 @@ def vcas_backward_weight(shape: Shape, G, X, rho: float, nu: float, rng: Rng, to
     _check(lib().vcas_backward_weight(C.byref(shape), _ptr(G), _ptr(X), C.c_double(rho), C.c_double(nu),
                                       C.byref(rng), C.c_int32(1 if token_sampling else 0), C.byref(ptrs), _ptr(dW),
                                       _ptr(workspace), _stream()), "vcas_backward_weight")
+
+
+def vcas_backward_weight_cached(shape: Shape, G, X, xsq_forward, rho: float, nu: float, rng: Rng, token_sampling: bool,
+                                plan: Plan, dW, workspace):
+    ptrs = plan.ptrs()
+    _check(lib().vcas_backward_weight_cached(C.byref(shape), _ptr(G), _ptr(X), _ptr(xsq_forward), C.c_double(rho),
+                                             C.c_double(nu), C.byref(rng), C.c_int32(1 if token_sampling else 0),
+                                             C.byref(ptrs), _ptr(dW), _ptr(workspace), _stream()),
+           "vcas_backward_weight_cached")
 
 
 def vcas_variance_probe(shape: Shape, G, X, rho: float, nu: float, base: Rng, M: int, plan: Plan, out, workspace):

@@ -17,6 +17,9 @@ vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream
 vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K, int T, const uint8_t *keep,
                                       float *xsq, const float *gsq, const float *p, float *score, const vcas_rng &rng,
                                       uint32_t stream_id, float *uniforms, hipStream_t st);
+vcas_status cached_xsq_scores_uniforms(const float *xsq_forward, int64_t R, int T, const uint8_t *keep, float *xsq,
+                                       const float *gsq, const float *p, float *score, const vcas_rng &rng,
+                                       uint32_t stream_id, float *uniforms, hipStream_t st);
 // sampling.hip
 vcas_status keep_probs(const float *score, int n, double budget, float *prob, hipStream_t st);
 vcas_status sample_compact(const float *prob, int n, const vcas_rng &rng, uint32_t stream_id, uint8_t *mask,
@@ -261,12 +264,17 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
 // (large layers), SampleW, dW.
 static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X, double rho, double nu,
                                const vcas_rng &rng, int token_sampling, const vcas_plan &pl, float *dW,
-                               void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape)
+                               void *workspace, hipStream_t st, XNorms xnorms = kXNormsByShape,
+                               const float *xsq_forward = nullptr)
 {
     const int64_t R = (int64_t)s.N * s.T;
     float *u = uniforms_of(s, workspace);
-    const bool together = together_for(s, xnorms);
-    if (!together)
+    // cached norms of X: whatever the data half may have left in score and q is not used
+    const bool together = !xsq_forward && together_for(s, xnorms);
+    if (xsq_forward)
+        VCAS_TRY(cached_xsq_scores_uniforms(xsq_forward, R, s.T, pl.maskA, pl.xsq, pl.gsq, pl.p, pl.score, rng, 1u,
+                                            token_sampling ? u : nullptr, st));
+    else if (!together)
         VCAS_TRY(row_sumsq_scores_uniforms(X, s.dtype, R, s.K_in, s.T, pl.maskA, pl.xsq, pl.gsq, pl.p, pl.score, rng, 1u,
                                            token_sampling ? u : nullptr, st));
     // what the norm passes have left in score and q: roots (together) or the scores themselves
@@ -464,7 +472,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (!a.G || !a.X || !plan_complete(&a.plan)) return VCAS_ENULL;
         if (a.dX && !a.W) return VCAS_ENULL;
         if (!a.workspace) return VCAS_EWORKSPACE;
-        if (!ratio_ok(a.rho) || !ratio_ok(a.nu)) return VCAS_EINVAL;
+        if (!ratio_ok(a.rho) || !ratio_ok(a.nu) || (a.xsq_forward && a.xsq_forward == a.plan.xsq)) return VCAS_EINVAL;
         if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
             (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
             return VCAS_EINVAL;
@@ -488,13 +496,13 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         events.push_back(ev);
     }
     // with a stream of its own for the weight halves, the norms of X go there too
-    const XNorms xnorms = s2 != st ? kXNormsAfterSampleA : kXNormsByShape;
+    const XNorms xnorms_default = s2 != st ? kXNormsAfterSampleA : kXNormsByShape;
     for (int g = 0; g < groups; ++g) {
         const int l0 = first[g], l1 = first[g + 1];
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
-                               a.workspace, st, xnorms, true));
+                               a.workspace, st, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, true));
         }
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
                          hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))
@@ -502,7 +510,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         for (int l = l0; l < l1; ++l) {
             const vcas_layer_args &a = layers[l];
             VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr, a.workspace,
-                                 s2, xnorms));
+                                 s2, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, a.xsq_forward));
         }
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
@@ -566,6 +574,20 @@ vcas_status vcas_backward_weight(const vcas_shape *shape, const void *G, const v
     if (!ratio_ok(rho) || !ratio_ok(nu)) return VCAS_EINVAL;
     if (!aligned16(G) || !aligned16(X) || (dW && !aligned16(dW)) || !aligned16(workspace)) return VCAS_EINVAL;
     return weight_half(*shape, G, X, rho, nu, *rng, token_sampling, *plan, dW, workspace, as_stream(stream));
+}
+
+vcas_status vcas_backward_weight_cached(const vcas_shape *shape, const void *G, const void *X, const float *xsq_forward,
+                                        double rho, double nu, const vcas_rng *rng, int32_t token_sampling,
+                                        const vcas_plan *plan, float *dW, void *workspace, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
+    if (!G || !X || !xsq_forward || !rng || !plan_complete(plan)) return VCAS_ENULL;
+    if (!workspace) return VCAS_EWORKSPACE;
+    if (!ratio_ok(rho) || !ratio_ok(nu) || xsq_forward == plan->xsq) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(X) || (dW && !aligned16(dW)) || !aligned16(workspace)) return VCAS_EINVAL;
+    return weight_half(*shape, G, X, rho, nu, *rng, token_sampling, *plan, dW, workspace, as_stream(stream),
+                       kXNormsAfterSampleA, xsq_forward);
 }
 
 vcas_status vcas_variance_probe(const vcas_shape *shape, const void *G, const void *X, double rho, double nu,

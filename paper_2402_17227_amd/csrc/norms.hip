@@ -48,6 +48,33 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict_
     }
 }
 
+// The pass over X replaced by a pass over its cached row norms: xsq_forward holds sum_k X[t,k]^2
+// of EVERY row (taken when X was produced, e.g. in the forward pass, by the kernel above).  Writes
+// what row_sumsq_kernel with a ScoreJob writes, bit for bit: xsq (0 on dropped samples), the
+// SampleW score ((1/p_i) * sqrt(gsq_t)) * sqrt(xsq_t) (0 on dropped samples), and the uniforms.
+__global__ __launch_bounds__(256) void cached_xsq_scores_kernel(const float *__restrict__ xsq_forward, int64_t R, int T,
+                                                                const uint8_t *__restrict__ sample_keep,
+                                                                float *__restrict__ xsq, UniformJob job, ScoreJob sj)
+{
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= R) return;
+    if (job.uniforms) {
+        const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
+        job.uniforms[r] = philox_uniform(job.seed, job.layer, job.stream_id, draw, (uint32_t)r);
+    }
+    const int64_t i = r / T;
+    if (sample_keep[i] == 0) {
+        xsq[r] = 0.0f;
+        sj.score[r] = 0.0f;
+        return;
+    }
+    const float inv = 1.0f / sj.p[i];
+    const float s1 = inv * __builtin_sqrtf(sj.gsq[r]);
+    const float acc = xsq_forward[r];
+    xsq[r] = acc;
+    sj.score[r] = s1 * __builtin_sqrtf(acc);
+}
+
 // (keep_a, T: as sample_keep above, for the rows of A only.)
 // Row norms of two matrices with the same number of rows in one launch (G and X
 // of a layer when both are small enough that a second launch would cost more
@@ -140,6 +167,18 @@ vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K
     const ScoreJob sj = {gsq, p, score};
     return dtype == VCAS_BF16 ? launch_row_sumsq<true>(X, R, K, T, keep, xsq, job, sj, st)
                               : launch_row_sumsq<false>(X, R, K, T, keep, xsq, job, sj, st);
+}
+
+// row_sumsq_scores_uniforms without the sweep over X: its row norms come from xsq_forward
+vcas_status cached_xsq_scores_uniforms(const float *xsq_forward, int64_t R, int T, const uint8_t *keep, float *xsq,
+                                       const float *gsq, const float *p, float *score, const vcas_rng &rng,
+                                       uint32_t stream_id, float *uniforms, hipStream_t st)
+{
+    const UniformJob job = {uniforms, rng.seed, rng.layer, stream_id, rng.draw, rng.draw_offset};
+    const ScoreJob sj = {gsq, p, score};
+    hipLaunchKernelGGL(cached_xsq_scores_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, xsq_forward, R, T,
+                       keep, xsq, job, sj);
+    return launch_status();
 }
 
 template <bool BF16>

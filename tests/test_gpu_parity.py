@@ -607,6 +607,71 @@ def test_stack_of_layers_equals_layer_by_layer_calls(vb, group, streams):
     assert rel_l2(from_device(outs[2][1]), want_dX) <= TOL[BF16] and rel_l2(from_device(outs[2][2]), want_dW) <= TOL[BF16]
 
 
+@pytest.mark.parametrize("streams", [1, 3])
+def test_cached_row_norms_of_x_give_the_same_bits(vb, streams):
+    """The squared row norms of X can be taken once, when X is produced (vcas_row_norms over every row), and
+    handed to the weight half instead of a second sweep over X: every plan field, dX and dW must come out bit
+    for bit as without the cache, in the stack launch and in the stand-alone weight call, and as the oracle says."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    specs = [workloads.LayerSpec("cx0", BF16, 8, 128, 768, 264, 0.5, 0.5, layer=0, seed=6, gen_seed=1, token_sigma=0.5),
+             workloads.LayerSpec("cx1", F32, 6, 50, 72, 136, 0.6, 0.4, layer=1, seed=6, gen_seed=2, token_sigma=0.5),
+             workloads.LayerSpec("cx2", BF16, 12, 300, 2048, 64, 0.4, 0.5, layer=2, seed=6, gen_seed=3, token_sigma=0.5),
+             workloads.LayerSpec("cx3", BF16, 16, 64, 256, 768, 1.0, 1.0, layer=3, seed=6, gen_seed=4, token_sigma=0.5)]
+    refs, entries, outs, alone, keep, host = [], [], [], [], [], []
+    for sp in specs:
+        G, X, W = workloads.make_layer(sp)
+        shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+        g, x, w = (to_device(a, sp.dtype) for a in (G, X, W))
+        tdt = torch.bfloat16 if sp.dtype == BF16 else torch.float32
+
+        def fresh():
+            return (vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape),
+                    torch.full((sp.R, sp.K_in), float("nan"), dtype=tdt, device="cuda"),
+                    torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda"))
+        rng = vb.Rng(sp.seed, sp.layer, 2)
+        plan_r, ws_r, dX_r, dW_r = fresh()
+        vb.vcas_linear_backward(shape, g, x, w, sp.rho, sp.nu, rng, True, plan_r, dX_r, dW_r, ws_r)
+        refs.append((plan_to_numpy(plan_r), dX_r, dW_r))
+        # "forward pass": norms of every row of X, nothing masked
+        xsq_fwd = torch.full((sp.R,), float("nan"), device="cuda")
+        vb.vcas_row_norms(shape, None, x, None, None, xsq_fwd, None)
+        xsq_copy = xsq_fwd.clone()
+        plan, ws, dX, dW = fresh()
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, xsq_fwd))
+        outs.append((plan, dX, dW))
+        # stand-alone: data call, then the weight call with the cache
+        plan_a, ws_a, dX_a, dW_a = fresh()
+        vb.vcas_backward_data(shape, g, x, w, sp.rho, rng, True, plan_a, dX_a, ws_a)
+        vb.vcas_backward_weight_cached(shape, g, x, xsq_fwd, sp.rho, sp.nu, rng, True, plan_a, dW_a, ws_a)
+        alone.append((plan_a, dX_a, dW_a))
+        keep.append((g, x, w, ws, ws_a, ws_r, xsq_fwd, xsq_copy))
+        host.append((G, X, W))
+    torch.cuda.synchronize()
+    stack = vb.make_stack(entries)
+    s2 = torch.cuda.Stream() if streams >= 2 else None
+    s3 = torch.cuda.Stream() if streams >= 3 else None
+    for _ in range(2):                                   # the cache must survive a step: twice
+        vb.vcas_backward_stack(stack, 2, s2, s3)
+    torch.cuda.synchronize()
+
+    def bits(t):
+        return t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    for k, sp in enumerate(specs):
+        plan_r, dX_r, dW_r = refs[k]
+        for name, (plan, dX, dW) in (("stack", outs[k]), ("alone", alone[k])):
+            got = plan_to_numpy(plan)
+            for key, val in plan_r.items():
+                assert np.array_equal(np.asarray(got[key]), np.asarray(val)), (sp.name, name, key)
+            assert torch.equal(bits(dX), bits(dX_r)), (sp.name, name)
+            assert torch.equal(bits(dW), bits(dW_r)), (sp.name, name)
+        assert torch.equal(keep[k][6], keep[k][7]), "the cached norms were written to"
+    sp = specs[2]
+    G, X, W = host[2]
+    want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 2)
+    compare_plan(plan_to_numpy(outs[2][0]), want)
+    assert rel_l2(from_device(outs[2][2]), want_dW) <= TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_variance_probe_matches_oracle(vb, dtype):
     spec = workloads.LayerSpec("probe", dtype, 8, 24, 72, 64, 0.5, 0.5, layer=4, seed=5, gen_seed=4, token_sigma=0.5)

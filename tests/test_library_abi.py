@@ -84,6 +84,16 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
     arr[1].workspace = 0x1000
     arr[1].nu = 1.5
     assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
+    arr[1].nu = 0.5
+    arr[1].xsq_forward = 0x1000                                                  # the cache must not be plan.xsq itself
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
+    cached = lib.vcas_backward_weight_cached
+    assert cached(C.byref(good), fake, fake, null, C.c_double(0.5), C.c_double(0.5), C.byref(rng), C.c_int32(1),
+                  C.byref(plan), fake, fake, null) == 2                          # no cache given
+    assert cached(C.byref(good), fake, fake, fake, C.c_double(0.5), C.c_double(0.5), C.byref(rng), C.c_int32(1),
+                  C.byref(plan), fake, fake, null) == 1                          # the cache is plan.xsq
+    assert cached(C.byref(good), fake, fake, C.c_void_p(0x2000), C.c_double(0.5), C.c_double(0.5), C.byref(rng),
+                  C.c_int32(1), C.byref(plan), fake, null, null) == 4            # workspace
     # the Jacobian and the stack variants: J is required where the name says so, needs a dX where it is
     # optional, and is held to the same alignment as the other tensors
     assert lib.vcas_sampled_dgrad_jac(C.byref(good), fake, fake, fake, fake, fake, null, fake, null) == 2
