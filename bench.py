@@ -4,7 +4,9 @@
 One "step" is one pass of the whole hot path (row norms -> keep probabilities
 -> Philox masks -> compaction -> sampled dX and dW) over every linear layer of
 the BERT-base-shaped stack (72 layers, B=32, L=128, bf16), each layer with its
-own synthetic G, X, W resident in HBM.  Prints ONE JSON line.
+own synthetic G, X, W resident in HBM.  The data halves run in the order a backward
+pass imposes: down, up, out-projection one behind the other, then V, K and Q, whose
+upstream gradients do not depend on each other, together.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base]
 """
@@ -76,6 +78,13 @@ def _sample_blocks(specs):
     if dense_tflop <= 2.0:
         return set(blocks)
     return {blocks[0], blocks[len(blocks) // 2], blocks[-1]}
+
+
+def _is_sibling(name):
+    """In backward order a block's layers come as down, up, o, v, k, q.  The gradients of the Q, K and V
+    projections' outputs all come out of the attention backward at once: k and q do not wait for the dX of
+    the entry before them, which is what vcas_layer_args.sibling states."""
+    return name.endswith((".k", ".q"))
 
 
 def measured_traffic(workload, kernel):
@@ -241,6 +250,9 @@ def main():
     ap.add_argument("--nu", type=float, default=None, help="override every layer's token keep ratio (sweeps)")
     ap.add_argument("--graph", action="store_true",
                     help="per-layer vcas_linear_backward calls captured in one HIP graph per step instead")
+    ap.add_argument("--no-siblings", action="store_true",
+                    help="stack launch: do not mark the K and Q projections as siblings of V (every data half then "
+                         "waits for the one before it)")
     ap.add_argument("--xsq-cached", action="store_true",
                     help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
                          "pass would, vcas_row_norms over every row) and handed to the weight halves; not the default, "
@@ -308,7 +320,9 @@ def main():
                 vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
         stack = vb.make_stack([vb.layer_args(l.shape, l.G, l.X, l.W, l.spec.rho, l.spec.nu,
                                              vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
-                                             l.plan, l.dX, l.dW, l.ws, l.xsq_forward) for l in layers])
+                                             l.plan, l.dX, l.dW, l.ws, l.xsq_forward,
+                                             sibling=not args.no_siblings and _is_sibling(l.spec.name))
+                              for l in layers])
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 
     def step():
@@ -379,15 +393,20 @@ def main():
                    + l.spec.R * l.spec.K_in * e for l in layers) / len(layers)
     wg_bytes = sum(int(l.plan.cntW.item()) * (l.spec.K_out + l.spec.K_in) * e + 4 * l.spec.K_in * l.spec.K_out
                    for l in layers) / len(layers)
+    # a launch may cover several layers (siblings): flops and bytes per launch follow the launch count
+    dg_per_step, wg_per_step = max(dg_n, 1) / reps, max(wg_n, 1) / reps
+    dg_bytes *= len(layers) / dg_per_step
+    wg_bytes *= len(layers) / wg_per_step
     if dg_total >= wg_total:
-        name, avg_ms, flops, alg_bytes = f"dgrad_{sfx}_kernel", dg_avg, kept_rows / len(layers), dg_bytes
+        name, avg_ms, flops, alg_bytes = f"dgrad_{sfx}_kernel", dg_avg, kept_rows / dg_per_step, dg_bytes
     else:
-        name, avg_ms, flops, alg_bytes = f"wgrad_{sfx}_kernel", wg_avg, kept_toks / len(layers), wg_bytes
+        name, avg_ms, flops, alg_bytes = f"wgrad_{sfx}_kernel", wg_avg, kept_toks / wg_per_step, wg_bytes
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
     achieved = flops / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                 "frac": achieved / peak, "traffic": measured_traffic(args.workload, name),
                 "algorithmic_bytes": alg_bytes, "avg_launch_us": avg_ms * 1e3,
+                "launches_per_step": dg_per_step if name.startswith("dgrad") else wg_per_step,
                 "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
 
     # ---- dense yardsticks at the same shapes -------------------------------------
@@ -430,6 +449,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
+                   + ("" if args.no_siblings else ", data halves of V, K, Q of a block in shared launches")
                    + (", row norms of X cached before the timed region" if args.xsq_cached else "")
                    if stack is not None else
                    ("eager" if args.eager else "hip_graph") +

@@ -221,6 +221,10 @@ typedef struct {
     float *dW;       /* may be null */
     void *workspace; /* of this layer's shape; layers must not share one */
     const float *xsq_forward; /* null, or the cached row norms of X: see vcas_backward_weight_cached */
+    int32_t sibling; /* nonzero: this layer's G does not depend on the dX of the entry before it (the
+                        Q, K and V projections of one attention block all get their gradients from
+                        the attention backward), so vcas_backward_stack may launch the two data
+                        halves together instead of one behind the other; results are the same bits */
 } vcas_layer_args;
 
 /*
@@ -234,6 +238,8 @@ typedef struct {
  *   sampler_stream  for each group of `group` consecutive layers, after the
  *                   group's last SampleA: row norms of X where still due, SampleW;
  *   gemm_stream     after the group's SampleW: dW (and its split-K reduction).
+ * Consecutive entries marked `sibling` that have one shape may share the launches
+ * of their data halves (up to four layers per launch).
  * Towards the end of the stack the groups shrink (each takes half of the layers
  * that are left), so that the side streams finish shortly after `stream`.
  * sampler_stream and gemm_stream may be the same stream, or null (= `stream`).

@@ -14,6 +14,7 @@ KernelTimer &kernel_timer()
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,
                       hipStream_t st);
 vcas_status sample_norms(const float *gsq, int N, int T, float *gnorm, hipStream_t st);
+vcas_status row_sumsq_group(const RowNormGroup &grp, int n, int dtype, int64_t R, int K, int T, hipStream_t st);
 vcas_status row_sumsq_scores_uniforms(const void *X, int dtype, int64_t R, int K, int T, const uint8_t *keep,
                                       float *xsq, const float *gsq, const float *p, float *score, const vcas_rng &rng,
                                       uint32_t stream_id, float *uniforms, hipStream_t st);
@@ -32,6 +33,7 @@ vcas_status row_scale(const float *p, const float *q, const uint8_t *maskW, int6
 vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q, uint8_t *maskW, hipStream_t st);
 vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
                       uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st);
+vcas_status sampler_a_group(const SampleAGroup &grp, int n, int N, int T, hipStream_t st);
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
 vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
                       const float *u, int N, int T, double budget, int token_sampling, int prepared, float *score,
@@ -50,6 +52,8 @@ int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
                        const InlineSampleA *sample_a, hipStream_t st);
+vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
+                             hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
                        hipStream_t st);
@@ -286,6 +290,64 @@ static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X
     return VCAS_OK;
 }
 
+// Can layer b of a stack share the launches of its data half with layer a in front of it?  Only
+// where the caller says that b's G does not depend on a's dX and the two have one shape (bf16, a
+// dX wanted, at most 1024 samples: the one-workgroup SampleA).
+static bool shares_data_half(const vcas_layer_args &a, const vcas_layer_args &b)
+{
+    const vcas_shape &s = a.shape, &t = b.shape;
+    return b.sibling != 0 && s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out &&
+           s.dtype == VCAS_BF16 && t.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX;
+}
+
+// Data halves of n sibling layers (shares_data_half): the row norms of every G in one launch,
+// every dX in one launch.  SampleA in between: on short vectors each dgrad workgroup decides its
+// own layer's (as in data_half), else one launch with a workgroup per layer.  Bit for bit what
+// n calls of data_half compute.
+static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipStream_t st)
+{
+    const vcas_shape &s = layers[0].shape;
+    const int64_t R = (int64_t)s.N * s.T;
+    const bool in_dgrad = s.N <= 64 && R <= 4096;
+    RowNormGroup norms = {};
+    SampleAGroup samplers = {};
+    DgradProblem probs[kMaxSiblings];
+    double rho_max = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const vcas_layer_args &a = layers[i];
+        norms.A[i] = static_cast<const uint4 *>(a.G);
+        norms.out[i] = a.plan.gsq;
+        norms.keep[i] = nullptr;
+        InlineSampleA sa;
+        sa.gsq = a.plan.gsq;
+        sa.budget = (double)s.N * a.rho;
+        sa.seed = a.rng.seed;
+        sa.layer = a.rng.layer;
+        sa.draw = a.rng.draw;
+        sa.draw_offset = a.rng.draw_offset;
+        sa.gnorm = a.plan.gnorm;
+        sa.p = a.plan.p;
+        sa.maskA = a.plan.maskA;
+        sa.idxA = a.plan.idxA;
+        sa.cntA = a.plan.cntA;
+        samplers.prob[i] = sa;
+        DgradProblem &q = probs[i];
+        q.G = static_cast<const uint16_t *>(a.G);
+        q.W = static_cast<const uint16_t *>(a.W);
+        q.p = a.plan.p;
+        q.idxA = a.plan.idxA;
+        q.cntA = a.plan.cntA;
+        q.dX = static_cast<uint16_t *>(a.dX);
+        q.J = nullptr;
+        q.sa = sa;
+        if (!in_dgrad) q.sa.gsq = nullptr;
+        if (a.rho > rho_max) rho_max = a.rho;
+    }
+    VCAS_TRY(row_sumsq_group(norms, n, s.dtype, R, s.K_out, s.T, st));
+    if (!in_dgrad) VCAS_TRY(sampler_a_group(samplers, n, s.N, s.T, st));
+    return dgrad_bf16_group(s, probs, n, true, (int64_t)((double)R * rho_max + 0.5), st);
+}
+
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                                         double nu, const vcas_rng &rng, int token_sampling, const vcas_plan &pl,
                                         void *dX, float *dW, void *workspace, hipStream_t st, hipStream_t side)
@@ -499,10 +561,18 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
     const XNorms xnorms_default = s2 != st ? kXNormsAfterSampleA : kXNormsByShape;
     for (int g = 0; g < groups; ++g) {
         const int l0 = first[g], l1 = first[g + 1];
-        for (int l = l0; l < l1; ++l) {
+        for (int l = l0; l < l1;) {
             const vcas_layer_args &a = layers[l];
-            VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
-                               a.workspace, st, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, true));
+            // siblings share launches only where the norms of X are not taken beside those of G
+            int n = 1;
+            if (s2 != st)
+                while (l + n < l1 && n < kMaxSiblings && shares_data_half(a, layers[l + n])) ++n;
+            if (n > 1)
+                VCAS_TRY(data_half_siblings(layers + l, n, st));
+            else
+                VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
+                                   a.workspace, st, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, true));
+            l += n;
         }
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
                          hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))

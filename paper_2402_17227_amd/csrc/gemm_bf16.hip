@@ -347,16 +347,13 @@ constexpr int kIdxStaged = 1024;   // kept-sample indices a workgroup stages in 
 // ones write the zero rows of dropped samples, the rest exit.
 // SPQ: the loads of the next step are spread over the MFMAs of the first SPQ
 // quarters of the current one (0: all issued right after the barrier).
-template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
-__global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint16_t *__restrict__ G,
-                                                                  const uint16_t *__restrict__ W,
-                                                                  const float *__restrict__ p,
-                                                                  const int32_t *__restrict__ idxA,
-                                                                  const int32_t *__restrict__ cntA,
-                                                                  uint16_t *__restrict__ dX, int N, int T, int K_in,
-                                                                  int K_out, int tiles_n,
-                                                                  const uint16_t *__restrict__ J, int fill_dropped,
-                                                                  InlineSampleA sa)
+template <int BM, int BN, int WM, int WN, int NS, int SPQ>
+__device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, const uint16_t *__restrict__ W,
+                                                const float *__restrict__ p, const int32_t *__restrict__ idxA,
+                                                const int32_t *__restrict__ cntA, uint16_t *__restrict__ dX, int N,
+                                                int T, int K_in, int K_out, int tiles_n,
+                                                const uint16_t *__restrict__ J, int fill_dropped,
+                                                const InlineSampleA &sa)
 {
     constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -620,6 +617,32 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                 }
             }
         }
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint16_t *__restrict__ G,
+                                                                  const uint16_t *__restrict__ W,
+                                                                  const float *__restrict__ p,
+                                                                  const int32_t *__restrict__ idxA,
+                                                                  const int32_t *__restrict__ cntA,
+                                                                  uint16_t *__restrict__ dX, int N, int T, int K_in,
+                                                                  int K_out, int tiles_n,
+                                                                  const uint16_t *__restrict__ J, int fill_dropped,
+                                                                  InlineSampleA sa)
+{
+    dgrad_bf16_body<BM, BN, WM, WN, NS, SPQ>(G, W, p, idxA, cntA, dX, N, T, K_in, K_out, tiles_n, J, fill_dropped, sa);
+}
+
+// Several layers of one shape whose upstream gradients do not depend on each other (the Q, K and V
+// projections of an attention block) in one launch: blockIdx.y picks the layer, everything else
+// is the kernel above.
+template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_group_kernel(DgradGroup grp, int N, int T, int K_in,
+                                                                        int K_out, int tiles_n, int fill_dropped)
+{
+    const DgradProblem &q = grp.prob[blockIdx.y];
+    dgrad_bf16_body<BM, BN, WM, WN, NS, SPQ>(q.G, q.W, q.p, q.idxA, q.cntA, q.dX, N, T, K_in, K_out, tiles_n, q.J,
+                                             fill_dropped, q.sa);
 }
 
 // ------------------------------------------------------------------ wgrad
@@ -1070,6 +1093,48 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
                  s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0, sa);
     return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
+static vcas_status launch_dgrad_group(const vcas_shape &s, const DgradGroup &grp, int n, bool fill, hipStream_t st)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    const int tiles_n = (s.K_in + BN - 1) / BN;
+    // a multiple of 8 per layer, so that a workgroup's XCD is the same function of blockIdx.x in every layer
+    const int64_t grid = (tiles_n * ((R + BM - 1) / BM + (fill ? 1 : 0)) + 8 + 7) / 8 * 8;
+    if (grid > (int64_t)1 << 30) return VCAS_EINVAL;
+    const size_t lds = NS * (BM + BN) * 128 + BM * 8;
+    auto kern = dgrad_bf16_group_kernel<BM, BN, WM, WN, NS, OCC, SPQ>;
+    static bool allowed = false;
+    if (!allowed) {
+        if (!allow_lds(kern, lds)) return VCAS_EHIP;
+        allowed = true;
+    }
+    launch_timed(0, kern, dim3((unsigned)grid, (unsigned)n), dim3(WM * WN * 64), lds, st, grp, s.N, s.T, s.K_in,
+                 s.K_out, tiles_n, fill ? 1 : 0);
+    return launch_status();
+}
+
+// dgrad of n <= kMaxSiblings layers of shape s in one launch (see dgrad_bf16_group_kernel); the
+// tile choice looks at the tiles of all of them together.
+vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
+                             hipStream_t st)
+{
+    if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
+    DgradGroup grp = {};
+    for (int i = 0; i < n; ++i) {
+        if (probs[i].sa.gsq && s.N > 64) return VCAS_EINVAL;
+        grp.prob[i] = probs[i];
+    }
+    const int64_t R = (int64_t)s.N * s.T;
+    const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
+    const int64_t tiles256 = n * ((rows + 255) / 256) * ((s.K_in + 255) / 256);
+    const int64_t tiles128 = n * ((rows + 127) / 128) * ((s.K_in + 127) / 128);
+    if (tiles256 >= 192) return launch_dgrad_group<256, 256, 2, 4, 2, 1, 2>(s, grp, n, fill, st);
+    if (tiles128 > 256) return launch_dgrad_group<128, 128, 2, 2, 2, 2, 4>(s, grp, n, fill, st);
+    const int64_t tiles64 = n * ((rows + 63) / 64) * ((s.K_in + 127) / 128);
+    if (tiles64 > 256) return launch_dgrad_group<64, 128, 2, 2, 2, 2, 0>(s, grp, n, fill, st);
+    return launch_dgrad_group<64, 128, 2, 2, 4, 1, 0>(s, grp, n, fill, st);
 }
 
 // expected_rows: how many of the R rows the caller expects to be kept (R if unknown); it only

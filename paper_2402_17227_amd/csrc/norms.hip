@@ -2,6 +2,7 @@
 // Eq. 3 and the per-sample Frobenius norms of Sec. 4.1 of the VCAS paper).
 // HBM-bound: every element is read once, one fp32 per row is written.
 #include "rowsum.hpp"
+#include "sample_a_small.hpp"
 
 namespace vcas {
 
@@ -75,6 +76,24 @@ __global__ __launch_bounds__(256) void cached_xsq_scores_kernel(const float *__r
     sj.score[r] = s1 * __builtin_sqrtf(acc);
 }
 
+// row_sumsq_kernel (without the side jobs) for several matrices of one shape in one launch:
+// blockIdx.y picks the matrix.
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void row_sumsq_group_kernel(RowNormGroup grp, int64_t R, int groups_per_row, int T)
+{
+    const uint4 *__restrict__ A = grp.A[blockIdx.y];
+    float *__restrict__ out = grp.out[blockIdx.y];
+    const uint8_t *__restrict__ sample_keep = grp.keep[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t row = wave; row < R; row += nwaves) {
+        const bool skip = sample_keep && sample_keep[row / T] == 0;
+        const float acc = skip ? 0.0f : wave_row_sumsq<BF16, CH>(A + row * groups_per_row, groups_per_row);
+        if (lane == 0) out[row] = acc;
+    }
+}
+
 // (keep_a, T: as sample_keep above, for the rows of A only.)
 // Row norms of two matrices with the same number of rows in one launch (G and X
 // of a layer when both are small enough that a second launch would cost more
@@ -146,6 +165,33 @@ static vcas_status launch_row_sumsq(const void *A, int64_t R, int K, int T, cons
     else VCAS_LAUNCH_CH(8);
 #undef VCAS_LAUNCH_CH
     return launch_status();
+}
+
+template <bool BF16>
+static vcas_status launch_row_sumsq_group(const RowNormGroup &grp, int n, int64_t R, int K, int T, hipStream_t st)
+{
+    const int groups = K / (BF16 ? 8 : 4);
+    const int need = (groups + 63) / 64;
+    int64_t blocks64 = (R + 3) / 4;
+    const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
+#define VCAS_LAUNCH_CH(C) \
+    hipLaunchKernelGGL((row_sumsq_group_kernel<BF16, C>), dim3(blocks, n), dim3(256), 0, st, grp, R, groups, T)
+    if (need <= 1) VCAS_LAUNCH_CH(1);
+    else if (need <= 2) VCAS_LAUNCH_CH(2);
+    else if (need <= 3) VCAS_LAUNCH_CH(3);
+    else if (need <= 4) VCAS_LAUNCH_CH(4);
+    else if (need <= 6) VCAS_LAUNCH_CH(6);
+    else VCAS_LAUNCH_CH(8);
+#undef VCAS_LAUNCH_CH
+    return launch_status();
+}
+
+// row_sumsq for n <= kMaxSiblings matrices [R, K] in one launch
+vcas_status row_sumsq_group(const RowNormGroup &grp, int n, int dtype, int64_t R, int K, int T, hipStream_t st)
+{
+    if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
+    return dtype == VCAS_BF16 ? launch_row_sumsq_group<true>(grp, n, R, K, T, st)
+                              : launch_row_sumsq_group<false>(grp, n, R, K, T, st);
 }
 
 vcas_status row_sumsq(const void *A, int dtype, int64_t R, int K, int T, const uint8_t *keep, float *out,

@@ -400,6 +400,14 @@ __global__ __launch_bounds__(1024) void sampler_a_fast_kernel(const float *__res
     sampler_a_fast_body(gsq, N, T, budget, seed, layer, draw, draw_offset, gnorm, p, maskA, idxA, cntA);
 }
 
+// SampleA of up to kMaxSiblings layers with the same N and T, one workgroup per layer.
+__global__ __launch_bounds__(1024) void sampler_a_group_kernel(SampleAGroup grp, int N, int T)
+{
+    const InlineSampleA &q = grp.prob[blockIdx.x];
+    sampler_a_fast_body(q.gsq, N, T, q.budget, q.seed, q.layer, q.draw, q.draw_offset, q.gnorm, q.p, q.maskA, q.idxA,
+                        q.cntA);
+}
+
 // What the caller has already left in the score and q arrays when SampleW starts.
 enum : int {
     kFromSquares = 0,   // nothing: scores come from gsq, xsq and p
@@ -663,6 +671,14 @@ vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_
     else
         hipLaunchKernelGGL(sampler_a_kernel, dim3(1), dim3(1024), 0, st, gsq, N, T, budget, rng.seed, rng.layer,
                            rng.draw, rng.draw_offset, gnorm, p, maskA, idxA, cntA);
+    return launch_status();
+}
+
+// sampler_a for n <= kMaxSiblings layers of N <= 1024 samples in one launch
+vcas_status sampler_a_group(const SampleAGroup &grp, int n, int N, int T, hipStream_t st)
+{
+    if (n < 1 || n > kMaxSiblings || N > 1024) return VCAS_EINVAL;
+    hipLaunchKernelGGL(sampler_a_group_kernel, dim3(n), dim3(1024), 0, st, grp, N, T);
     return launch_status();
 }
 

@@ -607,6 +607,77 @@ def test_stack_of_layers_equals_layer_by_layer_calls(vb, group, streams):
     assert rel_l2(from_device(outs[2][1]), want_dX) <= TOL[BF16] and rel_l2(from_device(outs[2][2]), want_dW) <= TOL[BF16]
 
 
+@pytest.mark.parametrize("group", [2, 8])
+def test_sibling_layers_share_launches_and_keep_their_bits(vb, group):
+    """Layers marked as siblings (their G does not depend on the previous entry's dX: Q, K, V of one block) may
+    be launched together by vcas_backward_stack.  Each must still come out bit for bit as from a call of its
+    own, and as the oracle says: six layers of one shape in a row (split into launches of at most four, and by
+    the group boundaries), one of another shape in between, a sibling flag on a layer of another shape or
+    dtype (ignored), different keep ratios and Philox layers inside a launch."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    mk = workloads.LayerSpec
+    specs = [mk("sb0", BF16, 8, 128, 264, 136, 0.5, 0.5, layer=0, seed=8, gen_seed=1, token_sigma=0.5),
+             mk("sb1", BF16, 8, 128, 264, 136, 0.9, 0.5, layer=1, seed=8, gen_seed=2, token_sigma=0.5),
+             mk("sb2", BF16, 8, 128, 264, 136, 0.2, 0.7, layer=2, seed=8, gen_seed=3, token_sigma=0.5),
+             mk("sb3", BF16, 8, 128, 264, 136, 0.5, 0.5, layer=3, seed=8, gen_seed=4, token_sigma=0.5),
+             mk("sb4", BF16, 8, 128, 264, 136, 1.0, 1.0, layer=4, seed=8, gen_seed=5, token_sigma=0.5),
+             mk("sb5", BF16, 8, 128, 264, 136, 0.4, 0.5, layer=5, seed=8, gen_seed=6, token_sigma=0.5),
+             mk("sb6", BF16, 8, 128, 136, 264, 0.5, 0.5, layer=6, seed=8, gen_seed=7, token_sigma=0.5),   # other shape
+             mk("sb7", F32, 8, 128, 136, 264, 0.5, 0.5, layer=7, seed=8, gen_seed=8, token_sigma=0.5),    # other dtype
+             mk("sb8", BF16, 32, 128, 768, 768, 0.3, 0.5, layer=8, seed=8, gen_seed=9, token_sigma=0.5),
+             mk("sb9", BF16, 32, 128, 768, 768, 0.6, 0.5, layer=9, seed=8, gen_seed=10, token_sigma=0.5),
+             mk("sb10", BF16, 32, 128, 768, 768, 1.0, 0.5, layer=10, seed=8, gen_seed=11, token_sigma=0.5),
+             # vectors too long for the dgrad workgroups to decide SampleA themselves: one SampleA launch for all
+             mk("sb11", BF16, 12, 400, 72, 136, 0.5, 0.5, layer=11, seed=8, gen_seed=12, token_sigma=0.5),
+             mk("sb12", BF16, 12, 400, 72, 136, 0.3, 0.5, layer=12, seed=8, gen_seed=13, token_sigma=0.5),
+             mk("sb13", BF16, 12, 400, 72, 136, 0.8, 0.5, layer=13, seed=8, gen_seed=14, token_sigma=0.5),
+             # more samples than a wavefront
+             mk("sb14", BF16, 100, 8, 136, 72, 0.5, 0.5, layer=14, seed=8, gen_seed=15, token_sigma=0.5),
+             mk("sb15", BF16, 100, 8, 136, 72, 0.25, 0.5, layer=15, seed=8, gen_seed=16, token_sigma=0.5)]
+    flags = [False, True, True, True, True, True, True, True, False, True, True, False, True, True, False, True]
+    refs, entries, outs, keep, host = [], [], [], [], []
+    for sp, flag in zip(specs, flags):
+        G, X, W = workloads.make_layer(sp)
+        shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+        g, x, w = (to_device(a, sp.dtype) for a in (G, X, W))
+        tdt = torch.bfloat16 if sp.dtype == BF16 else torch.float32
+
+        def fresh():
+            return (vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape),
+                    torch.full((sp.R, sp.K_in), float("nan"), dtype=tdt, device="cuda"),
+                    torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda"))
+        rng = vb.Rng(sp.seed, sp.layer, 4)
+        plan_r, ws_r, dX_r, dW_r = fresh()
+        vb.vcas_linear_backward(shape, g, x, w, sp.rho, sp.nu, rng, True, plan_r, dX_r, dW_r, ws_r)
+        refs.append((plan_to_numpy(plan_r), dX_r, dW_r))
+        plan, ws, dX, dW = fresh()
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, None, flag))
+        outs.append((plan, dX, dW))
+        keep.append((g, x, w, ws, ws_r))
+        host.append((G, X, W))
+    torch.cuda.synchronize()
+    stack = vb.make_stack(entries)
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(2):
+        vb.vcas_backward_stack(stack, group, s2, s3)
+    torch.cuda.synchronize()
+
+    def bits(t):
+        return t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    for sp, (plan, dX, dW), (plan_r, dX_r, dW_r) in zip(specs, outs, refs):
+        got = plan_to_numpy(plan)
+        for key, val in plan_r.items():
+            assert np.array_equal(np.asarray(got[key]), np.asarray(val)), (sp.name, key)
+        assert torch.equal(bits(dX), bits(dX_r)), sp.name
+        assert torch.equal(bits(dW), bits(dW_r)), sp.name
+    for k in (2, 9, 12, 15):
+        sp = specs[k]
+        G, X, W = host[k]
+        want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 4)
+        compare_plan(plan_to_numpy(outs[k][0]), want)
+        assert rel_l2(from_device(outs[k][1]), want_dX) <= TOL[BF16] and rel_l2(from_device(outs[k][2]), want_dW) <= TOL[BF16]
+
+
 @pytest.mark.parametrize("streams", [1, 3])
 def test_cached_row_norms_of_x_give_the_same_bits(vb, streams):
     """The squared row norms of X can be taken once, when X is produced (vcas_row_norms over every row), and
