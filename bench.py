@@ -242,7 +242,7 @@ def main():
     ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
     ap.add_argument("--side-streams", type=int, default=1, help="streams the weight-gradient halves rotate over")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a HIP graph")
-    ap.add_argument("--stack", type=int, default=4, metavar="GROUP",
+    ap.add_argument("--stack", type=int, default=3, metavar="GROUP",
                     help="the default launch: one vcas_backward_stack call per step (from the host, no graph), "
                          "cross-stream dependencies once per GROUP layers, SampleW and dW on two side streams; "
                          "0 = per-layer calls (see --graph-free options below)")

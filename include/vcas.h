@@ -239,7 +239,8 @@ typedef struct {
  *                   group's last SampleA: row norms of X where still due, SampleW;
  *   gemm_stream     after the group's SampleW: dW (and its split-K reduction).
  * Consecutive entries marked `sibling` that have one shape may share the launches
- * of their data halves (up to four layers per launch).
+ * of their data halves and of their weight gradients (up to four layers per
+ * launch); a group is extended rather than cut inside such a run.
  * Towards the end of the stack the groups shrink (each takes half of the layers
  * that are left), so that the side streams finish shortly after `stream`.
  * sampler_stream and gemm_stream may be the same stream, or null (= `stream`).

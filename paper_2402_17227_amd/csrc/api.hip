@@ -54,6 +54,7 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
                        const InlineSampleA *sample_a, hipStream_t st);
 vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
                              hipStream_t st);
+vcas_status wgrad_bf16_group(const vcas_shape &s, const WgradProblem *probs, int n, int tile, int splits, hipStream_t st);
 vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
                        hipStream_t st);
@@ -156,6 +157,14 @@ static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void
 
 // expected_tokens: how many tokens the caller expects SampleW to keep (R if unknown); it only
 // steers the tile choice.
+// Tile edge and split-K slices dispatch_wgrad picks for a bf16 layer.
+static void wgrad_choice_bf16(const vcas_shape &s, int64_t expected_tokens, int &tile, int &splits)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    tile = wgrad_tile_bf16(s.K_out, s.K_in, expected_tokens > 0 && expected_tokens < R ? expected_tokens : R);
+    splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile));
+}
+
 static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
                                   const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
                                   int64_t expected_tokens, hipStream_t st)
@@ -165,9 +174,8 @@ static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void
     float *partials = reinterpret_cast<float *>(base + w.partials);
     if (s.dtype != VCAS_BF16)
         return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split(&s), st);
-    const int64_t R = (int64_t)s.N * s.T;
-    const int tile = wgrad_tile_bf16(s.K_out, s.K_in, expected_tokens > 0 && expected_tokens < R ? expected_tokens : R);
-    const int splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile));
+    int tile, splits;
+    wgrad_choice_bf16(s, expected_tokens, tile, splits);
     return wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, tile, splits, st);
 }
 
@@ -545,8 +553,10 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
     for (int l = 0; l < L;) {
         first.push_back(l);
         const int left = L - l;
-        const int n = left > 2 * group ? group : (left + 1) / 2;
-        l += n < 1 ? 1 : n;
+        int n = left > 2 * group ? group : (left + 1) / 2;
+        if (n < 1) n = 1;
+        while (l + n < L && layers[l + n].sibling) ++n;   // a run of siblings is not cut: it shares launches
+        l += n;
     }
     first.push_back(L);
     const int groups = (int)first.size() - 1;
@@ -585,12 +595,51 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
             return VCAS_EHIP;
-        for (int l = l0; l < l1; ++l) {
-            const vcas_layer_args &a = layers[l];
-            if (!a.dW) continue;
+        auto expected_tokens = [](const vcas_layer_args &a) {
             const int64_t R = (int64_t)a.shape.N * a.shape.T;
-            VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
-                                    (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5), s3));
+            return (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5);
+        };
+        for (int l = l0; l < l1;) {
+            const vcas_layer_args &a = layers[l];
+            if (!a.dW) {
+                ++l;
+                continue;
+            }
+            // sibling layers that would run with the same tile and slices share the launch (and the
+            // launch of their reductions): the order of a weight gradient's sums, hence its bits, stays
+            int n = 1, tile = 0, splits = 0;
+            if (a.shape.dtype == VCAS_BF16) {
+                wgrad_choice_bf16(a.shape, expected_tokens(a), tile, splits);
+                while (l + n < l1 && n < kMaxSiblings) {
+                    const vcas_layer_args &b = layers[l + n];
+                    int tile_b, splits_b;
+                    if (!b.sibling || !b.dW || b.shape.dtype != VCAS_BF16 || b.shape.N != a.shape.N ||
+                        b.shape.T != a.shape.T || b.shape.K_in != a.shape.K_in || b.shape.K_out != a.shape.K_out)
+                        break;
+                    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b);
+                    if (tile_b != tile || splits_b != splits) break;
+                    ++n;
+                }
+            }
+            if (n > 1) {
+                WgradProblem probs[kMaxSiblings];
+                for (int i = 0; i < n; ++i) {
+                    const vcas_layer_args &b = layers[l + i];
+                    probs[i].G = static_cast<const uint16_t *>(b.G);
+                    probs[i].X = static_cast<const uint16_t *>(b.X);
+                    probs[i].row_scale = b.plan.scaleW;
+                    probs[i].idxW = b.plan.idxW;
+                    probs[i].cntW = b.plan.cntW;
+                    probs[i].dW = b.dW;
+                    probs[i].partials = reinterpret_cast<float *>(static_cast<unsigned char *>(b.workspace) +
+                                                                  workspace_layout(&b.shape).partials);
+                }
+                VCAS_TRY(wgrad_bf16_group(a.shape, probs, n, tile, splits, s3));
+            } else {
+                VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
+                                        expected_tokens(a), s3));
+            }
+            l += n;
         }
     }
     return VCAS_OK;

@@ -663,10 +663,9 @@ __host__ __device__ inline int wgrad_active_splits(int steps_all, int splits, in
 // dW = partial[0] + partial[1] + ... in that order; does nothing when only one
 // split was active (the GEMM wrote dW itself).  `step` is the GEMM's
 // contraction step in tokens.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partials,
-                                                            const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                            int64_t R, int64_t elems, int splits, int min_steps,
-                                                            int step)
+__device__ __forceinline__ void splitk_reduce_body(const float *__restrict__ partials,
+                                                   const int32_t *__restrict__ cntW, float *__restrict__ dW,
+                                                   int64_t R, int64_t elems, int splits, int min_steps, int step)
 {
     const int64_t cnt = min((int64_t)max(*cntW, 0), R);
     int per;
@@ -691,6 +690,33 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partials,
+                                                            const int32_t *__restrict__ cntW, float *__restrict__ dW,
+                                                            int64_t R, int64_t elems, int splits, int min_steps,
+                                                            int step)
+{
+    splitk_reduce_body(partials, cntW, dW, R, elems, splits, min_steps, step);
+}
+
+// the same for several layers of one shape: blockIdx.y picks the layer
+__global__ __launch_bounds__(256) void splitk_reduce_group_kernel(WgradGroup grp, int64_t R, int64_t elems, int splits,
+                                                                  int min_steps, int step)
+{
+    const WgradProblem &q = grp.prob[blockIdx.y];
+    splitk_reduce_body(q.partials, q.cntW, q.dW, R, elems, splits, min_steps, step);
+}
+
+static vcas_status splitk_reduce_group(const WgradGroup &grp, int n, int64_t R, int64_t elems, int splits,
+                                       int min_steps, int step, hipStream_t st)
+{
+    if (splits <= 1) return VCAS_OK;
+    int64_t blocks = (elems / 4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_reduce_group_kernel, dim3((unsigned)blocks, (unsigned)n), dim3(256), 0, st, grp, R, elems,
+                       splits, min_steps, step);
+    return launch_status();
+}
+
 vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW, int64_t R, int64_t elems, int splits,
                           int min_steps, int step, hipStream_t st)
 {
@@ -712,15 +738,13 @@ vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW,
 // order, so the sum order is fixed.  (An in-kernel "last workgroup reduces"
 // scheme was measured first: its device-scope fences write back the XCD's L2
 // and cost more than the second launch.)
-template <int BM, int BN, int WM, int WN, int OCC>
-__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint16_t *__restrict__ G,
-                                                                  const uint16_t *__restrict__ X,
-                                                                  const float *__restrict__ row_scale,
-                                                                  const int32_t *__restrict__ idxW,
-                                                                  const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                                  float *__restrict__ partials, int64_t R, int K_in,
-                                                                  int K_out, int tiles_n, int tiles, int splits,
-                                                                  int min_steps)
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void wgrad_bf16_body(const uint16_t *__restrict__ G, const uint16_t *__restrict__ X,
+                                                const float *__restrict__ row_scale,
+                                                const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW,
+                                                float *__restrict__ dW, float *__restrict__ partials, int64_t R,
+                                                int K_in, int K_out, int tiles_n, int tiles, int splits,
+                                                int min_steps)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -855,6 +879,31 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
         }
 }
 
+template <int BM, int BN, int WM, int WN, int OCC>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint16_t *__restrict__ G,
+                                                                  const uint16_t *__restrict__ X,
+                                                                  const float *__restrict__ row_scale,
+                                                                  const int32_t *__restrict__ idxW,
+                                                                  const int32_t *__restrict__ cntW, float *__restrict__ dW,
+                                                                  float *__restrict__ partials, int64_t R, int K_in,
+                                                                  int K_out, int tiles_n, int tiles, int splits,
+                                                                  int min_steps)
+{
+    wgrad_bf16_body<BM, BN, WM, WN>(G, X, row_scale, idxW, cntW, dW, partials, R, K_in, K_out, tiles_n, tiles, splits,
+                                    min_steps);
+}
+
+// Several layers of one shape (siblings) in one launch: blockIdx.y picks the layer.
+template <int BM, int BN, int WM, int WN, int OCC>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_group_kernel(WgradGroup grp, int64_t R, int K_in,
+                                                                        int K_out, int tiles_n, int tiles,
+                                                                        int splits, int min_steps)
+{
+    const WgradProblem &q = grp.prob[blockIdx.y];
+    wgrad_bf16_body<BM, BN, WM, WN>(q.G, q.X, q.row_scale, q.idxW, q.cntW, q.dW, q.partials, R, K_in, K_out, tiles_n,
+                                    tiles, splits, min_steps);
+}
+
 // The 128x128 weight-gradient kernel for layers with many kept tokens.  Same split-K protocol
 // and epilogue as above, different data path: X goes straight into LDS (LDS-direct loads, as in
 // dgrad), G passes through registers only to be multiplied by the per-token scale and is written
@@ -864,7 +913,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint
 // consecutive kept tokens (one 16-byte index load); they occupy LDS rows 4 apart, which is fine
 // because both tiles use the same row order and the contraction does not care about it.
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_kernel(
+__device__ __forceinline__ void wgrad_bf16_dma_body(
     const uint16_t *__restrict__ G, const uint16_t *__restrict__ X, const float *__restrict__ row_scale,
     const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW, float *__restrict__ dW,
     float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles, int splits, int min_steps)
@@ -1050,6 +1099,26 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_kernel(
         }
 }
 
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_kernel(
+    const uint16_t *__restrict__ G, const uint16_t *__restrict__ X, const float *__restrict__ row_scale,
+    const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW, float *__restrict__ dW,
+    float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles, int splits, int min_steps)
+{
+    wgrad_bf16_dma_body<BM, BN, WM, WN>(G, X, row_scale, idxW, cntW, dW, partials, R, K_in, K_out, tiles_n, tiles,
+                                        splits, min_steps);
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_group_kernel(WgradGroup grp, int64_t R, int K_in,
+                                                                          int K_out, int tiles_n, int tiles,
+                                                                          int splits, int min_steps)
+{
+    const WgradProblem &q = grp.prob[blockIdx.y];
+    wgrad_bf16_dma_body<BM, BN, WM, WN>(q.G, q.X, q.row_scale, q.idxW, q.cntW, q.dW, q.partials, R, K_in, K_out,
+                                        tiles_n, tiles, splits, min_steps);
+}
+
 // ---------------------------------------------------------- host launchers
 
 // Tile edge of the bf16 weight-gradient GEMM: 128, unless dW has so few 128x128 tiles that filling
@@ -1218,6 +1287,41 @@ static vcas_status launch_wgrad_dma(const vcas_shape &s, const void *G, const vo
                  tiles, splits, MIN_STEPS);
     if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
     return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
+}
+
+// wgrad of n <= kMaxSiblings layers of shape s in one launch, and one launch for their reductions:
+// tile and splits as for a layer on its own, so that every dW keeps its bits.
+vcas_status wgrad_bf16_group(const vcas_shape &s, const WgradProblem *probs, int n, int tile, int splits, hipStream_t st)
+{
+    if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
+    WgradGroup grp = {};
+    for (int i = 0; i < n; ++i) grp.prob[i] = probs[i];
+    constexpr int MIN_STEPS = 2;
+    const int64_t R = (int64_t)s.N * s.T;
+    const int tiles_n = (s.K_in + tile - 1) / tile;
+    const int tiles = ((s.K_out + tile - 1) / tile) * tiles_n;
+    if (splits > 8) splits = 8;
+    const size_t lds = 2 * (size_t)(tile + tile) * 128;
+    const int grid = (tiles * splits + 7) / 8 * 8;
+    if (tile == 64) {
+        auto kern = wgrad_bf16_group_kernel<64, 64, 2, 1, 2>;
+        static bool allowed = false;
+        if (!allowed) {
+            if (!allow_lds(kern, lds)) return VCAS_EHIP;
+            allowed = true;
+        }
+        launch_timed(1, kern, dim3(grid, n), dim3(128), lds, st, grp, R, s.K_in, s.K_out, tiles_n, tiles, splits, MIN_STEPS);
+    } else {
+        auto kern = wgrad_bf16_dma_group_kernel<128, 128, 2, 2>;
+        static bool allowed = false;
+        if (!allowed) {
+            if (!allow_lds(kern, lds)) return VCAS_EHIP;
+            allowed = true;
+        }
+        launch_timed(1, kern, dim3(grid, n), dim3(256), lds, st, grp, R, s.K_in, s.K_out, tiles_n, tiles, splits, MIN_STEPS);
+    }
+    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
+    return splitk_reduce_group(grp, n, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
 }
 
 // tile: 64 or 128 (wgrad_tile_bf16); splits: as sized by the caller for that tile

@@ -146,6 +146,17 @@ struct SampleAGroup {
     InlineSampleA prob[kMaxSiblings];
 };
 
+// One layer of a grouped wgrad launch and of the split-K reduction behind it.
+struct WgradProblem {
+    const uint16_t *G, *X;
+    const float *row_scale;
+    const int32_t *idxW, *cntW;
+    float *dW, *partials;
+};
+struct WgradGroup {
+    WgradProblem prob[kMaxSiblings];
+};
+
 // The same for the row-norm launch: matrix, where its row sums go, and (null: all) the samples
 // whose rows are read at all.
 struct RowNormGroup {
