@@ -1,5 +1,6 @@
 // C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
 // launches on the caller's stream.  See include/vcas.h for the contract.
+#include "rowsum.hpp"
 #include "sample_a_small.hpp"
 
 namespace vcas {
@@ -34,6 +35,11 @@ vcas_status broadcast_data_mask(const uint8_t *maskA, int64_t R, int T, float *q
 vcas_status sampler_a(const float *gsq, int N, int T, double budget, const vcas_rng &rng, float *gnorm, float *p,
                       uint8_t *maskA, int32_t *idxA, int32_t *cntA, hipStream_t st);
 vcas_status sampler_a_group(const SampleAGroup &grp, int n, int N, int T, hipStream_t st);
+vcas_status sampler_w_group(const SampleWGroup &grp, int n, int zero_dropped_xsq, int N, int T, int token_sampling,
+                            int prepared, hipStream_t st);
+vcas_status row_sumsq_scores_uniforms_group(const RowJobGroup &grp, int n, int dtype, int64_t R, int K, int T,
+                                            hipStream_t st);
+static_assert(kMaxSiblings == 4, "RowJobGroup holds four entries");
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
 vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
                       const float *u, int N, int T, double budget, int token_sampling, int prepared, float *score,
@@ -356,6 +362,53 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
     return dgrad_bf16_group(s, probs, n, true, (int64_t)((double)R * rho_max + 0.5), st);
 }
 
+// Can layer b share the SampleW launches of layer a in front of it?  Siblings of one shape and
+// dtype with the same kind of token sampling, the rows of X still to be swept, and few enough
+// rows for the one-workgroup sampler.
+static bool shares_weight_half(const vcas_layer_args &a, const vcas_layer_args &b)
+{
+    const vcas_shape &s = a.shape, &t = b.shape;
+    return b.sibling != 0 && s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out &&
+           s.dtype == t.dtype && (int64_t)s.N * s.T <= 16384 && !a.xsq_forward && !b.xsq_forward &&
+           (a.token_sampling != 0) == (b.token_sampling != 0);
+}
+
+// What weight_half does before dW, for n sibling layers (shares_weight_half) whose data halves
+// left the norms of X to it: the row norms of X on kept samples with the SampleW scores and
+// uniforms in one launch, SampleW in one launch (a workgroup per layer).  The same bits.
+static vcas_status weight_half_siblings(const vcas_layer_args *layers, int n, hipStream_t st)
+{
+    const vcas_shape &s = layers[0].shape;
+    const int64_t R = (int64_t)s.N * s.T;
+    const int token_sampling = layers[0].token_sampling;
+    RowJobGroup norms = {};
+    SampleWGroup samplers = {};
+    for (int i = 0; i < n; ++i) {
+        const vcas_layer_args &a = layers[i];
+        float *u = uniforms_of(a.shape, a.workspace);
+        norms.A[i] = static_cast<const uint4 *>(a.X);
+        norms.keep[i] = a.plan.maskA;
+        norms.out[i] = a.plan.xsq;
+        norms.job[i] = {token_sampling ? u : nullptr, a.rng.seed, a.rng.layer, 1u, a.rng.draw, a.rng.draw_offset};
+        norms.sj[i] = {a.plan.gsq, a.plan.p, a.plan.score};
+        SampleWProblem &w = samplers.prob[i];
+        w.gsq = a.plan.gsq;
+        w.xsq = a.plan.xsq;
+        w.p = a.plan.p;
+        w.maskA = a.plan.maskA;
+        w.u = u;
+        w.budget = (double)R * a.rho * a.nu;
+        w.score = a.plan.score;
+        w.q = a.plan.q;
+        w.maskW = a.plan.maskW;
+        w.scaleW = a.plan.scaleW;
+        w.idxW = a.plan.idxW;
+        w.cntW = a.plan.cntW;
+    }
+    VCAS_TRY(row_sumsq_scores_uniforms_group(norms, n, s.dtype, R, s.K_in, s.T, st));
+    return sampler_w_group(samplers, n, 0, s.N, s.T, token_sampling, 2, st);
+}
+
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
                                         double nu, const vcas_rng &rng, int token_sampling, const vcas_plan &pl,
                                         void *dX, float *dW, void *workspace, hipStream_t st, hipStream_t side)
@@ -587,10 +640,18 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
                          hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))
             return VCAS_EHIP;
-        for (int l = l0; l < l1; ++l) {
+        for (int l = l0; l < l1;) {
             const vcas_layer_args &a = layers[l];
-            VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr, a.workspace,
-                                 s2, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, a.xsq_forward));
+            int n = 1;
+            if (s2 != st)
+                while (l + n < l1 && n < kMaxSiblings && shares_weight_half(a, layers[l + n])) ++n;
+            if (n > 1)
+                VCAS_TRY(weight_half_siblings(layers + l, n, s2));
+            else
+                VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr,
+                                     a.workspace, s2, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default,
+                                     a.xsq_forward));
+            l += n;
         }
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))

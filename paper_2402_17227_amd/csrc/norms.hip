@@ -15,9 +15,9 @@ namespace vcas {
 // the square roots and the division then run on every CU instead of in the one
 // workgroup of the sampler.
 template <bool BF16, int CH>
-__global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
-                                                        int T, const uint8_t *__restrict__ sample_keep,
-                                                        float *__restrict__ out, UniformJob job, ScoreJob sj)
+__device__ __forceinline__ void row_sumsq_body(const uint4 *__restrict__ A, int64_t R, int groups_per_row, int T,
+                                               const uint8_t *__restrict__ sample_keep, float *__restrict__ out,
+                                               const UniformJob &job, const ScoreJob &sj)
 {
     if (job.uniforms) {
         const uint32_t draw = job.draw + (job.draw_offset ? *job.draw_offset : 0u);
@@ -74,6 +74,23 @@ __global__ __launch_bounds__(256) void cached_xsq_scores_kernel(const float *__r
     const float acc = xsq_forward[r];
     xsq[r] = acc;
     sj.score[r] = s1 * __builtin_sqrtf(acc);
+}
+
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void row_sumsq_kernel(const uint4 *__restrict__ A, int64_t R, int groups_per_row,
+                                                        int T, const uint8_t *__restrict__ sample_keep,
+                                                        float *__restrict__ out, UniformJob job, ScoreJob sj)
+{
+    row_sumsq_body<BF16, CH>(A, R, groups_per_row, T, sample_keep, out, job, sj);
+}
+
+// The same, side jobs included, for several matrices of one shape: blockIdx.y picks the matrix.
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void row_sumsq_jobs_group_kernel(RowJobGroup grp, int64_t R, int groups_per_row,
+                                                                   int T)
+{
+    const int z = blockIdx.y;
+    row_sumsq_body<BF16, CH>(grp.A[z], R, groups_per_row, T, grp.keep[z], grp.out[z], grp.job[z], grp.sj[z]);
 }
 
 // row_sumsq_kernel (without the side jobs) for several matrices of one shape in one launch:
@@ -182,6 +199,34 @@ static vcas_status launch_row_sumsq_group(const RowNormGroup &grp, int n, int64_
     else if (need <= 4) VCAS_LAUNCH_CH(4);
     else if (need <= 6) VCAS_LAUNCH_CH(6);
     else VCAS_LAUNCH_CH(8);
+#undef VCAS_LAUNCH_CH
+    return launch_status();
+}
+
+// row_sumsq_scores_uniforms for n <= kMaxSiblings layers of one shape in one launch
+vcas_status row_sumsq_scores_uniforms_group(const RowJobGroup &grp, int n, int dtype, int64_t R, int K, int T,
+                                            hipStream_t st)
+{
+    if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
+    const bool bf = dtype == VCAS_BF16;
+    const int groups = K / (bf ? 8 : 4);
+    const int need = (groups + 63) / 64;
+    int64_t blocks64 = (R + 3) / 4;
+    const int blocks = (int)(blocks64 < 4096 ? blocks64 : 4096);
+#define VCAS_LAUNCH_CH(B, C) \
+    hipLaunchKernelGGL((row_sumsq_jobs_group_kernel<B, C>), dim3(blocks, n), dim3(256), 0, st, grp, R, groups, T)
+#define VCAS_LAUNCH_DT(C)          \
+    do {                           \
+        if (bf) VCAS_LAUNCH_CH(true, C); \
+        else VCAS_LAUNCH_CH(false, C);   \
+    } while (0)
+    if (need <= 1) VCAS_LAUNCH_DT(1);
+    else if (need <= 2) VCAS_LAUNCH_DT(2);
+    else if (need <= 3) VCAS_LAUNCH_DT(3);
+    else if (need <= 4) VCAS_LAUNCH_DT(4);
+    else if (need <= 6) VCAS_LAUNCH_DT(6);
+    else VCAS_LAUNCH_DT(8);
+#undef VCAS_LAUNCH_DT
 #undef VCAS_LAUNCH_CH
     return launch_status();
 }

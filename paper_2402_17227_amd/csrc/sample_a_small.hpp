@@ -157,6 +157,23 @@ struct WgradGroup {
     WgradProblem prob[kMaxSiblings];
 };
 
+// One layer of a grouped SampleW launch: the pointer arguments of the one-workgroup sampler.
+struct SampleWProblem {
+    const float *gsq;
+    float *xsq;
+    const float *p;
+    const uint8_t *maskA;
+    const float *u;
+    double budget;
+    float *score, *q;
+    uint8_t *maskW;
+    float *scaleW;
+    int32_t *idxW, *cntW;
+};
+struct SampleWGroup {
+    SampleWProblem prob[kMaxSiblings];
+};
+
 // The same for the row-norm launch: matrix, where its row sums go, and (null: all) the samples
 // whose rows are read at all.
 struct RowNormGroup {

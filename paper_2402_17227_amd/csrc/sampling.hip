@@ -527,6 +527,16 @@ __global__ __launch_bounds__(1024) void sampler_w_fast_kernel(const float *__res
                            maskW, scaleW, idxW, cntW);
 }
 
+// SampleW of up to kMaxSiblings layers of one shape, one workgroup per layer.
+template <int E>
+__global__ __launch_bounds__(1024) void sampler_w_group_kernel(SampleWGroup grp, int zero_dropped_xsq, int N, int T,
+                                                               int token_sampling, int prepared)
+{
+    const SampleWProblem &w = grp.prob[blockIdx.x];
+    sampler_w_fast_body<E>(w.gsq, w.xsq, zero_dropped_xsq, w.p, w.maskA, w.u, N, T, w.budget, token_sampling, prepared,
+                           w.score, w.q, w.maskW, w.scaleW, w.idxW, w.cntW);
+}
+
 // SampleA: ||G_i||_F from gsq, p, Bernoulli mask over samples, kept list.
 __global__ __launch_bounds__(1024) void sampler_a_kernel(const float *__restrict__ gsq, int N, int T, double budget,
                                                          uint64_t seed, uint32_t layer, uint32_t draw,
@@ -704,6 +714,21 @@ vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const 
     else
         hipLaunchKernelGGL(sampler_w_kernel, dim3(1), dim3(1024), 0, st, VCAS_SAMPLER_W_ARGS);
 #undef VCAS_SAMPLER_W_ARGS
+    return launch_status();
+}
+
+// sampler_w for n <= kMaxSiblings layers with at most 16384 rows each in one launch
+vcas_status sampler_w_group(const SampleWGroup &grp, int n, int zero_dropped_xsq, int N, int T, int token_sampling,
+                            int prepared, hipStream_t st)
+{
+    const int64_t R = (int64_t)N * T;
+    if (n < 1 || n > kMaxSiblings || R > 16384) return VCAS_EINVAL;
+    if (R <= 4096)
+        hipLaunchKernelGGL(sampler_w_group_kernel<4>, dim3(n), dim3(1024), 0, st, grp, zero_dropped_xsq, N, T,
+                           token_sampling, prepared);
+    else
+        hipLaunchKernelGGL(sampler_w_group_kernel<16>, dim3(n), dim3(1024), 0, st, grp, zero_dropped_xsq, N, T,
+                           token_sampling, prepared);
     return launch_status();
 }
 
