@@ -308,7 +308,7 @@ def main():
     sides = [] if args.one_stream else [torch.cuda.Stream() for _ in range(args.side_streams)]
 
     stack = None
-    if args.graph or args.eager or args.one_stream or args.counters_pass:
+    if args.graph or args.eager or args.one_stream:
         args.stack = 0
         if args.xsq_cached:
             sys.exit("bench.py: --xsq-cached goes with the stack launch only")
