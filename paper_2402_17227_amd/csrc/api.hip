@@ -1,7 +1,6 @@
 // C ABI of the VCAS gfx950 library: argument checks on the host, then kernel
 // launches on the caller's stream.  See include/vcas.h for the contract.
-#include "rowsum.hpp"
-#include "sample_a_small.hpp"
+#include "groups.hpp"
 
 namespace vcas {
 
@@ -39,7 +38,6 @@ vcas_status sampler_w_group(const SampleWGroup &grp, int n, int zero_dropped_xsq
                             int prepared, hipStream_t st);
 vcas_status row_sumsq_scores_uniforms_group(const RowJobGroup &grp, int n, int dtype, int64_t R, int K, int T,
                                             hipStream_t st);
-static_assert(kMaxSiblings == 4, "RowJobGroup holds four entries");
 vcas_status uniforms(int64_t R, const vcas_rng &rng, uint32_t stream_id, float *u, hipStream_t st);
 vcas_status sampler_w(const float *gsq, float *xsq, int zero_dropped_xsq, const float *p, const uint8_t *maskA,
                       const float *u, int N, int T, double budget, int token_sampling, int prepared, float *score,

@@ -24,7 +24,7 @@
 // per-row 1/p goes into the epilogue.
 #include <type_traits>
 
-#include "sample_a_small.hpp"
+#include "groups.hpp"
 
 namespace vcas {
 

@@ -2,7 +2,7 @@
 // Eq. 3 and the per-sample Frobenius norms of Sec. 4.1 of the VCAS paper).
 // HBM-bound: every element is read once, one fp32 per row is written.
 #include "rowsum.hpp"
-#include "sample_a_small.hpp"
+#include "groups.hpp"
 
 namespace vcas {
 

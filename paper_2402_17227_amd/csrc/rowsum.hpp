@@ -70,13 +70,4 @@ struct ScoreJob {
     float *score;       // null: no job
 };
 
-// Row norms with their side jobs for up to four matrices of one shape in one launch.
-struct RowJobGroup {
-    const uint4 *A[4];
-    const uint8_t *keep[4];
-    float *out[4];
-    UniformJob job[4];
-    ScoreJob sj[4];
-};
-
 }  // namespace vcas

@@ -126,60 +126,4 @@ struct InlineSampleA {
     int32_t *idxA, *cntA;
 };
 
-// One layer of a grouped dgrad launch (layers of one shape that do not depend on each other):
-// the pointer arguments of the bf16 dgrad kernel.
-struct DgradProblem {
-    const uint16_t *G, *W;
-    const float *p;
-    const int32_t *idxA, *cntA;
-    uint16_t *dX;
-    const uint16_t *J;   // null: no Jacobian
-    InlineSampleA sa;    // sa.gsq null: SampleA has been decided, p / idxA / cntA hold its outcome
-};
-constexpr int kMaxSiblings = 4;
-struct DgradGroup {
-    DgradProblem prob[kMaxSiblings];
-};
-
-// SampleA of several layers in one launch: one workgroup each, the fields of InlineSampleA.
-struct SampleAGroup {
-    InlineSampleA prob[kMaxSiblings];
-};
-
-// One layer of a grouped wgrad launch and of the split-K reduction behind it.
-struct WgradProblem {
-    const uint16_t *G, *X;
-    const float *row_scale;
-    const int32_t *idxW, *cntW;
-    float *dW, *partials;
-};
-struct WgradGroup {
-    WgradProblem prob[kMaxSiblings];
-};
-
-// One layer of a grouped SampleW launch: the pointer arguments of the one-workgroup sampler.
-struct SampleWProblem {
-    const float *gsq;
-    float *xsq;
-    const float *p;
-    const uint8_t *maskA;
-    const float *u;
-    double budget;
-    float *score, *q;
-    uint8_t *maskW;
-    float *scaleW;
-    int32_t *idxW, *cntW;
-};
-struct SampleWGroup {
-    SampleWProblem prob[kMaxSiblings];
-};
-
-// The same for the row-norm launch: matrix, where its row sums go, and (null: all) the samples
-// whose rows are read at all.
-struct RowNormGroup {
-    const uint4 *A[kMaxSiblings];
-    float *out[kMaxSiblings];
-    const uint8_t *keep[kMaxSiblings];
-};
-
 }  // namespace vcas

@@ -4,7 +4,7 @@
 // steps (leverage scores, per-row scale).  All vectors are at most R floats,
 // so these kernels are latency-bound, not bandwidth-bound.
 #include "rowsum.hpp"
-#include "sample_a_small.hpp"
+#include "groups.hpp"
 
 namespace vcas {
 
