@@ -121,3 +121,73 @@ def test_side_stream_gives_the_same_bits_eager_and_captured():
         torch.cuda.synchronize()
         graph.replay()
         check(snapshot())
+
+
+def test_stack_launch_captured_in_a_graph_matches_eager():
+    """vcas_backward_stack is meant for eager launching, but a caller may still capture it: its events then
+    become edges of the graph and the side streams join the capture.  Every replay must give the bits of the
+    eager call with the same draw, sibling launches included."""
+    from paper_2402_17227_amd import binding as vb
+    from tests.gpu_util import to_device, plan_to_numpy
+    mk = workloads.LayerSpec
+    specs = [mk("cap0", workloads.BF16, 10, 60, 264, 200, 0.6, 0.5, layer=0, seed=5, gen_seed=31, token_sigma=0.5),
+             mk("cap1", workloads.BF16, 10, 60, 136, 136, 0.5, 0.5, layer=1, seed=5, gen_seed=32, token_sigma=0.5),
+             mk("cap2", workloads.BF16, 10, 60, 136, 136, 0.7, 0.5, layer=2, seed=5, gen_seed=33, token_sigma=0.5),
+             mk("cap3", workloads.BF16, 10, 60, 136, 136, 0.4, 0.5, layer=3, seed=5, gen_seed=34, token_sigma=0.5),
+             mk("cap4", workloads.F32, 6, 50, 72, 136, 0.6, 0.4, layer=4, seed=5, gen_seed=35, token_sigma=0.5)]
+    flags = [False, False, True, True, False]
+    counter = torch.zeros(1, dtype=torch.int32, device="cuda")
+    layers, entries = [], []
+    for spec, flag in zip(specs, flags):
+        G, X, W = workloads.make_layer(spec)
+        shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+        g, x, w = (to_device(a, spec.dtype) for a in (G, X, W))
+        plan, ws = vb.Plan.allocate(spec.N, spec.T), vb.make_workspace(shape)
+        dX = torch.empty((spec.R, spec.K_in), dtype=g.dtype, device="cuda")
+        dW = torch.empty((spec.K_out, spec.K_in), device="cuda")
+        layers.append((plan, dX, dW, g, x, w, ws))
+        entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
+                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws, None,
+                                     flag))
+    stack = vb.make_stack(entries)
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def step():
+        main = torch.cuda.current_stream()
+        counter.add_(1)
+        vb.vcas_backward_stack(stack, 3, s2, s3)
+        main.wait_stream(s2)
+        main.wait_stream(s3)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [(plan_to_numpy(plan), dX.float().cpu().numpy().copy(), dW.cpu().numpy().copy())
+                for plan, dX, dW, *_ in layers]
+
+    def clear():
+        for plan, dX, dW, *_ in layers:
+            dX.fill_(float("nan"))
+            dW.fill_(float("nan"))
+            plan.cntW.fill_(-1)
+
+    want = []
+    for _ in range(3):                       # eager: draws 1, 2, 3
+        clear()
+        step()
+        want.append(snapshot())
+    assert any(not np.array_equal(a[0]["maskW"], b[0]["maskW"]) for a, b in zip(want[0], want[1]))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    counter.zero_()
+    for d in range(3):
+        clear()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for (gp, gx, gw), (wp, wx, ww) in zip(got, want[d]):
+            for k in ("gsq", "xsq", "p", "q", "maskA", "maskW", "idxA", "idxW", "scaleW", "score"):
+                assert np.array_equal(gp[k], wp[k]), (d, k)
+            assert gp["cntA"] == wp["cntA"] and gp["cntW"] == wp["cntW"]
+            assert np.array_equal(gx, wx) and np.array_equal(gw, ww), d
+        _ = (torch.randn(256, 256, device="cuda") @ torch.randn(256, 256, device="cuda")).sum().item()
