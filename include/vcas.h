@@ -225,6 +225,12 @@ typedef struct {
                         Q, K and V projections of one attention block all get their gradients from
                         the attention backward), so vcas_backward_stack may launch the two data
                         halves together instead of one behind the other; results are the same bits */
+    /* The three additions of vcas_backward_data_chained, for a stack whose entries feed each other
+       (an entry's dX buffer is the next entry's G): all optional, zero = off. */
+    const void *J;             /* elementwise Jacobian [R,K_in] multiplied into dX; needs dX */
+    const uint8_t *kept_above; /* N bytes, device: 0 = sample dropped by a layer above (its rows of G are
+                                  never read); usually the maskA array of the previous entry's plan */
+    int32_t leave_dropped_rows; /* nonzero: rows of dX of samples this layer does not keep are not written */
 } vcas_layer_args;
 
 /*

@@ -47,7 +47,8 @@ class LayerArgs(C.Structure):
     """vcas_layer_args"""
     _fields_ = [("shape", Shape), ("G", C.c_void_p), ("X", C.c_void_p), ("W", C.c_void_p), ("rho", C.c_double),
                 ("nu", C.c_double), ("rng", Rng), ("token_sampling", C.c_int32), ("plan", PlanPtrs),
-                ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p), ("xsq_forward", C.c_void_p), ("sibling", C.c_int32)]
+                ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p), ("xsq_forward", C.c_void_p), ("sibling", C.c_int32),
+                ("J", C.c_void_p), ("kept_above", C.c_void_p), ("leave_dropped_rows", C.c_int32)]
 
 
 _lib = None
@@ -198,7 +199,8 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
 
 
 def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dX, dW,
-               workspace, xsq_forward=None, sibling=False) -> LayerArgs:
+               workspace, xsq_forward=None, sibling=False, J=None, kept_above=None,
+               leave_dropped_rows=False) -> LayerArgs:
     """One entry of the array vcas_backward_stack takes (the tensors must stay alive while it is used)."""
     a = LayerArgs()
     a.shape = shape
@@ -210,6 +212,8 @@ def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sam
     a.dX, a.dW, a.workspace = _ptr(dX), _ptr(dW), _ptr(workspace)
     a.xsq_forward = _ptr(xsq_forward)
     a.sibling = 1 if sibling else 0
+    a.J, a.kept_above = _ptr(J), _ptr(kept_above)
+    a.leave_dropped_rows = 1 if leave_dropped_rows else 0
     return a
 
 

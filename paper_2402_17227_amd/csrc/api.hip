@@ -309,7 +309,8 @@ static bool shares_data_half(const vcas_layer_args &a, const vcas_layer_args &b)
 {
     const vcas_shape &s = a.shape, &t = b.shape;
     return b.sibling != 0 && s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out &&
-           s.dtype == VCAS_BF16 && t.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX;
+           s.dtype == VCAS_BF16 && t.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX &&
+           (a.leave_dropped_rows != 0) == (b.leave_dropped_rows != 0);
 }
 
 // Data halves of n sibling layers (shares_data_half): the row norms of every G in one launch,
@@ -329,7 +330,7 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         const vcas_layer_args &a = layers[i];
         norms.A[i] = static_cast<const uint4 *>(a.G);
         norms.out[i] = a.plan.gsq;
-        norms.keep[i] = nullptr;
+        norms.keep[i] = a.kept_above;
         InlineSampleA sa;
         sa.gsq = a.plan.gsq;
         sa.budget = (double)s.N * a.rho;
@@ -350,14 +351,14 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         q.idxA = a.plan.idxA;
         q.cntA = a.plan.cntA;
         q.dX = static_cast<uint16_t *>(a.dX);
-        q.J = nullptr;
+        q.J = static_cast<const uint16_t *>(a.J);
         q.sa = sa;
         if (!in_dgrad) q.sa.gsq = nullptr;
         if (a.rho > rho_max) rho_max = a.rho;
     }
     VCAS_TRY(row_sumsq_group(norms, n, s.dtype, R, s.K_out, s.T, st));
     if (!in_dgrad) VCAS_TRY(sampler_a_group(samplers, n, s.N, s.T, st));
-    return dgrad_bf16_group(s, probs, n, true, (int64_t)((double)R * rho_max + 0.5), st);
+    return dgrad_bf16_group(s, probs, n, layers[0].leave_dropped_rows == 0, (int64_t)((double)R * rho_max + 0.5), st);
 }
 
 // Can layer b share the SampleW launches of layer a in front of it?  Siblings of one shape and
@@ -594,6 +595,8 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (a.dX && !a.W) return VCAS_ENULL;
         if (!a.workspace) return VCAS_EWORKSPACE;
         if (!ratio_ok(a.rho) || !ratio_ok(a.nu) || (a.xsq_forward && a.xsq_forward == a.plan.xsq)) return VCAS_EINVAL;
+        if (a.J && !a.dX) return VCAS_ENULL;
+        if (a.J && !aligned16(a.J)) return VCAS_EINVAL;
         if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
             (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
             return VCAS_EINVAL;
@@ -630,9 +633,14 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
                 while (l + n < l1 && n < kMaxSiblings && shares_data_half(a, layers[l + n])) ++n;
             if (n > 1)
                 VCAS_TRY(data_half_siblings(layers + l, n, st));
-            else
-                VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, ChainArgs(),
+            else {
+                ChainArgs chain;
+                chain.J = a.J;
+                chain.kept_above = a.kept_above;
+                chain.fill = a.leave_dropped_rows == 0;
+                VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, chain,
                                    a.workspace, st, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, true));
+            }
             l += n;
         }
         if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||

@@ -517,6 +517,7 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
     kept_above_dev = None
     kept_above = np.ones(N, bool)
     conv = (lambda a: workloads.f32_to_bf16_bits(a)) if dtype == BF16 else (lambda a: a)
+    per_layer = []
     for l, rho in enumerate(rhos):
         k_in = K_in if l == 0 else K_out            # only the top layer is wide; its dX feeds a K_out-wide G below
         k_out = K_out if l == 0 else (K_in if l == 1 else K_out)
@@ -552,7 +553,33 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
         assert rel_l2(from_device(dW), want_dW) <= TOL[dtype]
         kept_above, kept_above_dev = kept, plan.maskA
         g = dX
+        per_layer.append((shape, x, w, jac, rho, r, plan_to_numpy(plan), dX, dW))
     assert kept_above.sum() < N
+
+    # the same chain as ONE vcas_backward_stack call: every entry's G is the dX buffer of the entry before it
+    entries, outs, keep = [], [], []
+    g = to_device(G_host, dtype)
+    above = None
+    for shape, x, w, jac, rho, r, _, dX_ref, dW_ref in per_layer:
+        plan = vb.Plan.allocate(N, T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full_like(dX_ref, float("nan"))
+        dW = torch.full_like(dW_ref, float("nan"))
+        entries.append(vb.layer_args(shape, g, x, w, rho, nu, r, True, plan, dX, dW, ws, None, False, jac, above, True))
+        outs.append((plan, dX, dW))
+        keep.append((g, ws))
+        g, above = dX, plan.maskA
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    vb.vcas_backward_stack(vb.make_stack(entries), 2, s2, s3)
+    torch.cuda.synchronize()
+
+    def bits(t):
+        return t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    for (plan, dX, dW), (_, _, _, _, _, _, plan_ref, dX_ref, dW_ref) in zip(outs, per_layer):
+        got = plan_to_numpy(plan)
+        for key, val in plan_ref.items():
+            assert np.array_equal(np.asarray(got[key]), np.asarray(val)), key
+        assert torch.equal(bits(dX), bits(dX_ref)) and torch.equal(bits(dW), bits(dW_ref))
 
 
 @pytest.mark.parametrize("group,streams", [(1, 3), (2, 3), (3, 2), (5, 1)])
@@ -676,6 +703,50 @@ def test_sibling_layers_share_launches_and_keep_their_bits(vb, group):
         want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 4)
         compare_plan(plan_to_numpy(outs[k][0]), want)
         assert rel_l2(from_device(outs[k][1]), want_dX) <= TOL[BF16] and rel_l2(from_device(outs[k][2]), want_dW) <= TOL[BF16]
+
+
+def test_sibling_layers_inside_a_sparse_chain(vb):
+    """Siblings with the additions of the chained data call: a mask of samples dropped above, an elementwise
+    Jacobian each, dropped rows left unwritten.  One stack call against per-layer chained calls, bit for bit."""
+    from tests.gpu_util import to_device, plan_to_numpy
+    N, T, K_in, K_out = 20, 64, 136, 264
+    rng_np = np.random.default_rng(41)
+    above = torch.from_numpy((rng_np.uniform(size=N) < 0.7).astype(np.uint8)).cuda()
+    entries, outs, refs, keep = [], [], [], []
+    for k in range(3):
+        sp = workloads.LayerSpec(f"sc{k}", BF16, N, T, K_in, K_out, 0.5 + 0.2 * k, 0.5, layer=k, seed=12, gen_seed=50 + k,
+                                 token_sigma=0.5)
+        G, X, W = workloads.make_layer(sp)
+        shape = vb.shape_of(N, T, K_in, K_out, BF16)
+        g, x, w = (to_device(a, BF16) for a in (G, X, W))
+        g.view(N, T, K_out)[above == 0] = float("nan")                  # rows that must never be read
+        jac = to_device(workloads.f32_to_bf16_bits((rng_np.uniform(size=(N * T, K_in)) < 0.6).astype(np.float32)), BF16)
+        r = vb.Rng(sp.seed, sp.layer, 1)
+
+        def fresh():
+            return (vb.Plan.allocate(N, T), vb.make_workspace(shape),
+                    torch.full((N * T, K_in), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                    torch.full((K_out, K_in), float("nan"), dtype=torch.float32, device="cuda"))
+        plan_r, ws_r, dX_r, dW_r = fresh()
+        vb.vcas_backward_data_chained(shape, g, x, w, jac, above, False, sp.rho, r, True, plan_r, dX_r, ws_r)
+        vb.vcas_backward_weight(shape, g, x, sp.rho, sp.nu, r, True, plan_r, dW_r, ws_r)
+        refs.append((plan_r, dX_r, dW_r))
+        plan, ws, dX, dW = fresh()
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, r, True, plan, dX, dW, ws, None, k > 0, jac, above,
+                                     True))
+        outs.append((plan, dX, dW))
+        keep.append((g, x, w, jac, ws, ws_r))
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    vb.vcas_backward_stack(vb.make_stack(entries), 3, s2, s3)
+    torch.cuda.synchronize()
+    for (plan, dX, dW), (plan_r, dX_r, dW_r) in zip(outs, refs):
+        got, want = plan_to_numpy(plan), plan_to_numpy(plan_r)
+        for key, val in want.items():
+            assert np.array_equal(np.asarray(got[key]), np.asarray(val)), key
+        assert not np.any(got["maskA"].astype(bool) & ~above.cpu().numpy().astype(bool))
+        assert torch.equal(dX.view(torch.int16), dX_r.view(torch.int16))
+        assert torch.equal(dW.view(torch.int32), dW_r.view(torch.int32))
+        assert torch.isfinite(dW).all()
 
 
 @pytest.mark.parametrize("streams", [1, 3])

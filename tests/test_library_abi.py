@@ -87,6 +87,11 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
     arr[1].nu = 0.5
     arr[1].xsq_forward = 0x1000                                                  # the cache must not be plan.xsq itself
     assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
+    arr[1].xsq_forward = 0
+    arr[1].J, arr[1].dX = 0x1000, 0                                              # a Jacobian needs a dX
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 2
+    arr[1].J, arr[1].dX = 0x1008, 0x1000                                         # and the usual alignment
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
     cached = lib.vcas_backward_weight_cached
     assert cached(C.byref(good), fake, fake, null, C.c_double(0.5), C.c_double(0.5), C.byref(rng), C.c_int32(1),
                   C.byref(plan), fake, fake, null) == 2                          # no cache given
