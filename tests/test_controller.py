@@ -72,10 +72,12 @@ def test_sparsity_ratio_of_a_real_plan(vb):
     spec = workloads.LayerSpec("ctl", BF16, 32, 128, 768, 768, 0.5, 0.5, layer=3, seed=1, gen_seed=2, token_sigma=0.5)
     G, X, W = workloads.make_layer(spec)
     plan, _, _ = run_layer_gpu(spec, G, X, W, want_dX=False, want_dW=False)
+    gn = oracle.sample_norms(oracle.row_sumsq(G, BF16), spec.N, spec.T)      # the oracle's own norms ...
+    assert np.array_equal(plan["gnorm"].view(np.uint32), gn.view(np.uint32))  # ... which are the library's, bit for bit
     out = torch.empty(2, device="cuda")
     vb.vcas_sparsity_ratio(torch.from_numpy(plan["gnorm"]).cuda(), [0.79, 0.81], out)
     torch.cuda.synchronize()
-    want = [oracle.sparsity_ratio(plan["gnorm"], s) for s in (0.79, 0.81)]
+    want = [oracle.sparsity_ratio(gn, s) for s in (0.79, 0.81)]
     assert out.cpu().tolist() == want and want[0] <= want[1]
 
 

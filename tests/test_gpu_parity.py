@@ -381,42 +381,79 @@ def test_data_and_weight_halves_equal_the_whole(vb, spec):
     assert np.array_equal(from_device(dX), whole_dX) and np.array_equal(from_device(dW), whole_dW)
 
 
+def _to_layer_dtype(a64, dtype):
+    """fp64 values -> the layer's storage (fp32, or bf16 bit patterns): how a tensor the oracle computed
+    becomes the next layer's input."""
+    a32 = np.asarray(a64, np.float64).astype(np.float32)
+    return workloads.f32_to_bf16_bits(a32) if dtype == BF16 else a32
+
+
+def _oracle_chain(dtype, N, T, G_top, layers, nu, seed, draw=0):
+    """A chain of layers computed by the oracle alone: layer l's G is the oracle's own dX of layer l-1
+    (times the Jacobian, if any), stored in the layer dtype, zero on dropped samples.  layers: list of
+    (X, W, J or None, rho).  Returns per layer (G, plan, dX fp64, dW fp64).  Nothing here comes from the GPU:
+    the GPU is then fed these G and compared with these results."""
+    out = []
+    G = G_top
+    for l, (X, W, J, rho) in enumerate(layers):
+        plan, dX, dW = oracle.linear_backward(G, X, W, dtype, N, T, rho, nu, seed, l, draw)
+        if J is not None:
+            dX = oracle.dgrad_jacobian(G, W, J, dtype, N, T, plan.p, plan.maskA)
+        out.append((G, plan, dX, dW))
+        G = _to_layer_dtype(dX, dtype)
+    return out
+
+
 def test_chained_layers_keep_dropped_samples_dropped(vb):
     """Three linears in a row, each layer's dX (kept rows scaled, dropped rows zero) serving as the G of
-    the layer below (Sec. 3: the activation gradient grows sparser layer by layer, rho_l monotone).  Each
-    layer is compared with the oracle on the very tensor the GPU fed it, and the kept sets must nest:
-    a sample dropped above has zero norm below, hence p = 0 and no token of it is ever kept."""
+    the layer below (Sec. 3: the activation gradient grows sparser layer by layer, rho_l monotone).
+    The oracle computes the chain on its own; the GPU gets each layer's G from the oracle and must match
+    its plan bit for bit.  Then the GPU runs the chain on its own tensors, and the kept sets must nest: a
+    sample dropped above has zero norm below, hence p = 0 and no token of it is ever kept."""
     from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
     N, T, K = 24, 40, 136
     rhos, nu = [0.8, 0.6, 0.4], 0.5                      # top layer first
     rng = np.random.default_rng(7)
     top = workloads.LayerSpec("chain", BF16, N, T, K, K, rhos[0], nu, layer=0, seed=3, gen_seed=21, token_sigma=0.5)
     G_host, _, _ = workloads.make_layer(top)
-    g = to_device(G_host, BF16)
     shape = vb.shape_of(N, T, K, K, BF16)
-    kept_above = np.ones(N, bool)
-    for l, rho in enumerate(rhos):
-        X_host = workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32))
-        W_host = workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32))
-        x, w = to_device(X_host, BF16), to_device(W_host, BF16)
+    layers = [(workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32)),
+               workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32)), None, rho)
+              for rho in rhos]
+    chain = _oracle_chain(BF16, N, T, G_host, layers, nu, 3)
+
+    def run(g, l):
+        X_host, W_host, _, rho = layers[l]
         plan = vb.Plan.allocate(N, T)
         ws = vb.make_workspace(shape)
         dX = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
         dW = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
-        vb.vcas_linear_backward(shape, g, x, w, rho, nu, vb.Rng(3, l, 0), True, plan, dX, dW, ws)
+        vb.vcas_linear_backward(shape, g, to_device(X_host, BF16), to_device(W_host, BF16), rho, nu, vb.Rng(3, l, 0),
+                                True, plan, dX, dW, ws)
         torch.cuda.synchronize()
-        G_fed = g.view(torch.int16).cpu().numpy().view(np.uint16)          # what this layer actually got
-        want, want_dX, want_dW = oracle.linear_backward(G_fed, X_host, W_host, BF16, N, T, rho, nu, 3, l, 0)
-        got = plan_to_numpy(plan)
+        return plan_to_numpy(plan), dX, dW
+
+    kept_above = np.ones(N, bool)
+    for l, (G_l, want, want_dX, want_dW) in enumerate(chain):        # every layer on the oracle's G
+        got, dX, dW = run(to_device(G_l, BF16), l)
         compare_plan(got, want)
         assert rel_l2(from_device(dX), want_dX) <= TOL[BF16] and rel_l2(from_device(dW), want_dW) <= TOL[BF16]
+        assert not np.any(want.maskA.astype(bool) & ~kept_above)
+        kept_above = want.maskA.astype(bool)
+    assert kept_above.sum() < N                                            # something was dropped on the way
+
+    kept_above = np.ones(N, bool)
+    g = to_device(G_host, BF16)
+    for l in range(len(rhos)):                                             # the GPU's own chain: structure
+        got, dX, dW = run(g, l)
         kept = got["maskA"].astype(bool)
         assert not np.any(kept & ~kept_above)                              # nested kept sets
         assert np.all(got["p"][~kept_above] == 0) and np.all(got["gnorm"][~kept_above] == 0)
         assert np.all(got["q"][np.repeat(~kept_above, T)] == 0)
+        assert np.all(from_device(dX)[np.repeat(~kept, T)] == 0) and torch.isfinite(dW).all()
         kept_above = kept
         g = dX                                                             # Jacobian of the identity in between
-    assert kept_above.sum() < N                                            # something was dropped on the way
+    assert kept_above.sum() < N
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -460,13 +497,18 @@ def test_dgrad_through_an_elementwise_jacobian(vb, dtype, N, T, kin, kout, frac)
 
 def test_chained_layers_through_relu_jacobians(vb):
     """Two linears with an elementwise layer between them: the upper layer's data half writes
-    (dX * J) (vcas_backward_data_chained), which is the lower layer's G as it stands."""
+    (dX * J) (vcas_backward_data_chained), which is the lower layer's G as it stands.  Expectations and
+    the lower layer's G come from the oracle's own chain; the GPU's own hand-over is checked for structure."""
     from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
     N, T, K = 16, 48, 136
     rng = np.random.default_rng(11)
     top = workloads.LayerSpec("chain_j", BF16, N, T, K, K, 0.7, 0.5, layer=0, seed=5, gen_seed=2, token_sigma=0.5)
     G_host, X_host, W_host = workloads.make_layer(top)
     J_host = workloads.f32_to_bf16_bits((rng.uniform(size=(N * T, K)) < 0.5).astype(np.float32))
+    X2 = workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32))
+    W2 = workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32))
+    (_, want, want_dX, want_dW), (G2, want2, want_dX2, want_dW2) = _oracle_chain(
+        BF16, N, T, G_host, [(X_host, W_host, J_host, 0.7), (X2, W2, None, 0.5)], 0.5, 5)
     shape = vb.shape_of(N, T, K, K, BF16)
     g, x, w, jac = (to_device(a, BF16) for a in (G_host, X_host, W_host, J_host))
     plan = vb.Plan.allocate(N, T)
@@ -476,33 +518,35 @@ def test_chained_layers_through_relu_jacobians(vb):
     vb.vcas_backward_data_chained(shape, g, x, w, jac, None, True, 0.7, vb.Rng(5, 0, 0), True, plan, dX, ws)
     vb.vcas_backward_weight(shape, g, x, 0.7, 0.5, vb.Rng(5, 0, 0), True, plan, dW, ws)
     torch.cuda.synchronize()
-    want, _, want_dW = oracle.linear_backward(G_host, X_host, W_host, BF16, N, T, 0.7, 0.5, 5, 0, 0)
     compare_plan(plan_to_numpy(plan), want)
-    want_dX = oracle.dgrad_jacobian(G_host, W_host, J_host, BF16, N, T, want.p, want.maskA)
     assert rel_l2(from_device(dX), want_dX) <= TOL[BF16] and rel_l2(from_device(dW), want_dW) <= TOL[BF16]
-    # the layer below takes that tensor as its G
-    X2 = workloads.f32_to_bf16_bits(rng.standard_normal((N * T, K)).astype(np.float32))
-    W2 = workloads.f32_to_bf16_bits((rng.standard_normal((K, K)) * 0.1).astype(np.float32))
-    plan2 = vb.Plan.allocate(N, T)
-    dX2 = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
-    dW2 = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
-    vb.vcas_linear_backward(shape, dX, to_device(X2, BF16), to_device(W2, BF16), 0.5, 0.5, vb.Rng(5, 1, 0), True,
-                            plan2, dX2, dW2, ws)
-    torch.cuda.synchronize()
-    G2 = dX.view(torch.int16).cpu().numpy().view(np.uint16)
-    want2, want_dX2, want_dW2 = oracle.linear_backward(G2, X2, W2, BF16, N, T, 0.5, 0.5, 5, 1, 0)
-    got2 = plan_to_numpy(plan2)
+
+    def lower(g2):
+        plan2 = vb.Plan.allocate(N, T)
+        dX2 = torch.full((N * T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dW2 = torch.full((K, K), float("nan"), dtype=torch.float32, device="cuda")
+        vb.vcas_linear_backward(shape, g2, to_device(X2, BF16), to_device(W2, BF16), 0.5, 0.5, vb.Rng(5, 1, 0), True,
+                                plan2, dX2, dW2, ws)
+        torch.cuda.synchronize()
+        return plan_to_numpy(plan2), dX2, dW2
+    # the layer below on the oracle's version of that tensor ...
+    got2, dX2, dW2 = lower(to_device(G2, BF16))
     compare_plan(got2, want2)
     assert rel_l2(from_device(dX2), want_dX2) <= TOL[BF16] and rel_l2(from_device(dW2), want_dW2) <= TOL[BF16]
+    # ... and on the tensor the GPU itself handed over
+    got2, dX2, dW2 = lower(dX)
     dropped = want.maskA == 0
     assert np.all(got2["p"][dropped] == 0) and not np.any(got2["maskA"][dropped])
+    assert torch.isfinite(dX2).all() and torch.isfinite(dW2).all()
 
 
 @pytest.mark.parametrize("dtype,K_in", [(BF16, 136), (F32, 72), (BF16, 4096)])
 def test_chained_layers_without_zero_fill(vb, dtype, K_in):
     """A stack in its sparse form: no layer writes the rows of samples it drops (they keep the NaN they
     were initialised with) and the layer below is told which samples exist (kept_above = the upper
-    layer's maskA), so it never reads them.  The oracle gets the same tensors with those rows zeroed.
+    layer's maskA), so it never reads them.  The oracle computes the chain on its own, with those rows as
+    zeros; the GPU gets each layer's G from the oracle with NaN planted in them.  Then the GPU's own chain,
+    as per-layer calls and as ONE vcas_backward_stack call, bit for bit the same.
     K_in = 4096 takes the path that norms X after SampleA (X above 16 MiB)."""
     from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
     N, T, K = (24, 90, 136) if K_in == 4096 else (24, 40, K_in)
@@ -512,34 +556,40 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
     top = workloads.LayerSpec("sparse_chain", dtype, N, T, K_out, K_out, rhos[0], nu, layer=0, seed=8, gen_seed=31,
                               token_sigma=0.5)
     G_host, _, _ = workloads.make_layer(top)
-    g = to_device(G_host, dtype)
     tdt = torch.bfloat16 if dtype == BF16 else torch.float32
-    kept_above_dev = None
-    kept_above = np.ones(N, bool)
     conv = (lambda a: workloads.f32_to_bf16_bits(a)) if dtype == BF16 else (lambda a: a)
-    per_layer = []
+    layers, shapes = [], []
     for l, rho in enumerate(rhos):
-        k_in = K_in if l == 0 else K_out            # only the top layer is wide; its dX feeds a K_out-wide G below
+        k_in = K_in if l == 0 else K_out            # only the top layer is wide; its dX feeds a K_in-wide G below
         k_out = K_out if l == 0 else (K_in if l == 1 else K_out)
+        shapes.append((k_in, k_out))
+        layers.append((conv(rng.standard_normal((N * T, k_in)).astype(np.float32)),
+                       conv((rng.standard_normal((k_out, k_in)) * 0.1).astype(np.float32)),
+                       conv((rng.uniform(size=(N * T, k_in)) < 0.7).astype(np.float32)), rho))
+    chain = _oracle_chain(dtype, N, T, G_host, layers, nu, 8)
+    dev = [tuple(to_device(a, dtype) for a in (X, W, J)) for X, W, J, _ in layers]
+
+    def run(l, g, above_dev):
+        k_in, k_out = shapes[l]
         shape = vb.shape_of(N, T, k_in, k_out, dtype)
-        X_host = conv(rng.standard_normal((N * T, k_in)).astype(np.float32))
-        W_host = conv((rng.standard_normal((k_out, k_in)) * 0.1).astype(np.float32))
-        J_host = conv((rng.uniform(size=(N * T, k_in)) < 0.7).astype(np.float32))
-        x, w, jac = (to_device(a, dtype) for a in (X_host, W_host, J_host))
+        x, w, jac = dev[l]
         plan = vb.Plan.allocate(N, T)
         ws = vb.make_workspace(shape)
         dX = torch.full((N * T, k_in), float("nan"), dtype=tdt, device="cuda")
         dW = torch.full((k_out, k_in), float("nan"), dtype=torch.float32, device="cuda")
         r = vb.Rng(8, l, 0)
-        vb.vcas_backward_data_chained(shape, g, x, w, jac, kept_above_dev, False, rho, r, True, plan, dX, ws)
-        vb.vcas_backward_weight(shape, g, x, rho, nu, r, True, plan, dW, ws)
+        vb.vcas_backward_data_chained(shape, g, x, w, jac, above_dev, False, layers[l][3], r, True, plan, dX, ws)
+        vb.vcas_backward_weight(shape, g, x, layers[l][3], nu, r, True, plan, dW, ws)
         torch.cuda.synchronize()
-        G_fed = from_device(g).astype(np.float32)
-        assert np.isnan(G_fed[np.repeat(~kept_above, T)]).all() or kept_above.all()
-        G_fed[np.repeat(~kept_above, T)] = 0.0                             # what those rows stand for
-        G_fed = conv(G_fed)
-        want, _, want_dW = oracle.linear_backward(G_fed, X_host, W_host, dtype, N, T, rho, nu, 8, l, 0)
-        want_dX = oracle.dgrad_jacobian(G_fed, W_host, J_host, dtype, N, T, want.p, want.maskA)
+        return shape, r, plan, dX, dW, ws
+
+    # every layer on the oracle's G, the rows of samples dropped above replaced by NaN
+    kept_above = np.ones(N, bool)
+    for l, (G_l, want, want_dX, want_dW) in enumerate(chain):
+        g = to_device(G_l, dtype)
+        g.view(N, T, -1)[torch.from_numpy(~kept_above).cuda()] = float("nan")
+        above_dev = None if l == 0 else torch.from_numpy(kept_above.astype(np.uint8)).cuda()
+        _, _, plan, dX, dW, _ = run(l, g, above_dev)
         got = plan_to_numpy(plan)
         compare_plan(got, want)
         kept = got["maskA"].astype(bool)
@@ -551,21 +601,32 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
         if kept.any():
             assert rel_l2(got_dX[kept_rows], want_dX[kept_rows]) <= TOL[dtype]
         assert rel_l2(from_device(dW), want_dW) <= TOL[dtype]
-        kept_above, kept_above_dev = kept, plan.maskA
-        g = dX
-        per_layer.append((shape, x, w, jac, rho, r, plan_to_numpy(plan), dX, dW))
+        kept_above = kept
     assert kept_above.sum() < N
 
-    # the same chain as ONE vcas_backward_stack call: every entry's G is the dX buffer of the entry before it
+    # the GPU's own chain, layer by layer: each dX buffer is the next G, each maskA the next kept_above
+    per_layer = []
+    g, above_dev, kept_above = to_device(G_host, dtype), None, np.ones(N, bool)
+    for l in range(len(rhos)):
+        shape, r, plan, dX, dW, ws = run(l, g, above_dev)
+        kept = plan.maskA.cpu().numpy().astype(bool)
+        assert not np.any(kept & ~kept_above)
+        assert torch.isnan(dX.float().view(N, T, -1)[torch.from_numpy(~kept).cuda()]).all()
+        assert torch.isfinite(dX.float().view(N, T, -1)[torch.from_numpy(kept).cuda()]).all() and torch.isfinite(dW).all()
+        per_layer.append((shape, r, plan_to_numpy(plan), dX, dW, plan, ws))
+        g, above_dev, kept_above = dX, plan.maskA, kept
+
+    # the same chain as ONE vcas_backward_stack call
     entries, outs, keep = [], [], []
-    g = to_device(G_host, dtype)
-    above = None
-    for shape, x, w, jac, rho, r, _, dX_ref, dW_ref in per_layer:
+    g, above = to_device(G_host, dtype), None
+    for l, (shape, r, _, dX_ref, dW_ref, _, _) in enumerate(per_layer):
+        x, w, jac = dev[l]
         plan = vb.Plan.allocate(N, T)
         ws = vb.make_workspace(shape)
         dX = torch.full_like(dX_ref, float("nan"))
         dW = torch.full_like(dW_ref, float("nan"))
-        entries.append(vb.layer_args(shape, g, x, w, rho, nu, r, True, plan, dX, dW, ws, None, False, jac, above, True))
+        entries.append(vb.layer_args(shape, g, x, w, layers[l][3], nu, r, True, plan, dX, dW, ws, None, False, jac, above,
+                                     True))
         outs.append((plan, dX, dW))
         keep.append((g, ws))
         g, above = dX, plan.maskA
@@ -575,7 +636,7 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
 
     def bits(t):
         return t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
-    for (plan, dX, dW), (_, _, _, _, _, _, plan_ref, dX_ref, dW_ref) in zip(outs, per_layer):
+    for (plan, dX, dW), (_, _, plan_ref, dX_ref, dW_ref, _, _) in zip(outs, per_layer):
         got = plan_to_numpy(plan)
         for key, val in plan_ref.items():
             assert np.array_equal(np.asarray(got[key]), np.asarray(val)), key
