@@ -90,7 +90,11 @@ def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
     torch.cuda.synchronize()
     draw = int(counter.item())
     assert draw == 3
+    _check_against_oracle(spec, G, X, W, plan, dX, dW, draw)
 
+
+def _check_against_oracle(spec, G, X, W, plan, dX, dW, draw):
+    from tests.gpu_util import plan_to_numpy, compare_plan, rel_l2
     want = oracle.sampling_plan(G, X, spec.dtype, spec.N, spec.T, spec.rho, spec.nu, spec.seed, spec.layer, draw)
     got = plan_to_numpy(plan)
     compare_plan(got, want)
@@ -120,6 +124,45 @@ def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
     assert rel_l2(val, ref) <= 1e-2
     scale = np.sqrt(np.mean(ref ** 2))
     assert np.max(np.abs(val - ref) / (np.abs(ref) + scale)) <= 2e-2
+
+
+@pytest.mark.parametrize("workload", ["bert_base", "bert_large"])
+def test_full_size_sibling_layers_in_shared_launches(vb, workload):
+    """The V, K and Q projections of one block at full size, launched as bench.py launches them: one
+    vcas_backward_stack call, groups of three, K and Q marked as siblings of V, so that the three share their
+    row-norm, SampleA, dgrad, X-sweep, SampleW, wgrad and reduction launches.  bert_base: SampleA inside the
+    dgrad workgroups; bert_large: a SampleA launch with a workgroup per layer."""
+    from tests.gpu_util import to_device
+    block = "b5" if workload == "bert_base" else "b11"
+    specs = [s for s in workloads.config(workload) if s.name.split(".")[1] == block and s.name.split(".")[2] in "vkq"]
+    assert [s.name.split(".")[2] for s in specs] == ["v", "k", "q"]
+    counter = torch.zeros(1, dtype=torch.int32, device="cuda")
+    host, entries, outs, keep = [], [], [], []
+    for k, spec in enumerate(specs):
+        G, X, W = workloads.make_layer(spec)
+        shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
+        g, x, w = (to_device(a, spec.dtype) for a in (G, X, W))
+        plan = vb.Plan.allocate(spec.N, spec.T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda")
+        dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
+        entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
+                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws, None,
+                                     k > 0))
+        host.append((G, X, W))
+        outs.append((plan, dX, dW))
+        keep.append((g, x, w, ws))
+    stack = vb.make_stack(entries)
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    for draw in (1, 2):
+        main = torch.cuda.current_stream()
+        counter.add_(1)
+        vb.vcas_backward_stack(stack, 3, s2, s3)
+        main.wait_stream(s2)
+        main.wait_stream(s3)
+    torch.cuda.synchronize()
+    for spec, (G, X, W), (plan, dX, dW) in zip(specs, host, outs):
+        _check_against_oracle(spec, G, X, W, plan, dX, dW, 2)
 
 
 def test_variance_probe_at_vit_size_with_eight_draws(vb):
