@@ -253,6 +253,11 @@ def main():
     ap.add_argument("--no-siblings", action="store_true",
                     help="stack launch: do not mark the K and Q projections as siblings of V (every data half then "
                          "waits for the one before it)")
+    ap.add_argument("--chained", action="store_true",
+                    help="stack launch: the layers feed each other as in a real backward pass (down's dX buffer is up's G, "
+                         "up's is o's, o's is the G of V, K and Q, Q's is the next block's down's), every layer is told "
+                         "which samples the one above kept and leaves the rows of dropped samples unwritten; only the top "
+                         "layer's G is an input")
     ap.add_argument("--xsq-cached", action="store_true",
                     help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
                          "pass would, vcas_row_norms over every row) and handed to the weight halves; not the default, "
@@ -310,19 +315,29 @@ def main():
     stack = None
     if args.graph or args.eager or args.one_stream:
         args.stack = 0
-        if args.xsq_cached:
-            sys.exit("bench.py: --xsq-cached goes with the stack launch only")
+        if args.xsq_cached or args.chained:
+            sys.exit("bench.py: --xsq-cached and --chained go with the stack launch only")
     if args.stack > 0:
         for l in layers:
             l.xsq_forward = None
             if args.xsq_cached:
                 l.xsq_forward = torch.empty(l.spec.R, dtype=torch.float32, device="cuda")
                 vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
-        stack = vb.make_stack([vb.layer_args(l.shape, l.G, l.X, l.W, l.spec.rho, l.spec.nu,
-                                             vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
-                                             l.plan, l.dX, l.dW, l.ws, l.xsq_forward,
-                                             sibling=not args.no_siblings and _is_sibling(l.spec.name))
-                              for l in layers])
+        entries, prev = [], None
+        for l in layers:
+            sib = not args.no_siblings and _is_sibling(l.spec.name)
+            G, above = l.G, None
+            if args.chained and prev is not None:
+                # a sibling takes what its elder sibling took; everybody else the dX of the entry before
+                G, above = (prev_G, prev_above) if _is_sibling(l.spec.name) else (prev.dX, prev.plan.maskA)
+                assert G.shape == l.G.shape, (l.spec.name, G.shape, l.G.shape)
+                l.G = G
+            entries.append(vb.layer_args(l.shape, G, l.X, l.W, l.spec.rho, l.spec.nu,
+                                         vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
+                                         l.plan, l.dX, l.dW, l.ws, l.xsq_forward, sibling=sib,
+                                         kept_above=above, leave_dropped_rows=args.chained))
+            prev, prev_G, prev_above = l, G, above
+        stack = vb.make_stack(entries)
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 
     def step():
@@ -450,6 +465,8 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
                    + ("" if args.no_siblings else ", data halves of V, K, Q of a block in shared launches")
+                   + (", layers chained (each dX buffer is the next G, dropped samples stay dropped and unwritten)"
+                      if args.chained else "")
                    + (", row norms of X cached before the timed region" if args.xsq_cached else "")
                    if stack is not None else
                    ("eager" if args.eager else "hip_graph") +

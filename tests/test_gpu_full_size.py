@@ -165,6 +165,58 @@ def test_full_size_sibling_layers_in_shared_launches(vb, workload):
         _check_against_oracle(spec, G, X, W, plan, dX, dW, 2)
 
 
+def test_full_size_block_in_the_chained_launch(vb):
+    """bench.py --chained at full size, one attention block of bert_base: the out-projection, then V, K, Q as
+    siblings that take its dX as their G, know which samples it kept (kept_above) and leave the rows of the
+    samples they drop unwritten.  The oracle computes the out-projection on its own and hands its dX (bf16) to
+    V, K, Q; the GPU gets the same tensor with NaN in the rows of dropped samples, in one stack call."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    specs = {s.name.split(".")[2]: s for s in workloads.config("bert_base") if s.name.split(".")[1] == "b5"}
+    o = specs["o"]
+    G, X, W = workloads.make_layer(o)
+    want_o, dX_o, _ = oracle.linear_backward(G, X, W, o.dtype, o.N, o.T, o.rho, o.nu, o.seed, o.layer, 1)
+    G2 = workloads.f32_to_bf16_bits(dX_o.astype(np.float32))
+    kept = want_o.maskA.astype(bool)
+    assert 0 < kept.sum() < o.N
+    g2 = to_device(G2, BF16)
+    g2.view(o.N, o.T, -1)[torch.from_numpy(~kept).cuda()] = float("nan")
+    above = torch.from_numpy(want_o.maskA.astype(np.uint8)).cuda()
+    entries, outs, keep, host = [], [], [], []
+    for k, name in enumerate(["o", "v", "k", "q"]):
+        sp = specs[name]
+        Gs, Xs, Ws = (G, X, W) if name == "o" else workloads.make_layer(sp)
+        shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+        x, w = to_device(Xs, BF16), to_device(Ws, BF16)
+        g = to_device(G, BF16) if name == "o" else g2
+        plan = vb.Plan.allocate(sp.N, sp.T)
+        ws = vb.make_workspace(shape)
+        dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws,
+                                     None, name in "kq", None, None if name == "o" else above, True))
+        outs.append((sp, plan, dX, dW))
+        keep.append((g, x, w, ws))
+        host.append((G if name == "o" else G2, Xs, Ws))
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    vb.vcas_backward_stack(vb.make_stack(entries), 3, s2, s3)
+    torch.cuda.synchronize()
+    for (sp, plan, dX, dW), (Gs, Xs, Ws) in zip(outs, host):
+        want, want_dX, want_dW = oracle.linear_backward(Gs, Xs, Ws, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed,
+                                                        sp.layer, 1)
+        got = plan_to_numpy(plan)
+        compare_plan(got, want)
+        m = got["maskA"].astype(bool)
+        if sp.name.endswith(".o"):
+            assert np.array_equal(m, kept)
+        else:
+            assert not np.any(m & ~kept)
+        rows = np.repeat(m, sp.T)
+        got_dX = from_device(dX)
+        assert np.isnan(got_dX[~rows]).all() and np.isfinite(got_dX[rows]).all()
+        assert rel_l2(got_dX[rows], want_dX[rows]) <= 1e-2
+        assert rel_l2(from_device(dW), want_dW) <= 1e-2
+
+
 def test_variance_probe_at_vit_size_with_eight_draws(vb):
     """Config 4's probe: N=64, T=197, M=8 draws (Alg. 1's Monte-Carlo lines, Eq. 3)."""
     from tests.gpu_util import to_device
