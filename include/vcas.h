@@ -252,7 +252,8 @@ typedef struct {
  * sampler_stream and gemm_stream may be the same stream, or null (= `stream`).
  * layers: HOST array, read during the call only.  group >= 1.  The call joins
  * nothing: results of the weight halves are complete when the streams they ran
- * on have drained.  All streams at default priority.  Meant for eager launching;
+ * on have drained, and work that reuses any of the layers' buffers (the next
+ * call on the same stack included) must be ordered after all three streams.  All streams at default priority.  Meant for eager launching;
  * under graph capture it is correct but gains nothing over per-layer calls.
  * Every layer's arguments are checked before anything is launched.  The events
  * that order the streams belong to the library and are shared by all calls:

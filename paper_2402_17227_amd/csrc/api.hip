@@ -302,14 +302,25 @@ static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X
     return VCAS_OK;
 }
 
+static bool same_shape(const vcas_shape &s, const vcas_shape &t)
+{
+    return s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out && s.dtype == t.dtype;
+}
+
+// Tokens SampleW is expected to keep (its budget): steers the tile choice of the weight gradient.
+static int64_t expected_tokens(const vcas_layer_args &a)
+{
+    const int64_t R = (int64_t)a.shape.N * a.shape.T;
+    return (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5);
+}
+
 // Can layer b of a stack share the launches of its data half with layer a in front of it?  Only
 // where the caller says that b's G does not depend on a's dX and the two have one shape (bf16, a
 // dX wanted, at most 1024 samples: the one-workgroup SampleA).
 static bool shares_data_half(const vcas_layer_args &a, const vcas_layer_args &b)
 {
-    const vcas_shape &s = a.shape, &t = b.shape;
-    return b.sibling != 0 && s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out &&
-           s.dtype == VCAS_BF16 && t.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX &&
+    const vcas_shape &s = a.shape;
+    return b.sibling != 0 && same_shape(s, b.shape) && s.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX &&
            (a.leave_dropped_rows != 0) == (b.leave_dropped_rows != 0);
 }
 
@@ -366,10 +377,9 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
 // rows for the one-workgroup sampler.
 static bool shares_weight_half(const vcas_layer_args &a, const vcas_layer_args &b)
 {
-    const vcas_shape &s = a.shape, &t = b.shape;
-    return b.sibling != 0 && s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out &&
-           s.dtype == t.dtype && (int64_t)s.N * s.T <= 16384 && !a.xsq_forward && !b.xsq_forward &&
-           (a.token_sampling != 0) == (b.token_sampling != 0);
+    const vcas_shape &s = a.shape;
+    return b.sibling != 0 && same_shape(s, b.shape) && (int64_t)s.N * s.T <= 16384 && !a.xsq_forward &&
+           !b.xsq_forward && (a.token_sampling != 0) == (b.token_sampling != 0);
 }
 
 // What weight_half does before dW, for n sibling layers (shares_weight_half) whose data halves
@@ -406,6 +416,37 @@ static vcas_status weight_half_siblings(const vcas_layer_args *layers, int n, hi
     }
     VCAS_TRY(row_sumsq_scores_uniforms_group(norms, n, s.dtype, R, s.K_in, s.T, st));
     return sampler_w_group(samplers, n, 0, s.N, s.T, token_sampling, 2, st);
+}
+
+// Can layer b share the weight-gradient launch (and the launch of the reductions) of layer a in
+// front of it?  Siblings of one shape that would run with the same tile and slice count on their
+// own: the order of a weight gradient's sums, hence its bits, does not change.
+static bool shares_wgrad(const vcas_layer_args &a, const vcas_layer_args &b)
+{
+    if (!b.sibling || !a.dW || !b.dW || a.shape.dtype != VCAS_BF16 || !same_shape(a.shape, b.shape)) return false;
+    int tile_a, splits_a, tile_b, splits_b;
+    wgrad_choice_bf16(a.shape, expected_tokens(a), tile_a, splits_a);
+    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b);
+    return tile_a == tile_b && splits_a == splits_b;
+}
+
+static vcas_status wgrad_siblings(const vcas_layer_args *layers, int n, hipStream_t st)
+{
+    WgradProblem probs[kMaxSiblings];
+    for (int i = 0; i < n; ++i) {
+        const vcas_layer_args &b = layers[i];
+        probs[i].G = static_cast<const uint16_t *>(b.G);
+        probs[i].X = static_cast<const uint16_t *>(b.X);
+        probs[i].row_scale = b.plan.scaleW;
+        probs[i].idxW = b.plan.idxW;
+        probs[i].cntW = b.plan.cntW;
+        probs[i].dW = b.dW;
+        probs[i].partials = reinterpret_cast<float *>(static_cast<unsigned char *>(b.workspace) +
+                                                      workspace_layout(&b.shape).partials);
+    }
+    int tile, splits;
+    wgrad_choice_bf16(layers[0].shape, expected_tokens(layers[0]), tile, splits);
+    return wgrad_bf16_group(layers[0].shape, probs, n, tile, splits, st);
 }
 
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
@@ -662,50 +703,15 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
             return VCAS_EHIP;
-        auto expected_tokens = [](const vcas_layer_args &a) {
-            const int64_t R = (int64_t)a.shape.N * a.shape.T;
-            return (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5);
-        };
         for (int l = l0; l < l1;) {
             const vcas_layer_args &a = layers[l];
-            if (!a.dW) {
-                ++l;
-                continue;
-            }
-            // sibling layers that would run with the same tile and slices share the launch (and the
-            // launch of their reductions): the order of a weight gradient's sums, hence its bits, stays
-            int n = 1, tile = 0, splits = 0;
-            if (a.shape.dtype == VCAS_BF16) {
-                wgrad_choice_bf16(a.shape, expected_tokens(a), tile, splits);
-                while (l + n < l1 && n < kMaxSiblings) {
-                    const vcas_layer_args &b = layers[l + n];
-                    int tile_b, splits_b;
-                    if (!b.sibling || !b.dW || b.shape.dtype != VCAS_BF16 || b.shape.N != a.shape.N ||
-                        b.shape.T != a.shape.T || b.shape.K_in != a.shape.K_in || b.shape.K_out != a.shape.K_out)
-                        break;
-                    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b);
-                    if (tile_b != tile || splits_b != splits) break;
-                    ++n;
-                }
-            }
-            if (n > 1) {
-                WgradProblem probs[kMaxSiblings];
-                for (int i = 0; i < n; ++i) {
-                    const vcas_layer_args &b = layers[l + i];
-                    probs[i].G = static_cast<const uint16_t *>(b.G);
-                    probs[i].X = static_cast<const uint16_t *>(b.X);
-                    probs[i].row_scale = b.plan.scaleW;
-                    probs[i].idxW = b.plan.idxW;
-                    probs[i].cntW = b.plan.cntW;
-                    probs[i].dW = b.dW;
-                    probs[i].partials = reinterpret_cast<float *>(static_cast<unsigned char *>(b.workspace) +
-                                                                  workspace_layout(&b.shape).partials);
-                }
-                VCAS_TRY(wgrad_bf16_group(a.shape, probs, n, tile, splits, s3));
-            } else {
+            int n = 1;
+            while (a.dW && l + n < l1 && n < kMaxSiblings && shares_wgrad(a, layers[l + n])) ++n;
+            if (n > 1)
+                VCAS_TRY(wgrad_siblings(layers + l, n, s3));
+            else if (a.dW)
                 VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
                                         expected_tokens(a), s3));
-            }
             l += n;
         }
     }
