@@ -125,22 +125,26 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
     const int a_row = tid >> 2, a_kq = tid & 3;
     const float *a_ptr = row_of[a_row] >= 0 ? G + (int64_t)row_of[a_row] * K_out : nullptr;
     const int b_k = tid >> 4, b_col = n0 + (tid & 15) * 4;
-    float4 ra, rb;
-    auto load = [&](int k0) {
-        ra = make_float4(0.f, 0.f, 0.f, 0.f);
-        rb = make_float4(0.f, 0.f, 0.f, 0.f);
+    // A step's MFMAs take a fifth of a microsecond and a workgroup often has its CU to itself, so the
+    // global loads run DEPTH steps ahead of the step on the matrix cores, each step in a register set
+    // of its own: set d holds step s = d (mod DEPTH) until the step before s has put it into LDS.
+    constexpr int DEPTH = 4;
+    float4 ra[DEPTH], rb[DEPTH];
+    auto load = [&](int k0, float4 &qa, float4 &qb) {   // a step past the end loads zeros
+        qa = make_float4(0.f, 0.f, 0.f, 0.f);
+        qb = make_float4(0.f, 0.f, 0.f, 0.f);
         const int ka = k0 + a_kq * 4;
-        if (a_ptr != nullptr && ka < K_out) ra = *reinterpret_cast<const float4 *>(a_ptr + ka);
+        if (a_ptr != nullptr && ka < K_out) qa = *reinterpret_cast<const float4 *>(a_ptr + ka);
         const int kb = k0 + b_k;
-        if (kb < K_out && b_col < K_in) rb = *reinterpret_cast<const float4 *>(W + (int64_t)kb * K_in + b_col);
+        if (kb < K_out && b_col < K_in) qb = *reinterpret_cast<const float4 *>(W + (int64_t)kb * K_in + b_col);
     };
-    auto store = [&](int buf) {
+    auto store = [&](int buf, const float4 &qa, const float4 &qb) {
         float *a = As[buf] + (a_kq * 4) * PITCH + a_row;
-        a[0] = ra.x;
-        a[PITCH] = ra.y;
-        a[2 * PITCH] = ra.z;
-        a[3 * PITCH] = ra.w;
-        *reinterpret_cast<float4 *>(Bs[buf] + b_k * PITCH + (tid & 15) * 4) = rb;
+        a[0] = qa.x;
+        a[PITCH] = qa.y;
+        a[2 * PITCH] = qa.z;
+        a[3 * PITCH] = qa.w;
+        *reinterpret_cast<float4 *>(Bs[buf] + b_k * PITCH + (tid & 15) * 4) = qb;
     };
 
     const int wave = tid >> 6;
@@ -150,15 +154,22 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     const int steps = (K_out + BKF - 1) / BKF;
-    load(0);
-    store(0);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load(d * BKF, ra[d], rb[d]);
+    store(0, ra[0], rb[0]);
     __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int cur = s & 1;
-        if (s + 1 < steps) load((s + 1) * BKF);
-        mma_step(As[cur], Bs[cur], wm0, wn0, acc);
-        if (s + 1 < steps) store(cur ^ 1);
-        __syncthreads();
+    for (int s0 = 0; s0 < steps; s0 += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int s = s0 + d;
+            if (s < steps) {   // the same for every thread
+                const int cur = s & 1;
+                load((s + DEPTH) * BKF, ra[d], rb[d]);   // set d (step s) went to LDS one step ago
+                mma_step(As[cur], Bs[cur], wm0, wn0, acc);
+                if (s + 1 < steps) store(cur ^ 1, ra[(d + 1) % DEPTH], rb[(d + 1) % DEPTH]);
+                __syncthreads();
+            }
+        }
     }
 
     const int col = n0 + wn0 + (tid & 31);
@@ -203,31 +214,25 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict_
 
     // both tiles: 16 tokens x 64 cols, thread = (token tid/16, col-quad tid%16)
     const int kk = tid >> 4, cq = (tid & 15) * 4;
-    int32_t tok, ntok;
-    float sc, nsc;
-    auto fetch = [&](int step, int32_t &t, float &s) {
-        const int64_t k = (int64_t)step * BKF + kk;
-        t = -1;
-        s = 0.0f;
-        if (step < s_end && k < cnt) {
-            const int32_t r = idxW[k];
-            if (r >= 0 && r < R) {
-                t = r;
-                s = row_scale[r];
-            }
-        }
+    // Token indices and scales of CHUNK steps at a time go to LDS first (two dependent loads that
+    // nothing else could hide); inside a chunk the row loads run DEPTH steps ahead of the MFMAs,
+    // each step in a register set of its own, as in dgrad.
+    constexpr int DEPTH = 4, CHUNK = 64;
+    __shared__ int32_t tok_of[CHUNK * BKF];
+    __shared__ float scale_of[CHUNK * BKF];
+    float4 ra[DEPTH], rb[DEPTH];
+    auto load = [&](int local_step, int local_steps, float4 &qa, float4 &qb) {   // past the chunk: zeros
+        qa = make_float4(0.f, 0.f, 0.f, 0.f);
+        qb = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int32_t t = local_step < local_steps ? tok_of[local_step * BKF + kk] : -1;
+        if (t >= 0 && o0 + cq < K_out) qa = *reinterpret_cast<const float4 *>(G + (int64_t)t * K_out + o0 + cq);
+        if (t >= 0 && c0 + cq < K_in) qb = *reinterpret_cast<const float4 *>(X + (int64_t)t * K_in + c0 + cq);
     };
-    float4 ra, rb;
-    auto load = [&]() {
-        ra = make_float4(0.f, 0.f, 0.f, 0.f);
-        rb = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (tok >= 0 && o0 + cq < K_out) ra = *reinterpret_cast<const float4 *>(G + (int64_t)tok * K_out + o0 + cq);
-        if (tok >= 0 && c0 + cq < K_in) rb = *reinterpret_cast<const float4 *>(X + (int64_t)tok * K_in + c0 + cq);
-    };
-    auto store = [&](int buf) {
-        const float4 a = make_float4(ra.x * sc, ra.y * sc, ra.z * sc, ra.w * sc);
+    auto store = [&](int buf, int local_step, const float4 &qa, const float4 &qb) {
+        const float sc = scale_of[local_step * BKF + kk];
+        const float4 a = make_float4(qa.x * sc, qa.y * sc, qa.z * sc, qa.w * sc);
         *reinterpret_cast<float4 *>(As[buf] + kk * PITCH + cq) = a;
-        *reinterpret_cast<float4 *>(Bs[buf] + kk * PITCH + cq) = rb;
+        *reinterpret_cast<float4 *>(Bs[buf] + kk * PITCH + cq) = qb;
     };
 
     const int wave = tid >> 6;
@@ -236,24 +241,40 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(const float *__restrict_
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-    if (s_begin < s_end) {
-        fetch(s_begin, tok, sc);
-        load();
-        fetch(s_begin + 1, ntok, nsc);
-        store(0);
-        __syncthreads();
-        for (int s = s_begin; s < s_end; ++s) {
-            const int cur = (s - s_begin) & 1;
-            const bool more = s + 1 < s_end;
-            if (more) {
-                tok = ntok;
-                sc = nsc;
-                load();
-                fetch(s + 2, ntok, nsc);
+    for (int chunk0 = s_begin; chunk0 < s_end; chunk0 += CHUNK) {
+        const int local_steps = min(CHUNK, s_end - chunk0);
+        __syncthreads();   // the previous chunk's table and tiles are no longer read
+        for (int i = tid; i < local_steps * BKF; i += NT) {
+            const int64_t k = (int64_t)chunk0 * BKF + i;
+            int32_t t = -1;
+            float sc = 0.0f;
+            if (k < cnt) {
+                const int32_t r = idxW[k];
+                if (r >= 0 && r < R) {
+                    t = r;
+                    sc = row_scale[r];
+                }
             }
-            mma_step(As[cur], Bs[cur], wm0, wn0, acc);
-            if (more) store(cur ^ 1);
-            __syncthreads();
+            tok_of[i] = t;
+            scale_of[i] = sc;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) load(d, local_steps, ra[d], rb[d]);
+        store(0, 0, ra[0], rb[0]);
+        __syncthreads();
+        for (int s0 = 0; s0 < local_steps; s0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int s = s0 + d;
+                if (s < local_steps) {   // the same for every thread
+                    const int cur = s & 1;
+                    load(s + DEPTH, local_steps, ra[d], rb[d]);
+                    mma_step(As[cur], Bs[cur], wm0, wn0, acc);
+                    if (s + 1 < local_steps) store(cur ^ 1, s + 1, ra[(d + 1) % DEPTH], rb[(d + 1) % DEPTH]);
+                    __syncthreads();
+                }
+            }
         }
     }
 
