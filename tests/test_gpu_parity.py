@@ -344,6 +344,36 @@ def test_sample_a_only_backward(vb):
     assert rel_l2(dX, want_dX) <= 1e-2 and rel_l2(dW, want_dW) <= 1e-2
 
 
+def test_sample_a_only_siblings_in_a_stack(vb):
+    """The SampleA-only backward (Alg. 1: no token sampling) through the shared launches of sibling layers,
+    and a run of siblings in which the kind of sampling changes (which ends the shared SampleW launch)."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    kinds = [False, False, False, True]
+    entries, outs, host, keep = [], [], [], []
+    for k, ts in enumerate(kinds):
+        sp = workloads.LayerSpec(f"ao{k}", BF16, 9, 40, 136, 200, 0.4 + 0.1 * k, 0.5, layer=k, seed=22, gen_seed=60 + k,
+                                 token_sigma=0.5)
+        G, X, W = workloads.make_layer(sp)
+        shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+        g, x, w = (to_device(a, BF16) for a in (G, X, W))
+        plan, ws = vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape)
+        dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), ts, plan, dX, dW, ws, None,
+                                     k > 0))
+        outs.append((sp, ts, plan, dX, dW))
+        host.append((G, X, W))
+        keep.append((g, x, w, ws))
+    s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+    vb.vcas_backward_stack(vb.make_stack(entries), 4, s2, s3)
+    torch.cuda.synchronize()
+    for (sp, ts, plan, dX, dW), (G, X, W) in zip(outs, host):
+        want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 1,
+                                                        token_sampling=ts)
+        compare_plan(plan_to_numpy(plan), want)
+        assert rel_l2(from_device(dX), want_dX) <= 1e-2 and rel_l2(from_device(dW), want_dW) <= 1e-2
+
+
 def test_results_are_reproducible(vb):
     from tests.gpu_util import run_layer_gpu
     spec = workloads.LayerSpec("repro", BF16, 8, 128, 768, 768, 0.5, 0.5, layer=2, seed=5, gen_seed=6, token_sigma=0.5)
