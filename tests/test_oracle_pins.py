@@ -471,3 +471,30 @@ def test_jacobian_product_is_the_chain_rule_by_finite_differences():
     plain = oracle.dgrad(G, W, oracle.F32, N, T, p, mask)
     assert np.array_equal(oracle.dgrad_jacobian(G, W, ones, oracle.F32, N, T, p, mask), plain)
     assert np.all(oracle.dgrad_jacobian(G, W, J, oracle.F32, N, T, p, mask)[T:] == 0)
+
+
+def test_squared_difference_and_exact_weight_gradient_against_numpy():
+    """The two helpers the Monte-Carlo lines of Alg. 1 lean on: ||a - b||_F^2 (exact on small integers, where
+    every partial sum is representable, and numpy's fp64 value elsewhere) and the exact weight gradient
+    G^T X, the keep-ratio-one state the sampled gradients are compared with (numpy fp64 matmul on the same
+    values; a transposed operand or a dropped row shows)."""
+    rng = np.random.default_rng(5)
+    a = rng.integers(-8, 9, size=(37, 53)).astype(np.float32)
+    b = rng.integers(-8, 9, size=(37, 53)).astype(np.float32)
+    assert oracle.sq_diff(a, b) == float(((a.astype(np.int64) - b.astype(np.int64)) ** 2).sum())
+    assert oracle.sq_diff(a, a) == 0.0
+    x = rng.standard_normal((64, 40)).astype(np.float32)
+    y = rng.standard_normal((64, 40)).astype(np.float32)
+    want = float(((x.astype(np.float64) - y.astype(np.float64)) ** 2).sum())
+    assert oracle.sq_diff(x, y) == pytest.approx(want, rel=1e-12)
+    assert oracle.sq_diff(x, y) == oracle.sq_diff(y, x)
+    for dtype in (F32, BF16):
+        R, K_out, K_in = 45, 24, 40                          # nothing square: a transposition changes the shape
+        G32 = rng.standard_normal((R, K_out)).astype(np.float32)
+        X32 = rng.standard_normal((R, K_in)).astype(np.float32)
+        G = workloads.f32_to_bf16_bits(G32) if dtype == BF16 else G32
+        X = workloads.f32_to_bf16_bits(X32) if dtype == BF16 else X32
+        Gv, Xv = oracle.to_f64(G, dtype), oracle.to_f64(X, dtype)
+        got = oracle.exact_wgrad(G, X, dtype)
+        assert got.shape == (K_out, K_in)
+        np.testing.assert_allclose(got, Gv.T @ Xv, rtol=1e-12, atol=1e-12)
