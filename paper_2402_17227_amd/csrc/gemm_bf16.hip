@@ -211,6 +211,17 @@ __device__ __forceinline__ int xcd_remap(int id, int total)
     return (id & 7) * per + (id >> 3);
 }
 
+// The same with the panel width chosen at run time.
+__device__ __forceinline__ void panel_order_rt(int tile, int tiles_m, int tiles_n, int panel_w, int &tile_m,
+                                               int &tile_n)
+{
+    const int panel = tile / (tiles_m * panel_w);
+    const int in_panel = tile - panel * tiles_m * panel_w;
+    const int width = min(panel_w, tiles_n - panel * panel_w);
+    tile_m = in_panel / width;
+    tile_n = panel * panel_w + in_panel % width;
+}
+
 // Tile number -> (row tile, column tile), column panels of PANEL tiles, row-major inside a panel.
 template <int PANEL>
 __device__ __forceinline__ void panel_order(int tile, int tiles_m, int tiles_n, int &tile_m, int &tile_n)
@@ -436,7 +447,13 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
     const int tile = xcd_remap(blockIdx.x, compute);
     if (tile >= compute) return;
     int tile_m, tile_n;
-    panel_order<8>(tile, compute / tiles_n, tiles_n, tile_m, tile_n);
+    // An XCD gets a contiguous run of tile ids and has an L2 of its own: a run that spans all
+    // column tiles reads its rows of G once and W whole (W eight times in all); with the
+    // columns in `a` panels an XCD reads 1/a of W and every row of G is read by `a` XCDs.
+    // a*|G kept| + (8/a)*|W|, i.e. a*M + (8/a)*K_in, is least at a = 1, 2, 4 for M >= 4 K_in, >= K_in, below.
+    const int a_panels = M >= 4 * (int64_t)K_in ? 1 : M >= K_in ? 2 : 4;
+    const int panel = min(8, max(1, (tiles_n + a_panels - 1) / a_panels));
+    panel_order_rt(tile, compute / tiles_n, tiles_n, panel, tile_m, tile_n);
     const int n0 = tile_n * BN;
     const int64_t m0 = (int64_t)tile_m * BM;
     __syncthreads();   // idx_staged complete
