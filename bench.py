@@ -253,6 +253,9 @@ def main():
     ap.add_argument("--no-siblings", action="store_true",
                     help="stack launch: do not mark the K and Q projections as siblings of V (every data half then "
                          "waits for the one before it)")
+    ap.add_argument("--wgrad-fill", type=int, default=128, metavar="WORKGROUPS",
+                    help="stack launch: workgroups a weight-gradient launch should have before it stops cutting the "
+                         "contraction into split-K slices (vcas_layer_args.wgrad_fill; 0 or 384 = what a stand-alone call uses)")
     ap.add_argument("--chained", action="store_true",
                     help="stack launch: the layers feed each other as in a real backward pass (down's dX buffer is up's G, "
                          "up's is o's, o's is the G of V, K and Q, Q's is the next block's down's), every layer is told "
@@ -335,7 +338,8 @@ def main():
             entries.append(vb.layer_args(l.shape, G, l.X, l.W, l.spec.rho, l.spec.nu,
                                          vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
                                          l.plan, l.dX, l.dW, l.ws, l.xsq_forward, sibling=sib,
-                                         kept_above=above, leave_dropped_rows=args.chained))
+                                         kept_above=above, leave_dropped_rows=args.chained,
+                                         wgrad_fill=args.wgrad_fill))
             prev, prev_G, prev_above = l, G, above
         stack = vb.make_stack(entries)
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
@@ -465,6 +469,7 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
                    + ("" if args.no_siblings else ", data halves of V, K, Q of a block in shared launches")
+                   + f", weight gradients sliced for {args.wgrad_fill or 384} workgroups"
                    + (", layers chained (each dX buffer is the next G, dropped samples stay dropped and unwritten)"
                       if args.chained else "")
                    + (", row norms of X cached before the timed region" if args.xsq_cached else "")

@@ -48,7 +48,8 @@ class LayerArgs(C.Structure):
     _fields_ = [("shape", Shape), ("G", C.c_void_p), ("X", C.c_void_p), ("W", C.c_void_p), ("rho", C.c_double),
                 ("nu", C.c_double), ("rng", Rng), ("token_sampling", C.c_int32), ("plan", PlanPtrs),
                 ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p), ("xsq_forward", C.c_void_p), ("sibling", C.c_int32),
-                ("J", C.c_void_p), ("kept_above", C.c_void_p), ("leave_dropped_rows", C.c_int32)]
+                ("J", C.c_void_p), ("kept_above", C.c_void_p), ("leave_dropped_rows", C.c_int32),
+                ("wgrad_fill", C.c_int32)]
 
 
 _lib = None
@@ -200,7 +201,7 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
 
 def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dX, dW,
                workspace, xsq_forward=None, sibling=False, J=None, kept_above=None,
-               leave_dropped_rows=False) -> LayerArgs:
+               leave_dropped_rows=False, wgrad_fill=0) -> LayerArgs:
     """One entry of the array vcas_backward_stack takes (the tensors must stay alive while it is used)."""
     a = LayerArgs()
     a.shape = shape
@@ -214,6 +215,7 @@ def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sam
     a.sibling = 1 if sibling else 0
     a.J, a.kept_above = _ptr(J), _ptr(kept_above)
     a.leave_dropped_rows = 1 if leave_dropped_rows else 0
+    a.wgrad_fill = wgrad_fill
     return a
 
 

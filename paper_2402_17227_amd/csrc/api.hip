@@ -70,12 +70,15 @@ vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const f
 // Split-K slices of the weight gradient: about one and a half workgroups per CU (a second one
 // hides the first one's waits; more splits cost reduction traffic), at most 8, and never so many
 // that a slice at full length R would have fewer than 2 (bf16) or 8 (fp32) contraction steps.
-static int wgrad_split_for(const vcas_shape *s, int tiles)
+constexpr int kWgradFill = 384;   // workgroups a weight-gradient launch wants when it has the chip to itself
+
+static int wgrad_split_for(const vcas_shape *s, int tiles, int fill = kWgradFill)
 {
     const bool bf = s->dtype == VCAS_BF16;
     const int64_t R = (int64_t)s->N * s->T;
     const int64_t steps = (R + (bf ? 63 : 15)) / (bf ? 64 : 16);
-    int64_t want = (384 + tiles - 1) / tiles;
+    if (fill <= 0 || fill > kWgradFill) fill = kWgradFill;   // the workspace is sized for kWgradFill
+    int64_t want = (fill + tiles - 1) / tiles;
     int64_t cap = steps / (bf ? 2 : 8);
     if (want > cap) want = cap;
     if (want > 8) want = 8;
@@ -162,24 +165,26 @@ static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void
 // expected_tokens: how many tokens the caller expects SampleW to keep (R if unknown); it only
 // steers the tile choice.
 // Tile edge and split-K slices dispatch_wgrad picks for a bf16 layer.
-static void wgrad_choice_bf16(const vcas_shape &s, int64_t expected_tokens, int &tile, int &splits)
+static void wgrad_choice_bf16(const vcas_shape &s, int64_t expected_tokens, int &tile, int &splits,
+                              int fill = kWgradFill)
 {
     const int64_t R = (int64_t)s.N * s.T;
     tile = wgrad_tile_bf16(s.K_out, s.K_in, expected_tokens > 0 && expected_tokens < R ? expected_tokens : R);
-    splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile));
+    splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile), fill);
 }
 
 static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
                                   const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
-                                  int64_t expected_tokens, hipStream_t st)
+                                  int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
 {
     const WorkspaceLayout w = workspace_layout(&s);
     unsigned char *base = static_cast<unsigned char *>(workspace);
     float *partials = reinterpret_cast<float *>(base + w.partials);
     if (s.dtype != VCAS_BF16)
-        return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split(&s), st);
+        return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split_for(&s, wgrad_tiles_f32(s.K_out, s.K_in), fill),
+                         st);
     int tile, splits;
-    wgrad_choice_bf16(s, expected_tokens, tile, splits);
+    wgrad_choice_bf16(s, expected_tokens, tile, splits, fill);
     return wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, tile, splits, st);
 }
 
@@ -425,8 +430,8 @@ static bool shares_wgrad(const vcas_layer_args &a, const vcas_layer_args &b)
 {
     if (!b.sibling || !a.dW || !b.dW || a.shape.dtype != VCAS_BF16 || !same_shape(a.shape, b.shape)) return false;
     int tile_a, splits_a, tile_b, splits_b;
-    wgrad_choice_bf16(a.shape, expected_tokens(a), tile_a, splits_a);
-    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b);
+    wgrad_choice_bf16(a.shape, expected_tokens(a), tile_a, splits_a, a.wgrad_fill);
+    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b, b.wgrad_fill);
     return tile_a == tile_b && splits_a == splits_b;
 }
 
@@ -445,7 +450,7 @@ static vcas_status wgrad_siblings(const vcas_layer_args *layers, int n, hipStrea
                                                       workspace_layout(&b.shape).partials);
     }
     int tile, splits;
-    wgrad_choice_bf16(layers[0].shape, expected_tokens(layers[0]), tile, splits);
+    wgrad_choice_bf16(layers[0].shape, expected_tokens(layers[0]), tile, splits, layers[0].wgrad_fill);
     return wgrad_bf16_group(layers[0].shape, probs, n, tile, splits, st);
 }
 
@@ -636,6 +641,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (a.dX && !a.W) return VCAS_ENULL;
         if (!a.workspace) return VCAS_EWORKSPACE;
         if (!ratio_ok(a.rho) || !ratio_ok(a.nu) || (a.xsq_forward && a.xsq_forward == a.plan.xsq)) return VCAS_EINVAL;
+        if (a.wgrad_fill < 0) return VCAS_EINVAL;
         if (a.J && !a.dX) return VCAS_ENULL;
         if (a.J && !aligned16(a.J)) return VCAS_EINVAL;
         if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
@@ -711,7 +717,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
                 VCAS_TRY(wgrad_siblings(layers + l, n, s3));
             else if (a.dW)
                 VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
-                                        expected_tokens(a), s3));
+                                        expected_tokens(a), s3, a.wgrad_fill));
             l += n;
         }
     }

@@ -1,5 +1,6 @@
 """Parity at the full sizes of the benchmark configurations, launched the way bench.py launches:
-vcas_backward_stack from the host, SampleW and dW on two side streams, draw index read from device
+vcas_backward_stack from the host, SampleW and dW on two side streams, weight gradients sliced for 128
+workgroups, draw index read from device
 memory (and, for one layer of each model, the graph-replay launch bench.py offers as --graph).
 The sampling plan is compared bit for bit with the oracle's; dX and dW are compared on entries
 drawn at random (the oracle computes them one by one), and on properties that hold everywhere
@@ -76,7 +77,8 @@ def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
         graph.replay()                           # draw 2
         graph.replay()                           # draw 3
     else:
-        stack = vb.make_stack([vb.layer_args(shape, g, x, w, spec.rho, spec.nu, rng, True, plan, dX, dW, ws)])
+        stack = vb.make_stack([vb.layer_args(shape, g, x, w, spec.rho, spec.nu, rng, True, plan, dX, dW, ws,
+                                             wgrad_fill=128)])
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
         for draw in (1, 2, 3):
             main = torch.cuda.current_stream()
@@ -148,7 +150,7 @@ def test_full_size_sibling_layers_in_shared_launches(vb, workload):
         dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
                                      vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws, None,
-                                     k > 0))
+                                     k > 0, wgrad_fill=128))
         host.append((G, X, W))
         outs.append((plan, dX, dW))
         keep.append((g, x, w, ws))
@@ -193,7 +195,7 @@ def test_full_size_block_in_the_chained_launch(vb):
         dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=torch.bfloat16, device="cuda")
         dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws,
-                                     None, name in "kq", None, None if name == "o" else above, True))
+                                     None, name in "kq", None, None if name == "o" else above, True, 128))
         outs.append((sp, plan, dX, dW))
         keep.append((g, x, w, ws))
         host.append((G if name == "o" else G2, Xs, Ws))

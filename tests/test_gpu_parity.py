@@ -840,6 +840,51 @@ def test_sibling_layers_inside_a_sparse_chain(vb):
         assert torch.isfinite(dW).all()
 
 
+@pytest.mark.parametrize("fill", [1, 128, 384, 100000])
+def test_weight_gradient_slices_are_a_choice_of_the_caller(vb, fill):
+    """vcas_layer_args.wgrad_fill sets how far the contraction of a weight gradient is cut into split-K slices.
+    Whatever it is, the plan is the oracle's bit for bit and dW within tolerance; 384 and anything above are the
+    stand-alone call's choice, hence its bits; the same value twice gives the same bits."""
+    from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2
+    specs = [workloads.LayerSpec("wf0", BF16, 16, 128, 264, 136, 0.8, 0.7, layer=0, seed=14, gen_seed=71, token_sigma=0.5),
+             workloads.LayerSpec("wf1", BF16, 16, 128, 264, 136, 0.6, 0.9, layer=1, seed=14, gen_seed=72, token_sigma=0.5),
+             workloads.LayerSpec("wf2", F32, 8, 128, 136, 72, 0.7, 0.8, layer=2, seed=14, gen_seed=73, token_sigma=0.5)]
+    runs = []
+    for rep in range(2):
+        entries, outs, keep, host = [], [], [], []
+        for k, sp in enumerate(specs):
+            G, X, W = workloads.make_layer(sp)
+            shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+            g, x, w = (to_device(a, sp.dtype) for a in (G, X, W))
+            plan, ws = vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape)
+            dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=g.dtype, device="cuda")
+            dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
+            entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 3), True, plan, dX, dW, ws,
+                                         None, k == 1, wgrad_fill=fill))
+            outs.append((plan, dX, dW))
+            keep.append((g, x, w, ws))
+            host.append((G, X, W))
+        s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
+        vb.vcas_backward_stack(vb.make_stack(entries), 3, s2, s3)
+        torch.cuda.synchronize()
+        runs.append(outs)
+    for k, sp in enumerate(specs):
+        G, X, W = host[k]
+        want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 3)
+        plan, dX, dW = runs[0][k]
+        compare_plan(plan_to_numpy(plan), want)
+        assert rel_l2(from_device(dX), want_dX) <= TOL[sp.dtype] and rel_l2(from_device(dW), want_dW) <= TOL[sp.dtype]
+        assert torch.equal(dW.view(torch.int32), runs[1][k][2].view(torch.int32))
+        if fill >= 384:
+            shape = vb.shape_of(sp.N, sp.T, sp.K_in, sp.K_out, sp.dtype)
+            g, x, w = (to_device(a, sp.dtype) for a in (G, X, W))
+            plan_r, ws_r = vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape)
+            dW_r = torch.full_like(dW, float("nan"))
+            vb.vcas_linear_backward(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 3), True, plan_r, None, dW_r, ws_r)
+            torch.cuda.synchronize()
+            assert torch.equal(dW.view(torch.int32), dW_r.view(torch.int32))
+
+
 @pytest.mark.parametrize("streams", [1, 3])
 def test_cached_row_norms_of_x_give_the_same_bits(vb, streams):
     """The squared row norms of X can be taken once, when X is produced (vcas_row_norms over every row), and

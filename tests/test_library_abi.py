@@ -92,6 +92,9 @@ def test_bad_arguments_are_rejected_on_the_host(vb):
     assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 2
     arr[1].J, arr[1].dX = 0x1008, 0x1000                                         # and the usual alignment
     assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
+    arr[1].J = 0
+    arr[1].wgrad_fill = -1
+    assert stack_fn(arr, C.c_int32(2), C.c_int32(1), null, null, null) == 1
     cached = lib.vcas_backward_weight_cached
     assert cached(C.byref(good), fake, fake, null, C.c_double(0.5), C.c_double(0.5), C.byref(rng), C.c_int32(1),
                   C.byref(plan), fake, fake, null) == 2                          # no cache given
