@@ -149,8 +149,8 @@ def test_full_size_sibling_layers_in_shared_launches(vb, workload):
         dX = torch.full((spec.R, spec.K_in), float("nan"), dtype=g.dtype, device="cuda")
         dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
-                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws, None,
-                                     k > 0, wgrad_fill=128))
+                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws,
+                                     sibling=k > 0, wgrad_fill=128))
         host.append((G, X, W))
         outs.append((plan, dX, dW))
         keep.append((g, x, w, ws))
@@ -195,7 +195,8 @@ def test_full_size_block_in_the_chained_launch(vb):
         dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=torch.bfloat16, device="cuda")
         dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws,
-                                     None, name in "kq", None, None if name == "o" else above, True, 128))
+                                     sibling=name in "kq", kept_above=None if name == "o" else above,
+                                     leave_dropped_rows=True, wgrad_fill=128))
         outs.append((sp, plan, dX, dW))
         keep.append((g, x, w, ws))
         host.append((G if name == "o" else G2, Xs, Ws))

@@ -147,8 +147,8 @@ def test_stack_launch_captured_in_a_graph_matches_eager():
         dW = torch.empty((spec.K_out, spec.K_in), device="cuda")
         layers.append((plan, dX, dW, g, x, w, ws))
         entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
-                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws, None,
-                                     flag))
+                                     vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws,
+                                     sibling=flag))
     stack = vb.make_stack(entries)
     s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 

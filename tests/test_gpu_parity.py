@@ -359,8 +359,8 @@ def test_sample_a_only_siblings_in_a_stack(vb):
         plan, ws = vb.Plan.allocate(sp.N, sp.T), vb.make_workspace(shape)
         dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=torch.bfloat16, device="cuda")
         dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
-        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), ts, plan, dX, dW, ws, None,
-                                     k > 0))
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), ts, plan, dX, dW, ws,
+                                     sibling=k > 0))
         outs.append((sp, ts, plan, dX, dW))
         host.append((G, X, W))
         keep.append((g, x, w, ws))
@@ -655,8 +655,8 @@ def test_chained_layers_without_zero_fill(vb, dtype, K_in):
         ws = vb.make_workspace(shape)
         dX = torch.full_like(dX_ref, float("nan"))
         dW = torch.full_like(dW_ref, float("nan"))
-        entries.append(vb.layer_args(shape, g, x, w, layers[l][3], nu, r, True, plan, dX, dW, ws, None, False, jac, above,
-                                     True))
+        entries.append(vb.layer_args(shape, g, x, w, layers[l][3], nu, r, True, plan, dX, dW, ws, J=jac, kept_above=above,
+                                     leave_dropped_rows=True))
         outs.append((plan, dX, dW))
         keep.append((g, ws))
         g, above = dX, plan.maskA
@@ -769,7 +769,7 @@ def test_sibling_layers_share_launches_and_keep_their_bits(vb, group):
         vb.vcas_linear_backward(shape, g, x, w, sp.rho, sp.nu, rng, True, plan_r, dX_r, dW_r, ws_r)
         refs.append((plan_to_numpy(plan_r), dX_r, dW_r))
         plan, ws, dX, dW = fresh()
-        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, None, flag))
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, sibling=flag))
         outs.append((plan, dX, dW))
         keep.append((g, x, w, ws, ws_r))
         host.append((G, X, W))
@@ -823,8 +823,8 @@ def test_sibling_layers_inside_a_sparse_chain(vb):
         vb.vcas_backward_weight(shape, g, x, sp.rho, sp.nu, r, True, plan_r, dW_r, ws_r)
         refs.append((plan_r, dX_r, dW_r))
         plan, ws, dX, dW = fresh()
-        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, r, True, plan, dX, dW, ws, None, k > 0, jac, above,
-                                     True))
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, r, True, plan, dX, dW, ws, sibling=k > 0, J=jac,
+                                     kept_above=above, leave_dropped_rows=True))
         outs.append((plan, dX, dW))
         keep.append((g, x, w, jac, ws, ws_r))
     s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
@@ -860,7 +860,7 @@ def test_weight_gradient_slices_are_a_choice_of_the_caller(vb, fill):
             dX = torch.full((sp.R, sp.K_in), float("nan"), dtype=g.dtype, device="cuda")
             dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
             entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 3), True, plan, dX, dW, ws,
-                                         None, k == 1, wgrad_fill=fill))
+                                         sibling=k == 1, wgrad_fill=fill))
             outs.append((plan, dX, dW))
             keep.append((g, x, w, ws))
             host.append((G, X, W))
@@ -915,7 +915,7 @@ def test_cached_row_norms_of_x_give_the_same_bits(vb, streams):
         vb.vcas_row_norms(shape, None, x, None, None, xsq_fwd, None)
         xsq_copy = xsq_fwd.clone()
         plan, ws, dX, dW = fresh()
-        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, xsq_fwd))
+        entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, rng, True, plan, dX, dW, ws, xsq_forward=xsq_fwd))
         outs.append((plan, dX, dW))
         # stand-alone: data call, then the weight call with the cache
         plan_a, ws_a, dX_a, dW_a = fresh()
