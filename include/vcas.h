@@ -209,7 +209,8 @@ vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const v
                                  const vcas_plan *plan, void *dX, float *dW, void *workspace,
                                  void *stream, void *side_stream);
 
-/* One layer of a stack: the arguments of vcas_linear_backward (host struct). */
+/* One layer of a stack: the arguments of vcas_linear_backward (host struct), then optional
+ * fields, every one of which is off when zero: a zero-initialised tail gives the plain layer. */
 typedef struct {
     vcas_shape shape;
     const void *G, *X, *W;
@@ -242,7 +243,8 @@ typedef struct {
 
 /*
  * A stack of L layers in one call: computes, bit for bit, what calling
- * vcas_linear_backward on layers[0], layers[1], ... computes, with the launches
+ * vcas_linear_backward on layers[0], layers[1], ... computes (dW: where wgrad_fill
+ * is left at zero; see there), with the launches
  * laid out over up to three streams so that a dependency between streams is
  * paid once per group of layers instead of once per layer (on this hardware a
  * cross-stream wait costs about as much as two small kernels):
@@ -260,8 +262,9 @@ typedef struct {
  * layers: HOST array, read during the call only.  group >= 1.  The call joins
  * nothing: results of the weight halves are complete when the streams they ran
  * on have drained, and work that reuses any of the layers' buffers (the next
- * call on the same stack included) must be ordered after all three streams.  All streams at default priority.  Meant for eager launching;
- * under graph capture it is correct but gains nothing over per-layer calls.
+ * call on the same stack included) must be ordered after all three streams.
+ * All streams at default priority.  Meant for eager launching; under graph
+ * capture it is correct but gains nothing over per-layer calls.
  * Every layer's arguments are checked before anything is launched.  The events
  * that order the streams belong to the library and are shared by all calls:
  * call it from one host thread at a time.
