@@ -1142,11 +1142,12 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_group_kernel(Wg
 // the chip takes many split-K slices, whose fp32 partial tiles then cost more HBM traffic than
 // the operands (BERT-base: 3 to 8 slices, partials 2 to 4 times dW), and few enough tokens are
 // expected that the matrix cores are not the limit: then 64x64 tiles, four times as many, with a
-// quarter of the slices (1000 kept tokens, 768x3072: 24 vs 28 us and no partials at all).
+// quarter of the slices (1000 kept tokens, 768x3072: 24 vs 28 us and no partials at all).  Up to
+// 1024 expected tokens: at 1900 (ViT-B/16) the 128x128 kernel is ahead again (step 3.67 -> 3.53 ms).
 int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens)
 {
     const int tiles128 = ((K_out + 127) / 128) * ((K_in + 127) / 128);
-    return tiles128 <= 160 && expected_tokens <= 2048 ? 64 : 128;
+    return tiles128 <= 160 && expected_tokens <= 1024 ? 64 : 128;
 }
 
 int wgrad_tiles_bf16(int K_out, int K_in, int tile) { return ((K_out + tile - 1) / tile) * ((K_in + tile - 1) / tile); }
