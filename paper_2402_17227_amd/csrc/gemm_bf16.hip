@@ -1217,7 +1217,7 @@ vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = n * ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = n * ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 192) return launch_dgrad_group<256, 256, 2, 4, 2, 1, 2>(s, grp, n, fill, st);
+    if (tiles256 >= 128) return launch_dgrad_group<256, 256, 2, 4, 2, 1, 2>(s, grp, n, fill, st);
     if (tiles128 > 256) return launch_dgrad_group<128, 128, 2, 2, 2, 2, 4>(s, grp, n, fill, st);
     const int64_t tiles64 = n * ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad_group<64, 128, 2, 2, 2, 2, 0>(s, grp, n, fill, st);
@@ -1241,7 +1241,8 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
         sa = *sample_a;
     }
     // The loads into LDS run at about 40 bytes per clock and CU, so the largest tile that still
-    // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 192 tiles up; else 128x128
+    // fills the chip wins: 256x256 (one 8-wave workgroup per CU) from 128 tiles up (half the CUs:
+    // inside a stack other kernels take the rest; 192 made a step 1-3 % longer); else 128x128
     // (two per CU) while more than 256 of them exist; else 64x128, twice as many workgroups with
     // half the serial work each.  Measured, R=16384, 1024->4096: 123 / 137 / 191 us; R=4096,
     // 768->3072: 68 / 37 / 33 us.  When even the 64x128 tiles leave CUs with a single workgroup,
@@ -1251,7 +1252,7 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 192) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+    if (tiles256 >= 128) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
