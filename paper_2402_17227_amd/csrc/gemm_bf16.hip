@@ -1252,7 +1252,10 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 128) return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+    // without an expectation (the kept count is known on the device only) the tiles of ALL rows are counted, and a
+    // kernel picked for them may find half of them empty: the larger tile then needs more of them to pay
+    if (tiles256 >= (expected_rows > 0 ? 128 : 192))
+        return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
