@@ -253,7 +253,7 @@ def main():
     ap.add_argument("--no-siblings", action="store_true",
                     help="stack launch: do not mark the K and Q projections as siblings of V (every data half then "
                          "waits for the one before it)")
-    ap.add_argument("--wgrad-fill", type=int, default=128, metavar="WORKGROUPS",
+    ap.add_argument("--wgrad-fill", type=int, default=64, metavar="WORKGROUPS",
                     help="stack launch: workgroups a weight-gradient launch should have before it stops cutting the "
                          "contraction into split-K slices (vcas_layer_args.wgrad_fill; 0 or 384 = what a stand-alone call uses)")
     ap.add_argument("--chained", action="store_true",

@@ -235,7 +235,7 @@ typedef struct {
     int32_t wgrad_fill; /* 0, or how many workgroups the weight-gradient launch should have before it stops
                            cutting the contraction into split-K slices (1..384; larger values count as 384).
                            0 = 384, what every other entry point uses: right for a launch that has the chip
-                           to itself.  Beside the data chain of a stack fewer, longer slices (128) make the
+                           to itself.  Beside the data chain of a stack fewer, longer slices (64) make the
                            step shorter.  The number of slices fixes the order of a weight gradient's sums:
                            dW is the same bits for the same value of this field, and within rounding
                            (fp32 sums in another order) across values. */

@@ -1,5 +1,5 @@
 """Parity at the full sizes of the benchmark configurations, launched the way bench.py launches:
-vcas_backward_stack from the host, SampleW and dW on two side streams, weight gradients sliced for 128
+vcas_backward_stack from the host, SampleW and dW on two side streams, weight gradients sliced for 64
 workgroups, draw index read from device
 memory (and, for one layer of each model, the graph-replay launch bench.py offers as --graph).
 The sampling plan is compared bit for bit with the oracle's; dX and dW are compared on entries
@@ -78,7 +78,7 @@ def test_full_size_layer_in_the_bench_launch_configuration(vb, spec):
         graph.replay()                           # draw 3
     else:
         stack = vb.make_stack([vb.layer_args(shape, g, x, w, spec.rho, spec.nu, rng, True, plan, dX, dW, ws,
-                                             wgrad_fill=128)])
+                                             wgrad_fill=64)])
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
         for draw in (1, 2, 3):
             main = torch.cuda.current_stream()
@@ -150,7 +150,7 @@ def test_full_size_sibling_layers_in_shared_launches(vb, workload):
         dW = torch.full((spec.K_out, spec.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, spec.rho, spec.nu,
                                      vb.Rng(spec.seed, spec.layer, 0, counter.data_ptr()), True, plan, dX, dW, ws,
-                                     sibling=k > 0, wgrad_fill=128))
+                                     sibling=k > 0, wgrad_fill=64))
         host.append((G, X, W))
         outs.append((plan, dX, dW))
         keep.append((g, x, w, ws))
@@ -196,7 +196,7 @@ def test_full_size_block_in_the_chained_launch(vb):
         dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws,
                                      sibling=name in "kq", kept_above=None if name == "o" else above,
-                                     leave_dropped_rows=True, wgrad_fill=128))
+                                     leave_dropped_rows=True, wgrad_fill=64))
         outs.append((sp, plan, dX, dW))
         keep.append((g, x, w, ws))
         host.append((G if name == "o" else G2, Xs, Ws))
