@@ -670,7 +670,10 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
     }
     // with a stream of its own for the weight halves, the norms of X go there too
     const XNorms xnorms_default = s2 != st ? kXNormsAfterSampleA : kXNormsByShape;
-    for (int g = 0; g < groups; ++g) {
+    // The host issues the data halves of group g + 1 before the side-stream work of group g: the
+    // main stream, which carries the chain every other launch waits for, is then always a group
+    // ahead of the host, whatever the side streams' launches cost it.
+    auto issue_data = [&](int g) -> vcas_status {
         const int l0 = first[g], l1 = first[g + 1];
         for (int l = l0; l < l1;) {
             const vcas_layer_args &a = layers[l];
@@ -690,9 +693,12 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
             }
             l += n;
         }
-        if (s2 != st && (hipEventRecord(events[2 * g], st) != hipSuccess ||
-                         hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess))
-            return VCAS_EHIP;
+        if (s2 != st && hipEventRecord(events[2 * g], st) != hipSuccess) return VCAS_EHIP;
+        return VCAS_OK;
+    };
+    auto issue_side = [&](int g) -> vcas_status {
+        const int l0 = first[g], l1 = first[g + 1];
+        if (s2 != st && hipStreamWaitEvent(s2, events[2 * g], 0) != hipSuccess) return VCAS_EHIP;
         for (int l = l0; l < l1;) {
             const vcas_layer_args &a = layers[l];
             int n = 1;
@@ -720,6 +726,12 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
                                         expected_tokens(a), s3, a.wgrad_fill));
             l += n;
         }
+            return VCAS_OK;
+    };
+    VCAS_TRY(issue_data(0));
+    for (int g = 0; g < groups; ++g) {
+        if (g + 1 < groups) VCAS_TRY(issue_data(g + 1));
+        VCAS_TRY(issue_side(g));
     }
     return VCAS_OK;
 }
