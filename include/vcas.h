@@ -115,8 +115,11 @@ vcas_status vcas_workspace_init(const vcas_shape *shape, void *workspace, void *
  *              sample has mask 0        (required if X is given)
  * fp32, each row summed in a fixed order that does not depend on the launch:
  * 16-byte group j of the row goes to accumulator j mod 64, accumulators fold
- * with fused multiply-add in ascending k and are combined pairwise at
- * distances 32,16,8,4,2,1; gnorm likewise over the T values of a sample.
+ * with fused multiply-add in ascending k and are then combined neighbours
+ * first: 64 -> 32 values by adding accumulators 2m and 2m+1, and so on at
+ * distances 1, 2, 4, 8, 16, 32 (a balanced binary tree); gnorm likewise over
+ * the T values of a sample (value t on accumulator t mod 64, plain adds, the
+ * same tree, then a correctly rounded square root).
  */
 vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X,
                            const uint8_t *sample_mask, float *gsq, float *xsq, float *gnorm,
@@ -152,7 +155,7 @@ vcas_status vcas_row_scale(const vcas_shape *shape, const float *p, const float 
                            const uint8_t *maskW, float *scaleW, void *stream);
 
 /*
- * Sampled activation gradient (Eq. 1, upper line; SampleA only):
+ * Sampled activation gradient (Eq. 2, upper line; SampleA only):
  *   dX[r,:] = (1/p[i]) * G[r,:] W   for the T rows r of every kept sample i,
  *   dX[r,:] = 0                     for rows of dropped samples.
  * idxA/cntA: kept samples ascending and their count (device).  dX [R,K_in] in
@@ -163,7 +166,7 @@ vcas_status vcas_sampled_dgrad(const vcas_shape *shape, const void *G, const voi
                                const int32_t *idxA, const int32_t *cntA, void *dX, void *stream);
 
 /*
- * The same through an elementwise layer below the linear one (App. A: for a
+ * The same through an elementwise layer below the linear one (App. E, proof of unbiasedness: for a
  * non-linear layer such as ReLU the activation gradient is multiplied, entry by
  * entry, by the Jacobian saved in the forward pass):
  *   dX[r,:] = ((1/p[i]) * G[r,:] W) * J[r,:]   on rows of kept samples, 0 elsewhere.
@@ -203,6 +206,9 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
  * event).  Consecutive calls may share one side stream; their weight-gradient
  * halves then run in call order behind each other.  Both streams must have the
  * default priority.  With side_stream null everything is on `stream`.
+ * The event that orders the two streams belongs to the library and is shared
+ * by all calls: with a side stream, call this (and every other entry point that
+ * takes more than one stream) from one host thread at a time.
  */
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W,
                                  double rho, double nu, const vcas_rng *rng, int32_t token_sampling,
@@ -277,7 +283,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
  * that schedule them apart (e.g. the weight gradients of a block of layers on a
  * second stream while the chain of activation gradients goes on).
  * vcas_backward_data: row norms of G, p, SampleA mask and kept list (Sec. 4.1),
- * dX (Eq. 1, upper line; dX may be null); on small layers also the row norms of
+ * dX (Eq. 2, upper line; dX may be null); on small layers also the row norms of
  * X and the SampleW uniforms, which do not depend on SampleA.  Fills gsq, gnorm,
  * p, maskA, idxA, cntA of *plan; the score and q arrays of *plan carry
  * intermediate values (square roots of the row norms) to the weight call and
@@ -293,8 +299,8 @@ vcas_status vcas_backward_data(const vcas_shape *shape, const void *G, const voi
                                double rho, const vcas_rng *rng, int32_t token_sampling,
                                const vcas_plan *plan, void *dX, void *workspace, void *stream);
 /*
- * vcas_backward_data for a layer inside a stack of layers (Sec. 3: the
- * activation gradient grows sparser layer by layer; App. A: elementwise layers
+ * vcas_backward_data for a layer inside a stack of layers (Sec. 4: the
+ * activation gradient grows sparser layer by layer; App. E: elementwise layers
  * in between multiply by their Jacobian).  Three additions, each optional:
  *   J (null: none): elementwise Jacobian [R,K_in] of the layer below, multiplied
  *     into dX as in vcas_sampled_dgrad_jac; needs dX.
@@ -405,7 +411,7 @@ vcas_status vcas_controller_update(const vcas_controller_params *prm, int32_t L,
 
 /*
  * Profiling aid, not part of the method: between vcas_profile_begin and
- * vcas_profile_end every dgrad / wgrad GEMM launch (Eq. 1 upper line resp.
+ * vcas_profile_end every dgrad / wgrad GEMM launch (Eq. 2 upper line resp.
  * Sec. 4.2's grad_W) is bracketed by HIP events stamped by the kernel's own
  * dispatch.  vcas_profile_end waits for them and returns, in HOST arrays of two
  * entries ([0] dgrad, [1] wgrad), the summed kernel durations in milliseconds

@@ -171,7 +171,7 @@ def dgrad(G, W, dtype: int, N: int, T: int, p, maskA) -> np.ndarray:
 
 def dgrad_jacobian(G, W, J, dtype: int, N: int, T: int, p, maskA) -> np.ndarray:
     """fp64 (SampleA(G) W) * J: the activation gradient passed through an elementwise layer whose
-    saved Jacobian is J [R, K_in] (App. A: the Hadamard product for non-linear layers such as ReLU)."""
+    saved Jacobian is J [R, K_in] (App. E, proof of unbiasedness: the Hadamard product for non-linear layers such as ReLU)."""
     J = _check(J, dtype)
     out = dgrad(G, W, dtype, N, T, p, maskA)
     assert J.shape == out.shape

@@ -328,7 +328,7 @@ void orc_row_scale(const float *p, const float *q, const uint8_t *maskW, int N, 
 /* --------------------------------------------------------------- gradients */
 
 /*
- * Activation gradient (Eq. 1 upper line with h = multiplication by W):
+ * Activation gradient (Eq. 2 upper line with h = multiplication by W):
  * dX[r,:] = (m_i / p_i) * sum_o G[r,o] W[o,:] for r in sample i; fp64.
  */
 void orc_dgrad(const void *G, const void *W, int dtype, int N, int T, int K_in, int K_out,

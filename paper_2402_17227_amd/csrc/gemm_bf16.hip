@@ -1,5 +1,5 @@
 // bf16 MFMA gather-GEMMs of the VCAS backward pass (gfx950):
-//   dgrad  dX[rows of kept samples] = (1/p_i) * G[row,:] W          (Eq. 1, upper line)
+//   dgrad  dX[rows of kept samples] = (1/p_i) * G[row,:] W          (Eq. 2, upper line)
 //   wgrad  dW = sum over kept tokens t of scale_t * g_t x_t^T        (Sec. 4.2)
 // Both are dense contractions over the kept rows only, so they run on the
 // matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
@@ -625,7 +625,7 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
                 float lo = odd ? recv : mine_e, hi = odd ? mine_o : recv;
                 const int col = n0 + wn0 + j * 32 + (lane & 30);
                 if (dst >= 0 && col < K_in) {
-                    if (J) {   // elementwise Jacobian of the layer below (App. A), same layout as dX
+                    if (J) {   // elementwise Jacobian of the layer below (App. E, proof of unbiasedness), same layout as dX
                         const uint32_t jw = *reinterpret_cast<const uint32_t *>(J + (int64_t)dst * K_in + col);
                         lo = lo * bf16_lo(jw);
                         hi = hi * bf16_hi(jw);

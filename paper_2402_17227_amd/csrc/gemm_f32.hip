@@ -1,5 +1,5 @@
 // fp32 gather-GEMMs of the VCAS backward pass (the fp32 configuration):
-// dgrad (Eq. 1, upper line) and wgrad (Sec. 4.2) on v_mfma_f32_32x32x2_f32.
+// dgrad (Eq. 2, upper line) and wgrad (Sec. 4.2) on v_mfma_f32_32x32x2_f32.
 // 64x64 output tile per workgroup of 4 wavefronts (2x2, one 32x32 MFMA block
 // each), contraction in steps of 16.  LDS tiles are k-major ([k][row], pitch
 // 68 floats) so that fragment reads are 32 consecutive floats; only dgrad's G
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void dgrad_f32_kernel(const float *__restrict_
         if (row_of[r] >= 0 && col < K_in) {
             const int64_t at = (int64_t)row_of[r] * K_in + col;
             float val = acc[v] * scale_of[r];
-            if (J) val = val * J[at];   // elementwise Jacobian of the layer below (App. A)
+            if (J) val = val * J[at];   // elementwise Jacobian of the layer below (App. E, proof of unbiasedness)
             dX[at] = val;
         }
     }

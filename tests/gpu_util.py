@@ -29,6 +29,36 @@ def rel_l2(got, ref) -> float:
     return num / den if den > 0 else num
 
 
+def rel_l2_rows(got, ref) -> float:
+    """Worst relative L2 error of a single row (dX: every row carries its own sample's and token's scale, so
+    a row is the natural unit).  A bound on every row implies the same bound on the whole tensor, and a
+    misplaced or stale tile cannot hide behind the rows with the large norms.  Rows that are zero in the
+    reference (dropped samples) must be exactly zero."""
+    got = np.asarray(got, np.float64).reshape(np.shape(ref))
+    ref = np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    num = np.sqrt(((got - ref) ** 2).sum(axis=-1))
+    den = np.sqrt((ref ** 2).sum(axis=-1))
+    zero = den == 0
+    if np.any(num[zero] != 0):
+        return float("inf")
+    return float((num[~zero] / den[~zero]).max()) if np.any(~zero) else 0.0
+
+
+def rel_l2_tiles(got, ref, tile: int = 128) -> float:
+    """Worst relative L2 error of a tile x tile block of a matrix (dW: one block = one workgroup's output
+    tile of the largest weight-gradient kernel, and a multiple of the smaller kernels' tiles); implies the
+    same bound on the whole matrix."""
+    got = np.asarray(got, np.float64).reshape(np.shape(ref))
+    ref = np.asarray(ref, np.float64)
+    worst = 0.0
+    for r0 in range(0, ref.shape[0], tile):
+        for c0 in range(0, ref.shape[1], tile):
+            worst = max(worst, rel_l2(got[r0:r0 + tile, c0:c0 + tile], ref[r0:r0 + tile, c0:c0 + tile]))
+    return worst
+
+
 def run_layer_gpu(spec, G, X, W, draw: int = 0, token_sampling: bool = True, want_dX=True, want_dW=True):
     """One call of vcas_linear_backward.  Returns (plan as numpy dict, dX fp64, dW fp64)."""
     shape = vb.shape_of(spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)

@@ -441,7 +441,7 @@ def test_config_one_runs_in_seconds_and_keeps_about_the_stated_fraction():
 
 
 def test_jacobian_product_is_the_chain_rule_by_finite_differences():
-    """App. A: behind an elementwise layer h = phi(z) the activation gradient is (G W) * phi'(z).
+    """App. E (proof of unbiasedness): behind an elementwise layer h = phi(z) the activation gradient is (G W) * phi'(z).
     Checked against central differences of L(z) = sum(G * (phi(z) W^T)) on a tiny case, all samples kept."""
     rng = np.random.default_rng(4)
     N, T, K_in, K_out = 2, 3, 5, 4
