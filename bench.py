@@ -3,12 +3,13 @@
 
 One "step" is one pass of the whole hot path (row norms -> keep probabilities
 -> Philox masks -> compaction -> sampled dX and dW) over every linear layer of
-the BERT-base-shaped stack (72 layers, B=32, L=128, bf16), each layer with its
-own synthetic G, X, W resident in HBM.  The data halves run in the order a backward
-pass imposes: down, up, out-projection one behind the other, then V, K and Q, whose
-upstream gradients do not depend on each other, together.  Prints ONE JSON line.
+the BERT-large-shaped stack (144 layers, B=32, L=512, bf16: the largest of the
+configurations by kept work), each layer with its own synthetic G, X, W
+resident in HBM.  The data halves run in the order a backward pass imposes:
+down, up, out-projection one behind the other, then V, K and Q, whose upstream
+gradients do not depend on each other, together.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large]
 """
 from __future__ import annotations
 
@@ -30,10 +31,12 @@ PEAK_F32_TFLOPS = 157.3
 class Layer:
     """Device-resident tensors and scratch of one linear layer."""
 
-    def __init__(self, spec, vb, to_device, make_layer, cache=None):
+    def __init__(self, spec, vb, to_device, make_layer, cache=None, arrays=None):
         import torch
         key = (spec.N, spec.T, spec.K_in, spec.K_out, spec.dtype)
-        if cache is not None and key in cache:
+        if arrays is not None:
+            G, X, W = arrays
+        elif cache is not None and key in cache:
             G, X, W = cache[key]
         else:
             G, X, W = make_layer(spec)
@@ -61,10 +64,13 @@ def cpu_baseline(specs, make_layer):
         oracle.linear_backward(G, X, W, s.dtype, s.N, s.T, s.rho, s.nu, s.seed, s.layer, 0)
         secs += time.perf_counter() - t0
         flops += 4.0 * s.R * s.K_in * s.K_out
+    whole = len(picked) == len(specs)
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s (effective, dense-equivalent)",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{len(picked)} of {len(specs)} layers (blocks {sorted(_sample_blocks(specs))}), "
-                      f"{secs:.1f} s of oracle time"}
+                      f"{secs:.1f} s of oracle time"
+                      + ("" if whole else f"; rate over the sample only, a whole step extrapolated by dense-equivalent "
+                                          f"flops would take {sum(4.0 * s.R * s.K_in * s.K_out for s in specs) / (flops / secs):.0f} s")}
 
 
 def _sample_blocks(specs):
@@ -91,17 +97,18 @@ def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary of this workload
     (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size); None
     if no summary covers it.  The counters cannot be read from inside this process."""
-    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.md")
+    rel = os.path.join("profiles", f"bench_{workload}_hbm_traffic.md")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         parts = [p.strip() for p in line.strip().strip("|").split("|")]
         if len(parts) >= 2 and parts[0] == f"traffic_bytes_per_launch {kernel}":
             try:
-                return float(parts[1])
+                return float(parts[1]), rel
             except ValueError:
-                return None
-    return None
+                return None, None
+    return None, None
 
 
 def per_shape_report(args, specs, vb, to_device, workloads):
@@ -232,12 +239,49 @@ def per_shape_report(args, specs, vb, to_device, workloads):
     print("\n".join(rows), file=sys.stderr)
 
 
+def adaptation_leg(args, layers, vb, torch):
+    """What one update of the adaptive keep ratios costs on this stack (Sec. 5, Alg. 1; App. D): for each of
+    M = 2 batches an exact backward pass (dX and dW at keep ratio one) whose dW feeds the running mean and
+    mean of squares on every 100th parameter, then the variance probe with M mask draws (SampleA-only dW
+    against the exact one, Eq. 3 under each draw's data mask) and Eq. 4's sparsity at s - alpha and
+    s + alpha.  The probe forms its own exact dW and also the Monte-Carlo term with both samplers, which
+    Alg. 1 does not need, so the figure is an upper bound.  The resident inputs stand in for both batches."""
+    import time
+    M, stride = 2, 100
+    side = []
+    for l in layers:
+        m = (l.spec.K_out * l.spec.K_in + stride - 1) // stride
+        side.append((torch.zeros(m, device="cuda"), torch.zeros(m, device="cuda"),
+                     torch.empty(4, dtype=torch.float64, device="cuda"), torch.empty(2, device="cuda"), m))
+
+    def update():
+        for i in range(M):
+            for l, (mean, sq, out4, pr, m) in zip(layers, side):
+                s = l.spec
+                vb.vcas_linear_backward(l.shape, l.G, l.X, l.W, 1.0, 1.0, vb.Rng(s.seed, s.layer, 0), True, l.plan,
+                                        l.dX, l.dW, l.ws)
+                vb.vcas_grad_stats_update(l.dW, m, stride, i + 1, mean, sq)
+                vb.vcas_variance_probe(l.shape, l.G, l.X, s.rho, s.nu, vb.Rng(s.seed, s.layer, 10 * i), M, l.plan,
+                                       out4, l.ws)
+                vb.vcas_sparsity_ratio(l.plan.gnorm, [0.98, 1.0], pr)
+
+    update()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    update()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    return {"ms_per_update": ms, "M": M, "kept_parameter_stride": stride,
+            "what": "2 batches x (exact dX+dW, running statistics, probe with 2 draws, Eq. 4 at two levels) over "
+                    "every layer, one stream; an upper bound (the probe repeats the exact dW and adds a SampleA+SampleW term)"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="bert_base")
+    ap.add_argument("--workload", default="bert_large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true", help="keep the weight-gradient half on the main stream")
     ap.add_argument("--side-streams", type=int, default=1, help="streams the weight-gradient halves rotate over")
@@ -272,6 +316,9 @@ def main():
                     help="instead of the stack step: one layer per distinct linear shape (at the workload's largest and "
                          "smallest data keep ratio), median of 50 event-timed calls after 10 warm-ups, inputs rotated "
                          "over enough copies to defeat the caches; writes a markdown table to FILE and prints no result line")
+    ap.add_argument("--adaptation", action="store_true",
+                    help="also time one update of the adaptive keep ratios (Alg. 1 with M = 2) on the same stack and "
+                         "print it beside ms_per_step")
     ap.add_argument("--counters-pass", action="store_true",
                     help="for a rocprofv3 --pmc run: the sampled steps only, launched eagerly, then one plain 256 MiB "
                          "device copy whose known size calibrates FETCH_SIZE / WRITE_SIZE; prints no result line")
@@ -282,7 +329,7 @@ def main():
     import torch
     import workloads
     from paper_2402_17227_amd import binding as vb
-    from tests.gpu_util import to_device
+    to_device = vb.to_device
 
     vb.lib()                                    # fails loudly if libvcas.so was not built
     assert torch.cuda.is_available(), "bench.py needs the GPU"
@@ -296,10 +343,24 @@ def main():
         return
     cache = {} if args.share_inputs else None
     layers = []
-    for k, s in enumerate(specs):
-        layers.append(Layer(s, vb, to_device, workloads.make_layer, cache))
-        if k % 24 == 23:
-            print(f"bench.py: {k + 1} of {len(specs)} layers resident", file=sys.stderr, flush=True)
+    if args.share_inputs:
+        for k, s in enumerate(specs):
+            layers.append(Layer(s, vb, to_device, workloads.make_layer, cache))
+    else:
+        # every layer gets values of its own; the host-side generators run a few layers ahead of the
+        # uploads on a handful of threads (numpy releases the interpreter lock while it draws)
+        from concurrent.futures import ThreadPoolExecutor
+        workers = max(1, min(8, (os.cpu_count() or 2) - 1))
+        with ThreadPoolExecutor(workers) as pool:
+            ahead = []
+            nxt = 0
+            for k, s in enumerate(specs):
+                while nxt < len(specs) and len(ahead) < 2 * workers:
+                    ahead.append(pool.submit(workloads.make_layer, specs[nxt]))
+                    nxt += 1
+                layers.append(Layer(s, vb, to_device, workloads.make_layer, arrays=ahead.pop(0).result()))
+                if k % 24 == 23:
+                    print(f"bench.py: {k + 1} of {len(specs)} layers resident", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     dense_flops = sum(l.dense_flops for l in layers)
 
@@ -427,8 +488,11 @@ def main():
         name, avg_ms, flops, alg_bytes = f"wgrad_{sfx}_kernel", wg_avg, kept_toks / wg_per_step, wg_bytes
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
     achieved = flops / (avg_ms * 1e-3) / 1e12
+    traffic, traffic_src = measured_traffic(args.workload.split(":")[0], name)
     roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": measured_traffic(args.workload, name),
+                "frac": achieved / peak, "traffic": traffic,
+                "traffic_source": (f"{traffic_src}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --counters-pass`, "
+                                   "taken with the build that file names, not measured in this run") if traffic_src else None,
                 "algorithmic_bytes": alg_bytes, "avg_launch_us": avg_ms * 1e3,
                 "launches_per_step": dg_per_step if name.startswith("dgrad") else wg_per_step,
                 "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
@@ -443,15 +507,41 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / reps
 
-    def dense_own():        # this library's two GEMMs at keep ratio one, sampling passes skipped
-        for l in layers:
-            vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.ones_p, l.iota_N, l.full_N, l.dX)
-            vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.ones_R, l.iota_R, l.full_R, l.dW, l.ws)
+    # Two launch forms each: everything on one stream, and the form the sampled step itself has (the
+    # chain of dX on the main stream, every dW on a side stream, joined at the end), so that the
+    # sampled step is compared with a dense step that overlaps its two halves the same way.
+    dense_side = torch.cuda.Stream()
 
-    def dense_torch():
-        for l in layers:
-            torch.matmul(l.G, l.W, out=l.dX)
-            torch.matmul(l.G.t(), l.X)
+    def two_streams(dx_half, dw_half):
+        def run():
+            main = torch.cuda.current_stream()
+            dense_side.wait_stream(main)
+            for l in layers:
+                dx_half(l)
+            with torch.cuda.stream(dense_side):
+                for l in layers:
+                    dw_half(l)
+            main.wait_stream(dense_side)
+        return run
+
+    def own_dx(l):          # this library's two GEMMs at keep ratio one, sampling passes skipped
+        vb.vcas_sampled_dgrad(l.shape, l.G, l.W, l.ones_p, l.iota_N, l.full_N, l.dX)
+
+    def own_dw(l):
+        vb.vcas_sampled_wgrad(l.shape, l.G, l.X, l.ones_R, l.iota_R, l.full_R, l.dW, l.ws)
+
+    def torch_dx(l):
+        torch.matmul(l.G, l.W, out=l.dX)
+
+    def torch_dw(l):        # dW in the layer dtype here (the library writes fp32), into a buffer that exists
+        torch.matmul(l.G.t(), l.X, out=l.dW_t)
+
+    def one_stream(dx_half, dw_half):
+        def run():
+            for l in layers:
+                dx_half(l)
+                dw_half(l)
+        return run
 
     for l in layers:
         s = l.spec
@@ -461,9 +551,19 @@ def main():
         l.ones_R = torch.ones(s.R, device="cuda")
         l.iota_R = torch.arange(s.R, dtype=torch.int32, device="cuda")
         l.full_R = torch.full((1,), s.R, dtype=torch.int32, device="cuda")
+        l.dW_t = torch.empty((s.K_out, s.K_in), dtype=l.G.dtype, device="cuda")
     reps = max(3, min(args.steps, 10))
-    dense_own_ms = timed(dense_own, reps)
-    dense_torch_ms = timed(dense_torch, reps)
+    dense_ms = {
+        "this_library_keep_ratio_1_gemms_only": timed(one_stream(own_dx, own_dw), reps),
+        "this_library_keep_ratio_1_gemms_only_two_streams": timed(two_streams(own_dx, own_dw), reps),
+        "torch_matmul": timed(one_stream(torch_dx, torch_dw), reps),
+        "torch_matmul_two_streams": timed(two_streams(torch_dx, torch_dw), reps),
+    }
+    dense_note = ("dX and dW of every layer at keep ratio one, no sampling passes; two_streams = the sampled step's own "
+                  "launch form (dX chain on the main stream, dW on a side stream); torch.matmul writes dW in bf16, "
+                  "the library in fp32")
+
+    adaptation = adaptation_leg(args, layers, vb, torch) if args.adaptation else None
 
     out = {
         "metric": METRIC,
@@ -484,10 +584,12 @@ def main():
         "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,
-        "dense_ms_per_step": {"this_library_keep_ratio_1_gemms_only": dense_own_ms, "torch_matmul": dense_torch_ms},
-        "speedup_vs_dense": {"this_library": dense_own_ms / ms_per_step, "torch_matmul": dense_torch_ms / ms_per_step},
+        "dense_ms_per_step": dict(dense_ms, note=dense_note),
+        "speedup_vs_dense": {k: v / ms_per_step for k, v in dense_ms.items()},
         "roofline": roofline,
     }
+    if adaptation is not None:
+        out["adaptation"] = adaptation
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, workloads.make_layer)
     print(json.dumps(out))

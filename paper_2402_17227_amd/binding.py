@@ -88,6 +88,15 @@ def shape_of(N: int, T: int, K_in: int, K_out: int, dtype: int) -> Shape:
     return Shape(N, T, K_in, K_out, dtype)
 
 
+def to_device(a, dtype: int) -> torch.Tensor:
+    """Host array (numpy fp32, or bf16 bit patterns as uint16) -> device tensor of the layer dtype; a copy,
+    no arithmetic."""
+    import numpy as np
+    if dtype == VCAS_BF16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
 def dtype_of(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return VCAS_BF16

@@ -9,11 +9,7 @@ import workloads
 from paper_2402_17227_amd import binding as vb
 
 
-def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
-    """numpy (fp32, or bf16 bit patterns as uint16) -> device tensor of the layer dtype."""
-    if dtype == workloads.BF16:
-        return torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16).cuda()
-    return torch.from_numpy(a).cuda()
+to_device = vb.to_device     # numpy (fp32, or bf16 bit patterns as uint16) -> device tensor of the layer dtype
 
 
 def from_device(t: torch.Tensor) -> np.ndarray:
