@@ -46,7 +46,8 @@ typedef enum {
     VCAS_ENULL = 2,      /* required pointer is null */
     VCAS_EDTYPE = 3,     /* dtype is neither VCAS_F32 nor VCAS_BF16 */
     VCAS_EWORKSPACE = 4, /* workspace missing */
-    VCAS_EHIP = 5        /* a HIP launch failed; hipGetLastError has the cause */
+    VCAS_EHIP = 5,       /* a HIP launch failed; hipGetLastError has the cause */
+    VCAS_ETOOBIG = 6     /* the problem needs more scratch than the library's static buffer holds */
 } vcas_status;
 
 typedef enum { VCAS_F32 = 0, VCAS_BF16 = 1 } vcas_dtype;
@@ -188,6 +189,27 @@ vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const
 vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X,
                                const float *row_scale, const int32_t *idxW, const int32_t *cntW,
                                float *dW, void *workspace, void *stream);
+
+/*
+ * vcas_sampled_wgrad for callers that cannot allocate or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without `workspace`, same kernels, the same bits in
+ * dW.  The split-K partial tiles go to a buffer of vcas_static_scratch_bytes()
+ * (64 MiB) that is part of the library's device image: each GPU the library runs
+ * on holds its own copy until the process ends, and its address is looked up once
+ * per device, on the first call there (with that device current).  The call
+ * allocates and frees nothing.  A shape whose partial tiles do not fit
+ * (K_out * K_in * 4 bytes times the number of split-K slices, at most 8) is
+ * refused with VCAS_ETOOBIG before anything is launched; every shape of the
+ * benchmark configurations fits.  All calls on one GPU share that buffer: calls
+ * that may overlap there (different streams without an ordering between them,
+ * different host threads) race on it and must be ordered by the caller.  Nothing
+ * needs clearing between calls: the kernels overwrite what they later read.
+ */
+size_t vcas_static_scratch_bytes(void);
+vcas_status vcas_sampled_wgrad_static(const vcas_shape *shape, const void *G, const void *X,
+                                      const float *row_scale, const int32_t *idxW, const int32_t *cntW,
+                                      float *dW, void *stream);
 
 /*
  * The whole path for one layer and one draw, in the paper's order: row norms

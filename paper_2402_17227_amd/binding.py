@@ -14,11 +14,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvcas.so")
 
 VCAS_F32, VCAS_BF16 = 0, 1
-STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: "VCAS_EWORKSPACE", 5: "VCAS_EHIP"}
+STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: "VCAS_EWORKSPACE", 5: "VCAS_EHIP",
+          6: "VCAS_ETOOBIG"}
 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
+    "vcas_static_scratch_bytes", "vcas_sampled_wgrad_static",
     "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_backward_weight_cached",
     "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
@@ -196,6 +198,17 @@ def vcas_sampled_dgrad_jac(shape: Shape, G, W, p, idxA, cntA, J, dX):
 def vcas_sampled_wgrad(shape: Shape, G, X, row_scale, idxW, cntW, dW, workspace):
     _check(lib().vcas_sampled_wgrad(C.byref(shape), _ptr(G), _ptr(X), _ptr(row_scale), _ptr(idxW), _ptr(cntW),
                                     _ptr(dW), _ptr(workspace), _stream()), "vcas_sampled_wgrad")
+
+
+def vcas_static_scratch_bytes() -> int:
+    f = lib().vcas_static_scratch_bytes
+    f.restype = C.c_size_t
+    return int(f())
+
+
+def vcas_sampled_wgrad_static(shape: Shape, G, X, row_scale, idxW, cntW, dW):
+    _check(lib().vcas_sampled_wgrad_static(C.byref(shape), _ptr(G), _ptr(X), _ptr(row_scale), _ptr(idxW), _ptr(cntW),
+                                           _ptr(dW), _stream()), "vcas_sampled_wgrad_static")
 
 
 def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan,

@@ -173,19 +173,55 @@ static void wgrad_choice_bf16(const vcas_shape &s, int64_t expected_tokens, int 
     splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile), fill);
 }
 
-static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
-                                  const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
-                                  int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
+// partials: room for the split-K partial tiles of this shape (wgrad_partial_bytes)
+static vcas_status dispatch_wgrad_into(const vcas_shape &s, const void *G, const void *X, const float *scale,
+                                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials,
+                                       int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
 {
-    const WorkspaceLayout w = workspace_layout(&s);
-    unsigned char *base = static_cast<unsigned char *>(workspace);
-    float *partials = reinterpret_cast<float *>(base + w.partials);
     if (s.dtype != VCAS_BF16)
         return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split_for(&s, wgrad_tiles_f32(s.K_out, s.K_in), fill),
                          st);
     int tile, splits;
     wgrad_choice_bf16(s, expected_tokens, tile, splits, fill);
     return wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, tile, splits, st);
+}
+
+static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
+                                  const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
+                                  int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
+{
+    const WorkspaceLayout w = workspace_layout(&s);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    return dispatch_wgrad_into(s, G, X, scale, idxW, cntW, dW, reinterpret_cast<float *>(base + w.partials),
+                               expected_tokens, st, fill);
+}
+
+// ---- the library's own scratch, for the entry point that takes no workspace --------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name
+// is only a handle: its device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *scratch_of_device[kMaxDevices];   // zero until first use on that device
+
+static vcas_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VCAS_EHIP;
+    if (!scratch_of_device[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return VCAS_EHIP;
+        scratch_of_device[dev] = ptr;
+    }
+    *out = scratch_of_device[dev];
+    return VCAS_OK;
+}
+
+// Bytes of split-K partial tiles vcas_sampled_wgrad's kernels write for this shape.
+static size_t wgrad_partial_bytes(const vcas_shape &s)
+{
+    return (size_t)s.K_out * s.K_in * sizeof(float) * (size_t)wgrad_split(&s);
 }
 
 static bool plan_complete(const vcas_plan *pl)
@@ -501,6 +537,7 @@ const char *vcas_status_string(vcas_status s)
     case VCAS_EDTYPE: return "unknown dtype";
     case VCAS_EWORKSPACE: return "workspace missing";
     case VCAS_EHIP: return "HIP launch failed";
+    case VCAS_ETOOBIG: return "problem needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -606,6 +643,24 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
     if (!workspace) return VCAS_EWORKSPACE;
     if (!aligned16(G) || !aligned16(X) || !aligned16(dW) || !aligned16(workspace)) return VCAS_EINVAL;
     return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, 0, as_stream(stream));
+}
+
+size_t vcas_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+vcas_status vcas_sampled_wgrad_static(const vcas_shape *shape, const void *G, const void *X, const float *row_scale_,
+                                      const int32_t *idxW, const int32_t *cntW, float *dW, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
+    if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
+    if (!aligned16(G) || !aligned16(X) || !aligned16(dW)) return VCAS_EINVAL;
+    if (wgrad_partial_bytes(*shape) > kStaticScratchBytes) return VCAS_ETOOBIG;
+    void *buf = nullptr;
+    VCAS_TRY(static_scratch(&buf));
+    // the partial tiles are written in full by the slices that are active before the reduction reads
+    // them, so whatever the last call left in the buffer does not matter and nothing is cleared
+    return dispatch_wgrad_into(*shape, G, X, row_scale_, idxW, cntW, dW, static_cast<float *>(buf), 0,
+                               as_stream(stream));
 }
 
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
