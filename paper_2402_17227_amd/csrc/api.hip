@@ -49,8 +49,7 @@ bool plan_fused_fits(int N, int T);
 vcas_status plan_fused(const void *G, int K_out, const void *X, int K_in, int dtype, int N, int T, double budget_a,
                        double budget_w, int token_sampling, const vcas_rng &rng, float *uniforms, uint32_t *ticket,
                        const vcas_plan &pl, hipStream_t st);
-// gemm_bf16.hip / gemm_f32.hip
-int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens);
+// gemm_bf16.hip / wgrad_bf16.hip / gemm_f32.hip
 int wgrad_tiles_bf16(int K_out, int K_in, int tile);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
@@ -58,10 +57,7 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
                        const InlineSampleA *sample_a, hipStream_t st);
 vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
                              hipStream_t st);
-vcas_status wgrad_bf16_group(const vcas_shape &s, const WgradProblem *probs, int n, int tile, int splits, hipStream_t st);
-vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
-                       hipStream_t st);
+vcas_status wgrad_bf16_batch(const WgradItem *items, int n, int tile, hipStream_t st);
 vcas_status dgrad_f32(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                       const int32_t *cntA, void *dX, const void *J, bool fill, hipStream_t st);
 vcas_status wgrad_f32(const vcas_shape &s, const void *G, const void *X, const float *row_scale, const int32_t *idxW,
@@ -162,38 +158,75 @@ static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void
                                 : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, fill, st);
 }
 
-// expected_tokens: how many tokens the caller expects SampleW to keep (R if unknown); it only
-// steers the tile choice.
-// Tile edge and split-K slices dispatch_wgrad picks for a bf16 layer.
-static void wgrad_choice_bf16(const vcas_shape &s, int64_t expected_tokens, int &tile, int &splits,
-                              int fill = kWgradFill)
+// Tile edge and split-K slices of bf16 weight gradients.  `fill` = the workgroups a launch should
+// have before the contraction stops being cut into slices; tiles256 / tiles128 = output tiles of
+// everything the launch covers (one layer, or a batch of layers).  The largest tile that fills the
+// launch without slicing wins (a 256x256 tile moves half the operand bytes per flop of a 128x128
+// one, and a CU pulls operand tiles in at a fixed rate); else 128x128 with slices; 64x64 for
+// weight gradients of a few tiles only.
+static int wgrad_tile_choice(int tiles256, int tiles128, int fill)
 {
-    const int64_t R = (int64_t)s.N * s.T;
-    tile = wgrad_tile_bf16(s.K_out, s.K_in, expected_tokens > 0 && expected_tokens < R ? expected_tokens : R);
-    splits = wgrad_split_for(&s, wgrad_tiles_bf16(s.K_out, s.K_in, tile), fill);
+    if (tiles256 >= fill) return 256;
+    return tiles128 >= 16 ? 128 : 64;
 }
 
-// partials: room for the split-K partial tiles of this shape (wgrad_partial_bytes)
+// Slices for one layer of a launch whose tiles (of every layer it covers) number `launch_tiles`:
+// enough to reach `fill` workgroups, at most 8, never so many that a slice at full length R would
+// have fewer than 2 contraction steps, never more than the workspace has room for.
+static int wgrad_slices_bf16(const vcas_shape &s, int launch_tiles, int fill)
+{
+    const int64_t R = (int64_t)s.N * s.T;
+    int64_t want = (fill + launch_tiles - 1) / launch_tiles;
+    const int64_t cap = ((R + 63) / 64) / 2;
+    if (want > cap) want = cap;
+    if (want > wgrad_split(&s)) want = wgrad_split(&s);
+    if (want > 8) want = 8;
+    return want < 1 ? 1 : (int)want;
+}
+
+static int fill_or_default(int fill) { return fill <= 0 || fill > kWgradFill ? kWgradFill : fill; }
+
+static WgradItem wgrad_item(const vcas_shape &s, const void *G, const void *X, const float *scale, const int32_t *idxW,
+                            const int32_t *cntW, float *dW, float *partials, uint16_t *packed)
+{
+    WgradItem it;
+    it.shape = s;
+    it.G = G;
+    it.X = X;
+    it.row_scale = scale;
+    it.idxW = idxW;
+    it.cntW = cntW;
+    it.dW = dW;
+    it.partials = partials;
+    it.packed = packed;
+    it.splits = 1;
+    return it;
+}
+
+// One layer on its own.  partials: room for wgrad_split(s) partial tiles; packed (bf16): room for
+// R rows of the narrower operand.
 static vcas_status dispatch_wgrad_into(const vcas_shape &s, const void *G, const void *X, const float *scale,
                                        const int32_t *idxW, const int32_t *cntW, float *dW, float *partials,
-                                       int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
+                                       uint16_t *packed, hipStream_t st, int fill = kWgradFill)
 {
     if (s.dtype != VCAS_BF16)
         return wgrad_f32(s, G, X, scale, idxW, cntW, dW, partials, wgrad_split_for(&s, wgrad_tiles_f32(s.K_out, s.K_in), fill),
                          st);
-    int tile, splits;
-    wgrad_choice_bf16(s, expected_tokens, tile, splits, fill);
-    return wgrad_bf16(s, G, X, scale, idxW, cntW, dW, partials, tile, splits, st);
+    fill = fill_or_default(fill);
+    const int tile = wgrad_tile_choice(wgrad_tiles_bf16(s.K_out, s.K_in, 256), wgrad_tiles_bf16(s.K_out, s.K_in, 128), fill);
+    WgradItem it = wgrad_item(s, G, X, scale, idxW, cntW, dW, partials, packed);
+    it.splits = wgrad_slices_bf16(s, wgrad_tiles_bf16(s.K_out, s.K_in, tile), fill);
+    return wgrad_bf16_batch(&it, 1, tile, st);
 }
 
 static vcas_status dispatch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *scale,
                                   const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace,
-                                  int64_t expected_tokens, hipStream_t st, int fill = kWgradFill)
+                                  hipStream_t st, int fill = kWgradFill)
 {
     const WorkspaceLayout w = workspace_layout(&s);
     unsigned char *base = static_cast<unsigned char *>(workspace);
     return dispatch_wgrad_into(s, G, X, scale, idxW, cntW, dW, reinterpret_cast<float *>(base + w.partials),
-                               expected_tokens, st, fill);
+                               reinterpret_cast<uint16_t *>(base + w.packed), st, fill);
 }
 
 // ---- the library's own scratch, for the entry point that takes no workspace --------------------
@@ -218,10 +251,17 @@ static vcas_status static_scratch(void **out)
     return VCAS_OK;
 }
 
-// Bytes of split-K partial tiles vcas_sampled_wgrad's kernels write for this shape.
+// Bytes of scratch vcas_sampled_wgrad's kernels use for this shape: the split-K partial tiles, then
+// (bf16) the packed operand.
 static size_t wgrad_partial_bytes(const vcas_shape &s)
 {
-    return (size_t)s.K_out * s.K_in * sizeof(float) * (size_t)wgrad_split(&s);
+    return (((size_t)s.K_out * s.K_in * sizeof(float) * (size_t)wgrad_split(&s)) + 255) & ~(size_t)255;
+}
+
+static size_t wgrad_scratch_bytes(const vcas_shape &s)
+{
+    const WorkspaceLayout w = workspace_layout(&s);
+    return wgrad_partial_bytes(s) + (w.total - w.packed);
 }
 
 static bool plan_complete(const vcas_plan *pl)
@@ -338,21 +378,13 @@ static vcas_status weight_half(const vcas_shape &s, const void *G, const void *X
     VCAS_TRY(sampler_w(pl.gsq, pl.xsq, together ? 1 : 0, pl.p, pl.maskA, u, s.N, s.T, (double)R * rho * nu,
                        token_sampling, together ? 1 : 2, pl.score, pl.q, pl.maskW, pl.scaleW, pl.idxW, pl.cntW, st));
     if (dW)
-        VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
-                                (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));
+        VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
     return VCAS_OK;
 }
 
 static bool same_shape(const vcas_shape &s, const vcas_shape &t)
 {
     return s.N == t.N && s.T == t.T && s.K_in == t.K_in && s.K_out == t.K_out && s.dtype == t.dtype;
-}
-
-// Tokens SampleW is expected to keep (its budget): steers the tile choice of the weight gradient.
-static int64_t expected_tokens(const vcas_layer_args &a)
-{
-    const int64_t R = (int64_t)a.shape.N * a.shape.T;
-    return (int64_t)((double)R * a.rho * (a.token_sampling ? a.nu : 1.0) + 0.5);
 }
 
 // Can layer b of a stack share the launches of its data half with layer a in front of it?  Only
@@ -459,35 +491,62 @@ static vcas_status weight_half_siblings(const vcas_layer_args *layers, int n, hi
     return sampler_w_group(samplers, n, 0, s.N, s.T, token_sampling, 2, st);
 }
 
-// Can layer b share the weight-gradient launch (and the launch of the reductions) of layer a in
-// front of it?  Siblings of one shape that would run with the same tile and slice count on their
-// own: the order of a weight gradient's sums, hence its bits, does not change.
-static bool shares_wgrad(const vcas_layer_args &a, const vcas_layer_args &b)
+// Weight gradients of the layers [l0, l1) of a stack that want one (bf16 layers in batched
+// launches, fp32 layers one by one).  A layer with wgrad_fill == 0 gets the tile and the slices a
+// call on its own would pick, hence that call's bits; the others are planned per launch: the
+// tiles of every layer of the batch count towards `fill`, so a block's weight gradients fill the
+// chip together and are rarely sliced at all.
+static vcas_status wgrad_of_layers(const vcas_layer_args *layers, int l0, int l1, hipStream_t st)
 {
-    if (!b.sibling || !a.dW || !b.dW || a.shape.dtype != VCAS_BF16 || !same_shape(a.shape, b.shape)) return false;
-    int tile_a, splits_a, tile_b, splits_b;
-    wgrad_choice_bf16(a.shape, expected_tokens(a), tile_a, splits_a, a.wgrad_fill);
-    wgrad_choice_bf16(b.shape, expected_tokens(b), tile_b, splits_b, b.wgrad_fill);
-    return tile_a == tile_b && splits_a == splits_b;
-}
-
-static vcas_status wgrad_siblings(const vcas_layer_args *layers, int n, hipStream_t st)
-{
-    WgradProblem probs[kMaxSiblings];
-    for (int i = 0; i < n; ++i) {
-        const vcas_layer_args &b = layers[i];
-        probs[i].G = static_cast<const uint16_t *>(b.G);
-        probs[i].X = static_cast<const uint16_t *>(b.X);
-        probs[i].row_scale = b.plan.scaleW;
-        probs[i].idxW = b.plan.idxW;
-        probs[i].cntW = b.plan.cntW;
-        probs[i].dW = b.dW;
-        probs[i].partials = reinterpret_cast<float *>(static_cast<unsigned char *>(b.workspace) +
-                                                      workspace_layout(&b.shape).partials);
+    for (int l = l0; l < l1;) {
+        const vcas_layer_args &a = layers[l];
+        if (!a.dW) {
+            ++l;
+            continue;
+        }
+        if (a.shape.dtype != VCAS_BF16) {
+            VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace, st,
+                                    a.wgrad_fill));
+            ++l;
+            continue;
+        }
+        // a run of bf16 layers that plan their launch the same way
+        const bool alone = a.wgrad_fill == 0 || a.wgrad_fill >= kWgradFill;
+        int picked[kWgradBatch], n = 0, next = l;
+        int tiles256 = 0, tiles128 = 0;
+        for (; next < l1 && n < kWgradBatch; ++next) {
+            const vcas_layer_args &b = layers[next];
+            if (!b.dW) continue;
+            if (b.shape.dtype != VCAS_BF16 || (b.wgrad_fill == 0 || b.wgrad_fill >= kWgradFill) != alone) break;
+            const int t256 = wgrad_tiles_bf16(b.shape.K_out, b.shape.K_in, 256), t128 = wgrad_tiles_bf16(b.shape.K_out, b.shape.K_in, 128);
+            if (alone && n > 0 &&
+                wgrad_tile_choice(t256, t128, kWgradFill) !=
+                    wgrad_tile_choice(wgrad_tiles_bf16(layers[picked[0]].shape.K_out, layers[picked[0]].shape.K_in, 256),
+                                      wgrad_tiles_bf16(layers[picked[0]].shape.K_out, layers[picked[0]].shape.K_in, 128), kWgradFill))
+                break;
+            picked[n++] = next;
+            tiles256 += t256;
+            tiles128 += t128;
+        }
+        const int fill = fill_or_default(a.wgrad_fill);
+        const vcas_shape &s0 = layers[picked[0]].shape;
+        const int tile = alone ? wgrad_tile_choice(wgrad_tiles_bf16(s0.K_out, s0.K_in, 256), wgrad_tiles_bf16(s0.K_out, s0.K_in, 128), fill)
+                               : wgrad_tile_choice(tiles256, tiles128, fill);
+        int launch_tiles = 0;
+        for (int i = 0; i < n; ++i) launch_tiles += wgrad_tiles_bf16(layers[picked[i]].shape.K_out, layers[picked[i]].shape.K_in, tile);
+        WgradItem items[kWgradBatch];
+        for (int i = 0; i < n; ++i) {
+            const vcas_layer_args &b = layers[picked[i]];
+            const WorkspaceLayout w = workspace_layout(&b.shape);
+            unsigned char *base = static_cast<unsigned char *>(b.workspace);
+            items[i] = wgrad_item(b.shape, b.G, b.X, b.plan.scaleW, b.plan.idxW, b.plan.cntW, b.dW,
+                                  reinterpret_cast<float *>(base + w.partials), reinterpret_cast<uint16_t *>(base + w.packed));
+            items[i].splits = wgrad_slices_bf16(b.shape, alone ? wgrad_tiles_bf16(b.shape.K_out, b.shape.K_in, tile) : launch_tiles, fill);
+        }
+        VCAS_TRY(wgrad_bf16_batch(items, n, tile, st));
+        l = next;
     }
-    int tile, splits;
-    wgrad_choice_bf16(layers[0].shape, expected_tokens(layers[0]), tile, splits, layers[0].wgrad_fill);
-    return wgrad_bf16_group(layers[0].shape, probs, n, tile, splits, st);
+    return VCAS_OK;
 }
 
 static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, const void *X, const void *W, double rho,
@@ -505,9 +564,7 @@ static vcas_status linear_backward_impl(const vcas_shape &s, const void *G, cons
         VCAS_TRY(plan_fused(G, s.K_out, X, s.K_in, s.dtype, s.N, s.T, (double)s.N * rho, (double)R * rho * nu,
                             token_sampling, rng, uniforms_of(s, workspace), tickets, pl, st));
         if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, nullptr, true, (int64_t)((double)R * rho + 0.5), st));
-        if (dW)
-            VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace,
-                                    (int64_t)((double)R * rho * (token_sampling ? nu : 1.0) + 0.5), st));
+        if (dW) VCAS_TRY(dispatch_wgrad(s, G, X, pl.scaleW, pl.idxW, pl.cntW, dW, workspace, st));
         return VCAS_OK;
     }
     if (!forked) {
@@ -642,7 +699,7 @@ vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const voi
     if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
     if (!workspace) return VCAS_EWORKSPACE;
     if (!aligned16(G) || !aligned16(X) || !aligned16(dW) || !aligned16(workspace)) return VCAS_EINVAL;
-    return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, 0, as_stream(stream));
+    return dispatch_wgrad(*shape, G, X, row_scale_, idxW, cntW, dW, workspace, as_stream(stream));
 }
 
 size_t vcas_static_scratch_bytes(void) { return kStaticScratchBytes; }
@@ -654,13 +711,14 @@ vcas_status vcas_sampled_wgrad_static(const vcas_shape *shape, const void *G, co
     VCAS_TRY(check_gemm_limits(shape));
     if (!G || !X || !row_scale_ || !idxW || !cntW || !dW) return VCAS_ENULL;
     if (!aligned16(G) || !aligned16(X) || !aligned16(dW)) return VCAS_EINVAL;
-    if (wgrad_partial_bytes(*shape) > kStaticScratchBytes) return VCAS_ETOOBIG;
+    if (wgrad_scratch_bytes(*shape) > kStaticScratchBytes) return VCAS_ETOOBIG;
     void *buf = nullptr;
     VCAS_TRY(static_scratch(&buf));
-    // the partial tiles are written in full by the slices that are active before the reduction reads
-    // them, so whatever the last call left in the buffer does not matter and nothing is cleared
-    return dispatch_wgrad_into(*shape, G, X, row_scale_, idxW, cntW, dW, static_cast<float *>(buf), 0,
-                               as_stream(stream));
+    // the partial tiles and the packed rows are written in full before anything reads them, so
+    // whatever the last call left in the buffer does not matter and nothing is cleared
+    unsigned char *base = static_cast<unsigned char *>(buf);
+    return dispatch_wgrad_into(*shape, G, X, row_scale_, idxW, cntW, dW, reinterpret_cast<float *>(base),
+                               reinterpret_cast<uint16_t *>(base + wgrad_partial_bytes(*shape)), as_stream(stream));
 }
 
 vcas_status vcas_linear_backward(const vcas_shape *shape, const void *G, const void *X, const void *W, double rho,
@@ -770,17 +828,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (s3 != s2 && (hipEventRecord(events[2 * g + 1], s2) != hipSuccess ||
                          hipStreamWaitEvent(s3, events[2 * g + 1], 0) != hipSuccess))
             return VCAS_EHIP;
-        for (int l = l0; l < l1;) {
-            const vcas_layer_args &a = layers[l];
-            int n = 1;
-            while (a.dW && l + n < l1 && n < kMaxSiblings && shares_wgrad(a, layers[l + n])) ++n;
-            if (n > 1)
-                VCAS_TRY(wgrad_siblings(layers + l, n, s3));
-            else if (a.dW)
-                VCAS_TRY(dispatch_wgrad(a.shape, a.G, a.X, a.plan.scaleW, a.plan.idxW, a.plan.cntW, a.dW, a.workspace,
-                                        expected_tokens(a), s3, a.wgrad_fill));
-            l += n;
-        }
+        VCAS_TRY(wgrad_of_layers(layers, l0, l1, s3));
             return VCAS_OK;
     };
     VCAS_TRY(issue_data(0));

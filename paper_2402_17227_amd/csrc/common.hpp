@@ -53,10 +53,11 @@ inline int elem_bytes(int dtype) { return dtype == VCAS_BF16 ? 2 : 4; }
 // kPlanTicketBytes of control words (the ticket counters of the fused planning
 // kernel), zero between calls; then splits * K_out * K_in fp32: split-K partial tiles of
 // the weight gradient, then two K_out*K_in fp32 matrices and 32 doubles for the
-// variance probe, then R floats: the SampleW uniforms of vcas_linear_backward
+// variance probe, then R floats: the SampleW uniforms of vcas_linear_backward, then (bf16) up to
+// R rows of min(K_in, K_out) elements: the packed operand of the weight gradient
 
 struct WorkspaceLayout {
-    size_t control, partials, probe_exact, probe_draw, probe_acc, uniforms, total;
+    size_t control, partials, probe_exact, probe_draw, probe_acc, uniforms, packed, total;
 };
 
 constexpr size_t kPlanTicketBytes = 8192;   // 33 counters, one 128-byte line each, rounded up
@@ -72,7 +73,10 @@ inline WorkspaceLayout workspace_layout(const vcas_shape *s)
     w.probe_draw = w.probe_exact + mat;
     w.probe_acc = w.probe_draw + mat;
     w.uniforms = w.probe_acc + 256;
-    w.total = w.uniforms + (((size_t)s->N * s->T * sizeof(float) + 255) & ~(size_t)255);
+    w.packed = w.uniforms + (((size_t)s->N * s->T * sizeof(float) + 255) & ~(size_t)255);
+    // bf16: the narrower of G and X over the kept tokens, gathered and multiplied by the token scales
+    const size_t packed_bytes = s->dtype == VCAS_BF16 ? (size_t)s->N * s->T * (s->K_in < s->K_out ? s->K_in : s->K_out) * 2 : 0;
+    w.total = w.packed + ((packed_bytes + 255) & ~(size_t)255);
     return w;
 }
 

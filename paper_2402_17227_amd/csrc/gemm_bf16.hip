@@ -1,237 +1,20 @@
-// bf16 MFMA gather-GEMMs of the VCAS backward pass (gfx950):
+// bf16 MFMA gather-GEMM of the VCAS activation gradient (gfx950):
 //   dgrad  dX[rows of kept samples] = (1/p_i) * G[row,:] W          (Eq. 2, upper line)
-//   wgrad  dW = sum over kept tokens t of scale_t * g_t x_t^T        (Sec. 4.2)
-// Both are dense contractions over the kept rows only, so they run on the
-// matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+// A dense contraction over the kept rows only, on the matrix cores:
+// v_mfma_f32_32x32x16_bf16, fp32 accumulation.  (The weight gradient is in wgrad_bf16.hip.)
 //
-// Tiling: a workgroup of WM x WN wavefronts owns a BM x BN output tile and
-// walks the contraction in steps of 64, operand tiles double (or deeper)
-// buffered in LDS.  An MFMA lane needs 8 consecutive contraction values of one
-// row/column, but W (for dgrad) and both G and X (for wgrad) are stored with
-// the contraction index as the slow dimension.  Two ways of getting them there:
-//
-//  * LDS-direct (dgrad, and the 128x128 wgrad): buffer loads write straight
-//    into LDS; an operand that lies "the wrong way" stays as it is in memory,
-//    [64 k][columns], and ds_read_b64_tr_b16 transposes it on the way out.
-//  * register-staged (the 64x64 wgrad for small dW): 4 rows x 8 columns per
-//    thread with coalesced 16-byte loads, transposed in registers (v_perm_b32)
-//    and written as 8-byte pieces to a [column][64 k] tile whose 16-byte slots
-//    are XOR-swizzled so that fragment reads and transposing writes spread
-//    over all banks.
-//
-// wgrad multiplies G by the per-token scale before it reaches LDS (the scale
-// lies on the contraction axis and cannot go into the epilogue); dgrad's
-// per-row 1/p goes into the epilogue.
-#include <type_traits>
-
-#include "groups.hpp"
+// Tiling: a workgroup of WM x WN wavefronts owns a BM x BN output tile and walks the contraction
+// in steps of 64, operand tiles double buffered in LDS.  The operand tiles never pass through
+// registers: buffer loads write straight into LDS; W, which lies "the wrong way" for an MFMA
+// lane (the contraction index is its slow dimension), stays as it is in memory, [64 k][columns],
+// and ds_read_b64_tr_b16 transposes it on the way out.  The per-row 1/p goes into the epilogue.
+#include "mfma_bf16.hpp"
 
 namespace vcas {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2v;
-typedef __attribute__((ext_vector_type(2))) float f32x2v;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-constexpr int BK = 64;  // contraction elements per step (one 128-byte LDS row)
 
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 7); }
 // byte offset of 16-byte slot `slot` (0..7) of tile row `row`
 __device__ __forceinline__ int lds_off(int row, int slot) { return row * 128 + ((slot ^ swz(row)) << 4); }
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    f32x2v v = {lo, hi};
-    bf16x2v r = __builtin_convertvector(v, bf16x2v);
-    return *reinterpret_cast<uint32_t *>(&r);
-}
-
-// ---------------------------------------------------------------- loaders
-//
-// All global reads are raw buffer loads: a 128-bit resource descriptor in
-// SGPRs (base, size), a per-thread byte offset in one VGPR that does not change
-// over the contraction loop, and the loop's advance in an SGPR.  Reads past the
-// end of the tensor return zero, so a masked-out row is just an offset beyond
-// the end (kOutside) and ragged tails need no branches or address arithmetic.
-
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-constexpr uint32_t kOutside = 0x80000000u;   // tensors are < 2 GiB (checked on the host)
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset)
-{
-    // soffset is wave-uniform by construction; say so, or the compiler loops over its values
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, __builtin_amdgcn_readfirstlane((int)soffset), 0);
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-// Operand stored [k][col] (col contiguous).  64 x COLS tile; unit u = 4 k-rows
-// x 8 columns.
-template <int COLS, int NT>
-struct TransLoader {
-    static constexpr int CH = COLS / 8;
-    static constexpr int PER = 16 * CH / NT;
-    static_assert(16 * CH % NT == 0 && PER >= 1, "tile/thread mismatch");
-    typedef uint4 Regs[PER][4];
-
-    // Neighbouring lanes take the two k-quads that share a 16-byte LDS slot, so that their 8-byte
-    // writes fill whole slots and 16 lanes cover 8 distinct slots (no bank conflicts).
-    __device__ __forceinline__ static int chunk(int j) { return ((threadIdx.x + j * NT) >> 1) % CH; }
-    __device__ __forceinline__ static int kquad(int j)
-    {
-        const int u = threadIdx.x + j * NT;
-        return ((u >> 1) / CH) * 2 + (u & 1);
-    }
-
-    // voff(j, i) -> byte offset of the 8 columns of k-row kquad(j)*4+i (or kOutside)
-    template <typename Off>
-    __device__ __forceinline__ static void load(Regs &regs, __amdgpu_buffer_rsrc_t rsrc, Off voff, uint32_t soffset)
-    {
-#pragma unroll
-        for (int j = 0; j < PER; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) regs[j][i] = buffer_load16(rsrc, voff(j, i), soffset);
-    }
-
-    __device__ __forceinline__ static void put(unsigned char *tile, int j, int c, uint32_t d0, uint32_t d1)
-    {
-        const int row = chunk(j) * 8 + c;
-        const int kq = kquad(j);
-        *reinterpret_cast<uint2 *>(tile + lds_off(row, kq >> 1) + (kq & 1) * 8) = make_uint2(d0, d1);
-    }
-
-    // plain transpose
-    __device__ __forceinline__ static void store(const Regs &regs, unsigned char *tile)
-    {
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            const uint32_t *r0 = reinterpret_cast<const uint32_t *>(&regs[j][0]);
-            const uint32_t *r1 = reinterpret_cast<const uint32_t *>(&regs[j][1]);
-            const uint32_t *r2 = reinterpret_cast<const uint32_t *>(&regs[j][2]);
-            const uint32_t *r3 = reinterpret_cast<const uint32_t *>(&regs[j][3]);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                // even column: low halves; odd column: high halves
-                put(tile, j, 2 * d, __builtin_amdgcn_perm(r1[d], r0[d], 0x05040100u),
-                    __builtin_amdgcn_perm(r3[d], r2[d], 0x05040100u));
-                put(tile, j, 2 * d + 1, __builtin_amdgcn_perm(r1[d], r0[d], 0x07060302u),
-                    __builtin_amdgcn_perm(r3[d], r2[d], 0x07060302u));
-            }
-        }
-    }
-
-    // transpose with k-row i multiplied by s[i] (fp32 multiply, one bf16 rounding); PER == 1
-    __device__ __forceinline__ static void store_scaled(const Regs &regs, unsigned char *tile, const float (&s)[4])
-    {
-        static_assert(PER == 1, "scaled store handles one unit per thread");
-        const uint32_t *r0 = reinterpret_cast<const uint32_t *>(&regs[0][0]);
-        const uint32_t *r1 = reinterpret_cast<const uint32_t *>(&regs[0][1]);
-        const uint32_t *r2 = reinterpret_cast<const uint32_t *>(&regs[0][2]);
-        const uint32_t *r3 = reinterpret_cast<const uint32_t *>(&regs[0][3]);
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            put(tile, 0, 2 * d, pack_bf16(bf16_lo(r0[d]) * s[0], bf16_lo(r1[d]) * s[1]),
-                pack_bf16(bf16_lo(r2[d]) * s[2], bf16_lo(r3[d]) * s[3]));
-            put(tile, 0, 2 * d + 1, pack_bf16(bf16_hi(r0[d]) * s[0], bf16_hi(r1[d]) * s[1]),
-                pack_bf16(bf16_hi(r2[d]) * s[2], bf16_hi(r3[d]) * s[3]));
-        }
-    }
-};
-
-// ------------------------------------------------------------ MFMA core
-
-template <int TM, int TN>
-__device__ __forceinline__ void mma_tile(const unsigned char *tileA, const unsigned char *tileB, int rowA0,
-                                         int rowB0, f32x16 (&acc)[TM][TN])
-{
-    const int lane = threadIdx.x & 63;
-    const int r = lane & 31, h = lane >> 5;
-    constexpr int KS = BK / 16;
-    // all fragment reads of the step are issued before the first MFMA, so only the first one's
-    // LDS latency is exposed
-    bf16x8 a[KS][TM], b[KS][TN];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            a[ks][i] = *reinterpret_cast<const bf16x8 *>(tileA + lds_off(rowA0 + i * 32 + r, ks * 2 + h));
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-            b[ks][i] = *reinterpret_cast<const bf16x8 *>(tileB + lds_off(rowB0 + i * 32 + r, ks * 2 + h));
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
-}
-
-// The instruction mix of one pipeline phase, spelled out for the scheduler (it
-// would otherwise sink every LDS read next to its MFMA and run global loads,
-// matrix work and LDS staging one after the other): global loads first, the
-// fragment reads of two k-slices, then each MFMA followed by one instruction of
-// the staging work (transposing VALU op or LDS write), with the fragment reads
-// of the slice after next in each slice's shadow.  Counts that exceed what the
-// region holds are harmless.
-template <int TM, int TN, int VMEM, int VALU, int DSW, int ID>
-__device__ __forceinline__ void schedule_phase()
-{
-    constexpr int KS = BK / 16, RD = TM + TN, MM = TM * TN, TOTAL = KS * MM;
-    constexpr int VALU_PER = (VALU + TOTAL - 1) / TOTAL, DSW_PER = (DSW + TOTAL - 1) / TOTAL;
-    __builtin_amdgcn_sched_group_barrier(0x020, VMEM, ID);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, ID);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int m = 0; m < MM; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
-            if (VALU_PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, ID);
-            if (DSW_PER > 0) __builtin_amdgcn_sched_group_barrier(0x200, DSW_PER, ID);
-        }
-        if (ks + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, RD, ID);
-    }
-}
-
-// Row of the 32x32 accumulator block that register v of this lane holds;
-// the column is lane % 32.
-__device__ __forceinline__ int acc_row(int v) { return (v >> 2) * 8 + ((threadIdx.x & 63) >> 5) * 4 + (v & 3); }
-
-// XCD-aware tile order: consecutive workgroup ids land on different XCDs
-// (id mod 8), so hand each XCD one contiguous run of tiles; neighbours in the
-// run share operand rows through that XCD's L2.
-__device__ __forceinline__ int xcd_remap(int id, int total)
-{
-    const int per = (total + 7) / 8;
-    return (id & 7) * per + (id >> 3);
-}
-
-// The same with the panel width chosen at run time.
-__device__ __forceinline__ void panel_order_rt(int tile, int tiles_m, int tiles_n, int panel_w, int &tile_m,
-                                               int &tile_n)
-{
-    const int panel = tile / (tiles_m * panel_w);
-    const int in_panel = tile - panel * tiles_m * panel_w;
-    const int width = min(panel_w, tiles_n - panel * panel_w);
-    tile_m = in_panel / width;
-    tile_n = panel * panel_w + in_panel % width;
-}
-
-// Tile number -> (row tile, column tile), column panels of PANEL tiles, row-major inside a panel.
-template <int PANEL>
-__device__ __forceinline__ void panel_order(int tile, int tiles_m, int tiles_n, int &tile_m, int &tile_n)
-{
-    const int panel = tile / (tiles_m * PANEL);
-    const int in_panel = tile - panel * tiles_m * PANEL;
-    const int width = min(PANEL, tiles_n - panel * PANEL);
-    tile_m = in_panel / width;
-    tile_n = panel * PANEL + in_panel % width;
-}
 
 // The j-th sample (0-based) that is NOT in the ascending list idx[0..cnt).
 __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
@@ -243,59 +26,6 @@ __device__ __forceinline__ int nth_missing(const int32_t *idx, int cnt, int j)
         else lo = mid + 1;
     }
     return j + lo;
-}
-
-// ------------------------------------------------- register-staged pipeline
-
-// Software pipeline of the weight-gradient kernel.  Two register sets and two LDS
-// buffers: while step s is on the matrix cores, the loads of step s+1 are
-// landing in one register set and the loads of step s+2 are being issued into
-// the other, so a global load has about one and a half steps to arrive.
-//   load(set, s)   issue the global loads of step s into register set `set`
-//   stage(set, b)  write register set `set` (transposed / scaled) to LDS buffer b
-//   compute(b)     MFMA over LDS buffer b
-template <typename Load, typename Stage, typename Compute, typename Schedule>
-__device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Compute compute, Schedule schedule)
-{
-    if (steps <= 0) return;
-    load(0, 0);
-    if (steps > 1) load(1, 1);
-    stage(0, 0);
-    __syncthreads();
-    // Steady state without conditions inside: LDS buffer 0 holds step s, register set 1 holds
-    // step s+1 (landed or about to).  One phase = issue the loads of step s+2 into the free
-    // set, run the MFMAs of step s and, interleaved with them, move step s+1 from its register
-    // set into the other LDS buffer.
-    int s = 0;
-    for (; s + 3 < steps; s += 2) {
-        load(0, s + 2);
-        compute(0);
-        stage(1, 1);
-        schedule(std::integral_constant<int, 0>());
-        __builtin_amdgcn_sched_barrier(0);   // nothing moves across the phase boundary
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        load(1, s + 3);
-        compute(1);
-        stage(0, 0);
-        schedule(std::integral_constant<int, 1>());
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    const int left = steps - s;   // 1, 2 or 3
-    if (left == 3) load(0, s + 2);
-    compute(0);
-    if (left >= 2) {
-        stage(1, 1);
-        __syncthreads();
-        compute(1);
-        if (left == 3) {
-            stage(0, 0);
-            __syncthreads();
-            compute(0);
-        }
-    }
 }
 
 // ------------------------------------------------------------------ dgrad
@@ -311,39 +41,6 @@ __device__ __forceinline__ void pipeline(int steps, Load load, Stage stage, Comp
 // barrier per step: before it every wavefront waits until its own loads of the
 // step have landed (s_waitcnt vmcnt, the counter is in order), after it the
 // stage computed in the previous step is free.
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) int i32x4;
-
-// slot XOR of W-tile row k: the four k rows that a half-wave transposes at once land in four
-// different 64-byte bank groups
-__device__ __forceinline__ int wswz(int k) { return (k & 3) * 4; }
-
-// 128-bit buffer descriptor built by hand (base, stride 0, size in bytes, raw dword format) for
-// use in inline assembly.
-__device__ __forceinline__ i32x4 raw_descriptor(const void *base, uint32_t bytes)
-{
-    const uint64_t b = reinterpret_cast<uint64_t>(base);
-    i32x4 d;
-    d[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-    d[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xffffu));
-    d[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-    d[3] = 0x00020000;
-    return d;
-}
-
-// One LDS-direct load: every lane fetches 16 bytes at buffer offset voffset + soffset, the
-// wavefront's 1 KiB lands at LDS byte address lds_base (wave-uniform) in lane order.  Written as
-// assembly so that the compiler does not track it: it would otherwise make every later LDS read
-// wait for ALL loads in flight (it cannot tell the stages apart), and the waits are placed by
-// hand before the barrier anyway.
-__device__ __forceinline__ void lds_direct_load16(i32x4 desc, uint32_t lds_base, uint32_t voffset, uint32_t soffset)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
-                 : "memory", "m0");
-}
-
 template <int N>
 __device__ __forceinline__ void wait_loads_outstanding()
 {
@@ -662,502 +359,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_group_kernel(Dgra
                                              fill_dropped, q.sa);
 }
 
-// ------------------------------------------------------------------ wgrad
-
-// How many of the launched split-K slices do work for a given number of
-// contraction steps, and how many steps each takes.  Used by the GEMM and by
-// the reduction so that both agree.
-__host__ __device__ inline int wgrad_active_splits(int steps_all, int splits, int min_steps, int &per)
-{
-    int active = splits < steps_all / min_steps ? splits : steps_all / min_steps;
-    if (active < 1) active = 1;
-    per = (steps_all + active - 1) / active;
-    if (per < 1) per = 1;
-    active = (steps_all + per - 1) / per;
-    return active < 1 ? 1 : active;
-}
-
-// dW = partial[0] + partial[1] + ... in that order; does nothing when only one
-// split was active (the GEMM wrote dW itself).  `step` is the GEMM's
-// contraction step in tokens.
-__device__ __forceinline__ void splitk_reduce_body(const float *__restrict__ partials,
-                                                   const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                   int64_t R, int64_t elems, int splits, int min_steps, int step)
-{
-    const int64_t cnt = min((int64_t)max(*cntW, 0), R);
-    int per;
-    const int active = wgrad_active_splits((int)((cnt + step - 1) / step), splits, min_steps, per);
-    if (active == 1) return;
-    for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < elems; i += (int64_t)gridDim.x * 1024) {
-        float4 t[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            t[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s < active) t[s] = *reinterpret_cast<const float4 *>(partials + s * elems + i);
-        }
-        float4 sum = t[0];
-#pragma unroll
-        for (int s = 1; s < 8; ++s) {
-            sum.x += t[s].x;
-            sum.y += t[s].y;
-            sum.z += t[s].z;
-            sum.w += t[s].w;
-        }
-        *reinterpret_cast<float4 *>(dW + i) = sum;
-    }
-}
-
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partials,
-                                                            const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                            int64_t R, int64_t elems, int splits, int min_steps,
-                                                            int step)
-{
-    splitk_reduce_body(partials, cntW, dW, R, elems, splits, min_steps, step);
-}
-
-// the same for several layers of one shape: blockIdx.y picks the layer
-__global__ __launch_bounds__(256) void splitk_reduce_group_kernel(WgradGroup grp, int64_t R, int64_t elems, int splits,
-                                                                  int min_steps, int step)
-{
-    const WgradProblem &q = grp.prob[blockIdx.y];
-    splitk_reduce_body(q.partials, q.cntW, q.dW, R, elems, splits, min_steps, step);
-}
-
-static vcas_status splitk_reduce_group(const WgradGroup &grp, int n, int64_t R, int64_t elems, int splits,
-                                       int min_steps, int step, hipStream_t st)
-{
-    if (splits <= 1) return VCAS_OK;
-    int64_t blocks = (elems / 4 + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_reduce_group_kernel, dim3((unsigned)blocks, (unsigned)n), dim3(256), 0, st, grp, R, elems,
-                       splits, min_steps, step);
-    return launch_status();
-}
-
-vcas_status splitk_reduce(const float *partials, const int32_t *cntW, float *dW, int64_t R, int64_t elems, int splits,
-                          int min_steps, int step, hipStream_t st)
-{
-    if (splits <= 1) return VCAS_OK;
-    int64_t blocks = (elems / 4 + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, partials, cntW, dW, R, elems,
-                       splits, min_steps, step);
-    return launch_status();
-}
-
-// grid: 1-D, splits * tiles workgroups (rounded up to a multiple of 8), split-
-// major, so that the workgroups one XCD gets (a contiguous run after the remap)
-// contract the same tokens and share those G and X rows in its L2.  Split s of
-// a tile contracts a contiguous run of 64-token steps.  The number of active
-// splits is derived from the device-side count (wgrad_active_splits).  With one
-// active split the tile goes straight to dW; otherwise the partial tiles go to
-// `partials` [split][K_out][K_in] and splitk_reduce_kernel adds them in split
-// order, so the sum order is fixed.  (An in-kernel "last workgroup reduces"
-// scheme was measured first: its device-scope fences write back the XCD's L2
-// and cost more than the second launch.)
-template <int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void wgrad_bf16_body(const uint16_t *__restrict__ G, const uint16_t *__restrict__ X,
-                                                const float *__restrict__ row_scale,
-                                                const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW,
-                                                float *__restrict__ dW, float *__restrict__ partials, int64_t R,
-                                                int K_in, int K_out, int tiles_n, int tiles, int splits,
-                                                int min_steps)
-{
-    constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto tA = [&](int buf) { return smem + buf * (BM * 128); };
-    auto tB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
-    const int total = tiles * splits;
-    const int id = xcd_remap(blockIdx.x, total);
-    if (id >= total) return;
-    const int split = id / tiles, tile = id % tiles;
-    int tile_o, tile_c;   // panels of 4 column tiles: an XCD's ~32-64 workgroups cover a squarish patch of dW
-    panel_order<4>(tile, tiles / tiles_n, tiles_n, tile_o, tile_c);
-    const int o0 = tile_o * BM, c0 = tile_c * BN;
-
-    const int64_t cnt = min((int64_t)max(*cntW, 0), R);
-    const int steps_all = (int)((cnt + BK - 1) / BK);
-    int per;
-    const int active = wgrad_active_splits(steps_all, splits, min_steps, per);
-    if (split >= active) return;
-    const int s_begin = split * per, s_end = min(steps_all, s_begin + per);
-
-    typedef TransLoader<BM, NT> LA;
-    typedef TransLoader<BN, NT> LB;
-    static_assert(LA::PER == 1 && LB::PER == 1 && BM == BN, "one unit per thread, square tile assumed");
-    const int kq = LA::kquad(0);
-    const int cola = o0 + LA::chunk(0) * 8, colb = c0 + LB::chunk(0) * 8;
-    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
-    const __amdgpu_buffer_rsrc_t rsrcX = make_rsrc(X, (uint32_t)(R * K_in * 2));
-    typename LA::Regs ra[2];
-    typename LB::Regs rb[2];
-    float scale_of_set[2][4];   // per-token scales of the step held in the register set of the same index
-
-    // Token indices and scales run two resp. one step ahead of the tile loads, and each small
-    // load is issued BEFORE the 16 tile loads of its phase: the memory counter is in-order, so
-    // waiting for an index then leaves the younger tile loads in flight.
-    const __amdgpu_buffer_rsrc_t rsrcI = make_rsrc(idxW, (uint32_t)(R * 4));
-    const __amdgpu_buffer_rsrc_t rsrcS = make_rsrc(row_scale, (uint32_t)(R * 4));
-    const int64_t k_end = min(cnt, (int64_t)s_end * BK);
-    struct Tokens {
-        int32_t tok[4];   // row of G / X, or -1
-    };
-    // this thread's column chunk lies inside G resp. X (only ragged edge tiles have chunks outside)
-    const bool a_inside = cola < K_out, b_inside = colb < K_in;
-    const uint32_t g_pitch = (uint32_t)K_out * 2u, x_pitch = (uint32_t)K_in * 2u;   // row bytes, < 2^15
-    auto fetch_tokens = [&](int step) {
-        const int64_t k0 = (int64_t)(s_begin + step) * BK + kq * 4;
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcI, k0 < k_end ? (int)(k0 * 4) : (int)kOutside, 0, 0);
-        Tokens t;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int32_t r = (int32_t)v[i];
-            t.tok[i] = (k0 + i < k_end && (uint32_t)r < (uint32_t)R) ? r : -1;
-        }
-        return t;
-    };
-    auto fetch_scales = [&](const Tokens &t, float (&sc)[4]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            sc[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                  rsrcS, t.tok[i] >= 0 ? t.tok[i] * 4 : (int)kOutside, 0, 0));
-    };
-
-    const int wave = threadIdx.x >> 6;
-    const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    Tokens tok_cur = fetch_tokens(0), tok_next = fetch_tokens(1);
-    float sc_cur[4];
-    fetch_scales(tok_cur, sc_cur);
-    auto load = [&](int set, int s) {
-        // steps are loaded in order: tok_cur / sc_cur belong to step s, tok_next to step s + 1
-        float sc_next[4];
-        fetch_scales(tok_next, sc_next);
-        const Tokens tok_after = fetch_tokens(s + 2);
-        const Tokens q = tok_cur;
-        // rows < 2^24 and row bytes < 2^15 (checked on the host): 24-bit multiplies are exact and full rate
-        auto g_voff = [&](int, int i) {
-            return (q.tok[i] >= 0 && a_inside) ? __umul24((uint32_t)q.tok[i], g_pitch) + (uint32_t)cola * 2u : kOutside;
-        };
-        auto x_voff = [&](int, int i) {
-            return (q.tok[i] >= 0 && b_inside) ? __umul24((uint32_t)q.tok[i], x_pitch) + (uint32_t)colb * 2u : kOutside;
-        };
-        if (set == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) scale_of_set[0][i] = sc_cur[i];
-            LA::load(ra[0], rsrcG, g_voff, 0u);
-            LB::load(rb[0], rsrcX, x_voff, 0u);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) scale_of_set[1][i] = sc_cur[i];
-            LA::load(ra[1], rsrcG, g_voff, 0u);
-            LB::load(rb[1], rsrcX, x_voff, 0u);
-        }
-        tok_cur = tok_next;
-        tok_next = tok_after;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sc_cur[i] = sc_next[i];
-    };
-    auto stage = [&](int set, int buf) {
-        if (set == 0) {
-            LA::store_scaled(ra[0], tA(buf), scale_of_set[0]);
-            LB::store(rb[0], tB(buf));
-        } else {
-            LA::store_scaled(ra[1], tA(buf), scale_of_set[1]);
-            LB::store(rb[1], tB(buf));
-        }
-    };
-    auto compute_step = [&](int buf) { mma_tile<TM, TN>(tA(buf), tB(buf), wm0, wn0, acc); };
-    // staging VALU per thread: G unit 40 (unpack, scale, pack), X unit 16 (byte permutes), a few for the token fetch
-    auto schedule = [&](auto id) { schedule_phase<TM, TN, 8 + 5, 64, 16, decltype(id)::value>(); };
-    pipeline(s_end - s_begin, load, stage, compute_step, schedule);
-
-    const int lane = threadIdx.x & 63;
-    float *dst = active == 1 ? dW : partials + (int64_t)split * K_out * K_in;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int o = o0 + wm0 + i * 32 + acc_row(v);
-            if (o >= K_out) continue;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int c = c0 + wn0 + j * 32 + (lane & 31);
-                if (c < K_in) dst[(int64_t)o * K_in + c] = acc[i][j][v];
-            }
-        }
-}
-
-template <int BM, int BN, int WM, int WN, int OCC>
-__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_kernel(const uint16_t *__restrict__ G,
-                                                                  const uint16_t *__restrict__ X,
-                                                                  const float *__restrict__ row_scale,
-                                                                  const int32_t *__restrict__ idxW,
-                                                                  const int32_t *__restrict__ cntW, float *__restrict__ dW,
-                                                                  float *__restrict__ partials, int64_t R, int K_in,
-                                                                  int K_out, int tiles_n, int tiles, int splits,
-                                                                  int min_steps)
-{
-    wgrad_bf16_body<BM, BN, WM, WN>(G, X, row_scale, idxW, cntW, dW, partials, R, K_in, K_out, tiles_n, tiles, splits,
-                                    min_steps);
-}
-
-// Several layers of one shape (siblings) in one launch: blockIdx.y picks the layer.
-template <int BM, int BN, int WM, int WN, int OCC>
-__global__ __launch_bounds__(WM *WN * 64, OCC) void wgrad_bf16_group_kernel(WgradGroup grp, int64_t R, int K_in,
-                                                                        int K_out, int tiles_n, int tiles,
-                                                                        int splits, int min_steps)
-{
-    const WgradProblem &q = grp.prob[blockIdx.y];
-    wgrad_bf16_body<BM, BN, WM, WN>(q.G, q.X, q.row_scale, q.idxW, q.cntW, q.dW, q.partials, R, K_in, K_out, tiles_n,
-                                    tiles, splits, min_steps);
-}
-
-// The 128x128 weight-gradient kernel for layers with many kept tokens.  Same split-K protocol
-// and epilogue as above, different data path: X goes straight into LDS (LDS-direct loads, as in
-// dgrad), G passes through registers only to be multiplied by the per-token scale and is written
-// as it came, 16 bytes per lane; both tiles lie in LDS as [64 tokens][128 columns] with the
-// 16-byte slots swizzled by wswz, and both MFMA operands are transposed on the way out by
-// ds_read_b64_tr_b16.  No v_perm transposes, half the staging registers.  A thread handles four
-// consecutive kept tokens (one 16-byte index load); they occupy LDS rows 4 apart, which is fine
-// because both tiles use the same row order and the contraction does not care about it.
-template <int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void wgrad_bf16_dma_body(
-    const uint16_t *__restrict__ G, const uint16_t *__restrict__ X, const float *__restrict__ row_scale,
-    const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW, float *__restrict__ dW,
-    float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles, int splits, int min_steps)
-{
-    static_assert(BM == 128 && BN == 128 && WM * WN == 4, "four wavefronts, 16 slots per tile row");
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_TILE = BK * BM * 2, STAGE = A_TILE + BK * BN * 2, PITCH = 256;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int total = tiles * splits;
-    const int id = xcd_remap(blockIdx.x, total);
-    if (id >= total) return;
-    const int split = id / tiles, tile = id % tiles;
-    int tile_o, tile_c;
-    panel_order<4>(tile, tiles / tiles_n, tiles_n, tile_o, tile_c);
-    const int o0 = tile_o * BM, c0 = tile_c * BN;
-
-    const int64_t cnt = min((int64_t)max(*cntW, 0), R);
-    const int steps_all = (int)((cnt + BK - 1) / BK);
-    int per;
-    const int active = wgrad_active_splits(steps_all, splits, min_steps, per);
-    if (split >= active) return;
-    const int s_begin = split * per, s_end = min(steps_all, s_begin + per);
-    const int steps = s_end - s_begin;
-    const int64_t k_end = min(cnt, (int64_t)s_end * BK);
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, slot = lane & 15;        // row within a 4-row load, 16-byte slot
-    const int k_first = 16 * wave + 4 * grp;            // this thread's tokens of a step: k_first + j, j < 4
-    // token k_first + j lives in LDS row 16*wave + 4*j + grp
-    const __amdgpu_buffer_rsrc_t rsrcG = make_rsrc(G, (uint32_t)(R * K_out * 2));
-    const __amdgpu_buffer_rsrc_t rsrcI = make_rsrc(idxW, (uint32_t)(R * 4));
-    const __amdgpu_buffer_rsrc_t rsrcS = make_rsrc(row_scale, (uint32_t)(R * 4));
-    const i32x4 descX = raw_descriptor(X, (uint32_t)(R * K_in * 2));
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const uint32_t g_pitch = (uint32_t)K_out * 2u, x_pitch = (uint32_t)K_in * 2u;
-    const int g_col = o0 + slot * 8;
-    const bool g_inside = g_col < K_out;
-    // column piece of X that lands in LDS slot `slot` of row r: slot ^ wswz(r); r & 3 == grp for all four rows
-    const int x_col = c0 + ((slot ^ wswz(grp)) * 8);
-    const bool x_inside = x_col < K_in;
-
-    struct Tokens {
-        int32_t tok[4];
-    };
-    auto fetch_tokens = [&](int step) {
-        const int64_t k0 = (int64_t)(s_begin + step) * BK + k_first;
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcI, k0 < k_end ? (int)(k0 * 4) : (int)kOutside, 0, 0);
-        Tokens t;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int32_t r = (int32_t)v[j];
-            t.tok[j] = (k0 + j < k_end && (uint32_t)r < (uint32_t)R) ? r : -1;
-        }
-        return t;
-    };
-    auto fetch_scales = [&](const Tokens &t, float (&sc)[4]) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            sc[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                  rsrcS, t.tok[j] >= 0 ? t.tok[j] * 4 : (int)kOutside, 0, 0));
-    };
-    uint4 g_regs[4];
-    auto load_g = [&](const Tokens &t) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            g_regs[j] = buffer_load16(rsrcG, (t.tok[j] >= 0 && g_inside)
-                                                 ? __umul24((uint32_t)t.tok[j], g_pitch) + (uint32_t)g_col * 2u
-                                                 : kOutside, 0u);
-    };
-    auto issue_x = [&](int stage, const Tokens &t) {
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + A_TILE + wave * 16 * PITCH);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            lds_direct_load16(descX, dst + j * 4 * PITCH,
-                              (t.tok[j] >= 0 && x_inside) ? __umul24((uint32_t)t.tok[j], x_pitch) + (uint32_t)x_col * 2u
-                                                          : kOutside, 0u);
-    };
-    auto stage_g = [&](int stage, const float (&sc)[4]) {
-        unsigned char *tileA = smem + stage * STAGE;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = 16 * wave + 4 * j + grp;
-            const uint32_t *r = reinterpret_cast<const uint32_t *>(&g_regs[j]);
-            uint4 o;
-            o.x = pack_bf16(bf16_lo(r[0]) * sc[j], bf16_hi(r[0]) * sc[j]);
-            o.y = pack_bf16(bf16_lo(r[1]) * sc[j], bf16_hi(r[1]) * sc[j]);
-            o.z = pack_bf16(bf16_lo(r[2]) * sc[j], bf16_hi(r[2]) * sc[j]);
-            o.w = pack_bf16(bf16_lo(r[3]) * sc[j], bf16_hi(r[3]) * sc[j]);
-            *reinterpret_cast<uint4 *>(tileA + row * PITCH + ((slot ^ wswz(row)) << 4)) = o;
-        }
-    };
-
-    const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    const int blk = lane >> 4, sl = lane & 15;
-    // fragment of 32 columns x 16 tokens of a [64][128] tile: two transposing reads
-    auto frag = [&](const unsigned char *t, int col0, int ks) {
-        bf16x4 half[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int k = ks * 16 + (blk >> 1) * 8 + e * 4 + (sl >> 2);
-            const int col = col0 + (blk & 1) * 16 + (sl & 3) * 4;
-            const unsigned char *src = t + k * PITCH + (((col >> 3) ^ wswz(k)) << 4) + (col & 7) * 2;
-            half[e] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(src));
-        }
-        return __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
-    };
-    auto compute = [&](int stage) {
-        const unsigned char *tileA = smem + stage * STAGE;
-        const unsigned char *tileB = tileA + A_TILE;
-        constexpr int KS = BK / 16;
-        bf16x8 a[KS][TM], b[KS][TN];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[ks][i] = frag(tileA, wm0 + i * 32, ks);
-#pragma unroll
-            for (int i = 0; i < TN; ++i) b[ks][i] = frag(tileB, wn0 + i * 32, ks);
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
-        // fragment reads of two k-slices, then each slice's MFMAs with the reads of the slice after next
-        constexpr int RD = 2 * (TM + TN), MM = TM * TN;
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, 0);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
-            if (ks + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-        }
-    };
-
-    // prologue: step 0 into stage 0, tokens of step 1 known
-    Tokens tok_cur = fetch_tokens(0), tok_next = fetch_tokens(1);
-    float sc_cur[4];
-    fetch_scales(tok_cur, sc_cur);
-    load_g(tok_cur);
-    issue_x(0, tok_cur);
-    stage_g(0, sc_cur);
-    for (int s = 0; s < steps; ++s) {
-        wait_loads_outstanding<0>();          // this wavefront's part of X(s) has landed
-        asm volatile("" ::: "memory");
-        __syncthreads();                       // tile s complete; tile s-1 no longer read
-        __builtin_amdgcn_sched_barrier(0);
-        // step s+1 on its way while step s is on the matrix cores (past the end: zeros); the
-        // scaled G(s+1) goes to LDS once the MFMAs of the step are issued
-        const Tokens tok_after = fetch_tokens(s + 2);
-        float sc_next[4];
-        fetch_scales(tok_next, sc_next);
-        load_g(tok_next);
-        issue_x((s + 1) & 1, tok_next);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(s & 1);
-        __builtin_amdgcn_sched_barrier(0);
-        stage_g((s + 1) & 1, sc_next);
-        tok_next = tok_after;
-    }
-    wait_loads_outstanding<0>();
-
-    const int lane32 = lane & 31;
-    float *dst = active == 1 ? dW : partials + (int64_t)split * K_out * K_in;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int o = o0 + wm0 + i * 32 + acc_row(v);
-            if (o >= K_out) continue;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int c = c0 + wn0 + j * 32 + lane32;
-                if (c < K_in) dst[(int64_t)o * K_in + c] = acc[i][j][v];
-            }
-        }
-}
-
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_kernel(
-    const uint16_t *__restrict__ G, const uint16_t *__restrict__ X, const float *__restrict__ row_scale,
-    const int32_t *__restrict__ idxW, const int32_t *__restrict__ cntW, float *__restrict__ dW,
-    float *__restrict__ partials, int64_t R, int K_in, int K_out, int tiles_n, int tiles, int splits, int min_steps)
-{
-    wgrad_bf16_dma_body<BM, BN, WM, WN>(G, X, row_scale, idxW, cntW, dW, partials, R, K_in, K_out, tiles_n, tiles,
-                                        splits, min_steps);
-}
-
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64, 2) void wgrad_bf16_dma_group_kernel(WgradGroup grp, int64_t R, int K_in,
-                                                                          int K_out, int tiles_n, int tiles,
-                                                                          int splits, int min_steps)
-{
-    const WgradProblem &q = grp.prob[blockIdx.y];
-    wgrad_bf16_dma_body<BM, BN, WM, WN>(q.G, q.X, q.row_scale, q.idxW, q.cntW, q.dW, q.partials, R, K_in, K_out,
-                                        tiles_n, tiles, splits, min_steps);
-}
-
 // ---------------------------------------------------------- host launchers
-
-// Tile edge of the bf16 weight-gradient GEMM: 128, unless dW has so few 128x128 tiles that filling
-// the chip takes many split-K slices, whose fp32 partial tiles then cost more HBM traffic than
-// the operands (BERT-base: 3 to 8 slices, partials 2 to 4 times dW), and few enough tokens are
-// expected that the matrix cores are not the limit: then 64x64 tiles, four times as many, with a
-// quarter of the slices (1000 kept tokens, 768x3072: 24 vs 28 us and no partials at all).  Up to
-// 1024 expected tokens: at 1900 (ViT-B/16) the 128x128 kernel is ahead again (step 3.67 -> 3.53 ms).
-int wgrad_tile_bf16(int K_out, int K_in, int64_t expected_tokens)
-{
-    const int tiles128 = ((K_out + 127) / 128) * ((K_in + 127) / 128);
-    return tiles128 <= 160 && expected_tokens <= 1024 ? 64 : 128;
-}
-
-int wgrad_tiles_bf16(int K_out, int K_in, int tile) { return ((K_out + tile - 1) / tile) * ((K_in + tile - 1) / tile); }
-
-template <typename Kern>
-static bool allow_lds(Kern kern, size_t bytes)
-{
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)bytes) == hipSuccess;
-}
 
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
@@ -1260,100 +462,6 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
     return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
-}
-
-template <int BM, int BN, int WM, int WN, int OCC>
-static vcas_status launch_wgrad(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                                const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int splits,
-                                hipStream_t st)
-{
-    constexpr int MIN_STEPS = 2;
-    const int64_t R = (int64_t)s.N * s.T;
-    const int tiles_n = (s.K_in + BN - 1) / BN;
-    const int tiles = ((s.K_out + BM - 1) / BM) * tiles_n;
-    if (splits > 8) splits = 8;
-    const size_t lds = 2 * (BM + BN) * 128;
-    auto kern = wgrad_bf16_kernel<BM, BN, WM, WN, OCC>;
-    static bool allowed = false;
-    if (!allowed) {
-        if (!allow_lds(kern, lds)) return VCAS_EHIP;
-        allowed = true;
-    }
-    const int grid = (tiles * splits + 7) / 8 * 8;
-    launch_timed(1, kern, dim3(grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
-                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
-                 tiles, splits, MIN_STEPS);
-    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
-    return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
-}
-
-static vcas_status launch_wgrad_dma(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                                    const int32_t *idxW, const int32_t *cntW, float *dW, float *partials,
-                                    int splits, hipStream_t st)
-{
-    constexpr int BM = 128, BN = 128, MIN_STEPS = 2;
-    const int64_t R = (int64_t)s.N * s.T;
-    const int tiles_n = (s.K_in + BN - 1) / BN;
-    const int tiles = ((s.K_out + BM - 1) / BM) * tiles_n;
-    if (splits > 8) splits = 8;
-    const size_t lds = 2 * (BM + BN) * 128;
-    auto kern = wgrad_bf16_dma_kernel<BM, BN, 2, 2>;
-    static bool allowed = false;
-    if (!allowed) {
-        if (!allow_lds(kern, lds)) return VCAS_EHIP;
-        allowed = true;
-    }
-    const int grid = (tiles * splits + 7) / 8 * 8;
-    launch_timed(1, kern, dim3(grid), dim3(256), lds, st, static_cast<const uint16_t *>(G),
-                 static_cast<const uint16_t *>(X), row_scale, idxW, cntW, dW, partials, R, s.K_in, s.K_out, tiles_n,
-                 tiles, splits, MIN_STEPS);
-    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
-    return splitk_reduce(partials, cntW, dW, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
-}
-
-// wgrad of n <= kMaxSiblings layers of shape s in one launch, and one launch for their reductions:
-// tile and splits as for a layer on its own, so that every dW keeps its bits.
-vcas_status wgrad_bf16_group(const vcas_shape &s, const WgradProblem *probs, int n, int tile, int splits, hipStream_t st)
-{
-    if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
-    WgradGroup grp = {};
-    for (int i = 0; i < n; ++i) grp.prob[i] = probs[i];
-    constexpr int MIN_STEPS = 2;
-    const int64_t R = (int64_t)s.N * s.T;
-    const int tiles_n = (s.K_in + tile - 1) / tile;
-    const int tiles = ((s.K_out + tile - 1) / tile) * tiles_n;
-    if (splits > 8) splits = 8;
-    const size_t lds = 2 * (size_t)(tile + tile) * 128;
-    const int grid = (tiles * splits + 7) / 8 * 8;
-    if (tile == 64) {
-        auto kern = wgrad_bf16_group_kernel<64, 64, 2, 1, 2>;
-        static bool allowed = false;
-        if (!allowed) {
-            if (!allow_lds(kern, lds)) return VCAS_EHIP;
-            allowed = true;
-        }
-        launch_timed(1, kern, dim3(grid, n), dim3(128), lds, st, grp, R, s.K_in, s.K_out, tiles_n, tiles, splits, MIN_STEPS);
-    } else {
-        auto kern = wgrad_bf16_dma_group_kernel<128, 128, 2, 2>;
-        static bool allowed = false;
-        if (!allowed) {
-            if (!allow_lds(kern, lds)) return VCAS_EHIP;
-            allowed = true;
-        }
-        launch_timed(1, kern, dim3(grid, n), dim3(256), lds, st, grp, R, s.K_in, s.K_out, tiles_n, tiles, splits, MIN_STEPS);
-    }
-    if (hipGetLastError() != hipSuccess) return VCAS_EHIP;
-    return splitk_reduce_group(grp, n, R, (int64_t)s.K_out * s.K_in, splits, MIN_STEPS, BK, st);
-}
-
-// tile: 64 or 128 (wgrad_tile_bf16); splits: as sized by the caller for that tile
-vcas_status wgrad_bf16(const vcas_shape &s, const void *G, const void *X, const float *row_scale,
-                       const int32_t *idxW, const int32_t *cntW, float *dW, float *partials, int tile, int splits,
-                       hipStream_t st)
-{
-    if (tile == 64)
-        return launch_wgrad<64, 64, 2, 1, 2>(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
-    return launch_wgrad_dma(s, G, X, row_scale, idxW, cntW, dW, partials, splits, st);
 }
 
 }  // namespace vcas

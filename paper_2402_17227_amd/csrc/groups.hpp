@@ -30,15 +30,18 @@ struct SampleAGroup {
     InlineSampleA prob[kMaxSiblings];
 };
 
-// One layer of a grouped wgrad launch and of the split-K reduction behind it.
-struct WgradProblem {
-    const uint16_t *G, *X;
+// One layer of a batched bf16 weight-gradient launch (host view): the arguments of
+// vcas_sampled_wgrad, where its split-K partial tiles and its packed (gathered and pre-scaled)
+// narrower operand go, and how many slices its contraction is cut into.
+constexpr int kWgradBatch = 8;
+struct WgradItem {
+    vcas_shape shape;
+    const void *G, *X;
     const float *row_scale;
     const int32_t *idxW, *cntW;
     float *dW, *partials;
-};
-struct WgradGroup {
-    WgradProblem prob[kMaxSiblings];
+    uint16_t *packed;
+    int splits;
 };
 
 // One layer of a grouped SampleW launch: the pointer arguments of the one-workgroup sampler.
