@@ -115,12 +115,13 @@ vcas_status vcas_workspace_init(const vcas_shape *shape, void *workspace, void *
  *   xsq[t]   = sum_k X[t,k]^2, or 0 if sample_mask is given and the row's
  *              sample has mask 0        (required if X is given)
  * fp32, each row summed in a fixed order that does not depend on the launch:
- * 16-byte group j of the row goes to accumulator j mod 64, accumulators fold
- * with fused multiply-add in ascending k and are then combined neighbours
- * first: 64 -> 32 values by adding accumulators 2m and 2m+1, and so on at
- * distances 1, 2, 4, 8, 16, 32 (a balanced binary tree); gnorm likewise over
- * the T values of a sample (value t on accumulator t mod 64, plain adds, the
- * same tree, then a correctly rounded square root).
+ * pairwise, neighbours first.  The squares v*v (fp32 product of the element's
+ * fp32 image, one rounding), padded with +0 to the next power of two, are added
+ * as a balanced binary tree in index order: s[2m] + s[2m+1] first, then those
+ * results pairwise, and so on.  gnorm: value t of a sample on accumulator
+ * t mod 64, accumulators add their values in ascending t and are combined by
+ * the same kind of tree (2m with 2m+1, distances 1, 2, 4, 8, 16, 32), then a
+ * correctly rounded square root.
  */
 vcas_status vcas_row_norms(const vcas_shape *shape, const void *G, const void *X,
                            const uint8_t *sample_mask, float *gsq, float *xsq, float *gnorm,

@@ -125,22 +125,18 @@ float orc_uniform(uint64_t seed, uint32_t layer, uint32_t stream, uint32_t draw,
 /* ------------------------------------------------- norms (Sec. 4.1 / 4.2) */
 
 /*
- * fp32 sum in the written-down "64-lane" order: value j of the sequence goes
- * to accumulator (j / group) mod 64, accumulators fold their values in
- * ascending j, then six pairwise exchange steps (distance 1,2,4,...,32) add
- * accumulator l and l^distance, i.e. neighbours first.  `sq` selects
- * acc = fma(v,v,acc) or acc += v.
+ * fp32 sum in the written-down "64-lane" order (the per-sample sums): value j
+ * of the sequence goes to accumulator j mod 64, accumulators add their values
+ * in ascending j, then six pairwise exchange steps (distance 1,2,4,...,32) add
+ * accumulator l and l^distance, i.e. neighbours first.
  */
-static float lane_sum(const void *base, int dtype, size_t first, int count, int group, int sq)
+static float lane_sum(const float *v, int count)
 {
     float acc[64];
     for (int l = 0; l < 64; ++l)
         acc[l] = 0.0f;
-    for (int j = 0; j < count; ++j) {
-        int l = (j / group) % 64;
-        float v = elem(base, dtype, first + (size_t)j);
-        acc[l] = sq ? fmaf(v, v, acc[l]) : acc[l] + v;
-    }
+    for (int j = 0; j < count; ++j)
+        acc[j % 64] = acc[j % 64] + v[j];
     for (int dist = 1; dist <= 32; dist <<= 1) {
         float nxt[64];
         for (int l = 0; l < 64; ++l)
@@ -151,21 +147,49 @@ static float lane_sum(const void *base, int dtype, size_t first, int count, int 
 }
 
 /*
+ * Pairwise summation, neighbours first: the n values, padded with +0 to the
+ * next power of two, are added as a balanced binary tree in index order.
+ * v is overwritten; room for the padded length.
+ */
+static float pairwise_sum_f32(float *v, int n)
+{
+    int len = 1;
+    while (len < n)
+        len *= 2;
+    for (int j = n; j < len; ++j)
+        v[j] = 0.0f;
+    for (; len > 1; len /= 2)
+        for (int j = 0; j < len / 2; ++j)
+            v[j] = v[2 * j] + v[2 * j + 1];
+    return v[0];
+}
+
+/*
  * Squared 2-norm of every row t of A[R,K] (the ||g_t||^2 and ||x_t||^2 of
- * Eq. 3), fp32, lane order with 16-byte groups.  If sample_keep is given
- * (one byte per sample of T rows), rows of dropped samples get 0.
+ * Eq. 3, the row sums behind the ||G_i||_F of Sec. 4.1), fp32: the squares
+ * v*v (one rounding each) summed pairwise, neighbours first.  The paper fixes
+ * no order; this is the written-down one.  If sample_keep is given (one byte
+ * per sample of T rows), rows of dropped samples get 0.
  */
 void orc_row_sumsq(const void *A, int dtype, int64_t R, int K, int T,
                    const uint8_t *sample_keep, float *out)
 {
-    int group = dtype == ORC_BF16 ? 8 : 4;
+    int len = 1;
+    while (len < K)
+        len *= 2;
+    float *sq = (float *)malloc((size_t)len * sizeof(float));
     for (int64_t t = 0; t < R; ++t) {
         if (sample_keep && !sample_keep[t / T]) {
             out[t] = 0.0f;
             continue;
         }
-        out[t] = lane_sum(A, dtype, (size_t)t * K, K, group, 1);
+        for (int k = 0; k < K; ++k) {
+            float v = elem(A, dtype, (size_t)t * K + k);
+            sq[k] = v * v;
+        }
+        out[t] = pairwise_sum_f32(sq, K);
     }
+    free(sq);
 }
 
 /* The same quantity by its plain definition in fp64 (used to pin the above). */
@@ -185,7 +209,7 @@ void orc_row_sumsq_f64(const void *A, int dtype, int64_t R, int K, double *out)
 void orc_sample_norms(const float *gsq, int N, int T, float *gnorm)
 {
     for (int i = 0; i < N; ++i)
-        gnorm[i] = sqrtf(lane_sum(gsq, ORC_F32, (size_t)i * T, T, 1, 0));
+        gnorm[i] = sqrtf(lane_sum(gsq + (size_t)i * T, T));
 }
 
 /* --------------------------- keep probabilities (Sec. 4.1, Sec. 4.2) */

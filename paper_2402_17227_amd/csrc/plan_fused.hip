@@ -370,13 +370,8 @@ __global__ __launch_bounds__(kThreads) void plan_fused_kernel(PlanArgs a)
                 v0[j] = gidx < gr0 ? p0[gidx] : make_uint4(0u, 0u, 0u, 0u);
                 v1[j] = two && gidx < gr1 ? p1[gidx] : make_uint4(0u, 0u, 0u, 0u);
             }
-            acc0 = 0.0f;
-#pragma unroll
-            for (int j = 0; j < CH; ++j) acc0 = fold16<BF16>(v0[j], acc0);
-#pragma unroll
-            for (int j = 0; j < CH; ++j) acc1 = fold16<BF16>(v1[j], acc1);
-            acc0 = wave_exchange_sum(acc0);
-            acc1 = wave_exchange_sum(acc1);
+            acc0 = chunk_sumsq<BF16, CH>(v0, (gr0 + 63) / 64);
+            if (two) acc1 = chunk_sumsq<BF16, CH>(v1, (gr1 + 63) / 64);
         } else {
             acc0 = wave_row_sumsq<BF16, CH>(p0, gr0);
             if (two) acc1 = wave_row_sumsq<BF16, CH>(p1, gr1);

@@ -80,6 +80,25 @@ def test_row_sumsq_exact_on_small_integers(dtype):
     assert np.array_equal(got, (a.astype(np.int64) ** 2).sum(axis=1).astype(np.float32))
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_row_sumsq_adds_neighbours_first(dtype):
+    """The written-down order of the row sums (pairwise, neighbours first, zero-padded to a power of two),
+    on rows worked out by hand where any other order rounds differently.  Squares 2^24, 1, 1, 1: the pair
+    (2^24 + 1) rounds back to 2^24 (tie to even), the pair (1 + 1) = 2 survives, 2^24 + 2 is exact; adding one
+    element after the other, or one chain per 16-byte group, loses all three ones.  Twelve elements
+    (padded to sixteen): 2^24, then eleven ones: pairs 2^24, 2, 2, 2, 2, 2 | fours 2^24 + 2, 4, 4 (+0) |
+    eights 2^24 + 6, 4 | 2^24 + 10."""
+    def row(vals):
+        a = np.zeros((1, 16 if len(vals) > 8 else 8), np.float32)
+        a[0, :len(vals)] = vals
+        return workloads.f32_to_bf16_bits(a) if dtype == BF16 else a
+    assert oracle.row_sumsq(row([4096, 1, 1, 1]), dtype)[0] == np.float32(16777218.0)
+    assert oracle.row_sumsq(row([1, 1, 4096, 1]), dtype)[0] == np.float32(16777218.0)
+    assert oracle.row_sumsq(row([4096] + [1] * 11), dtype)[0] == np.float32(16777226.0)
+    # sixteen elements, the large one in the middle of the second half: 8 + ((2^24 + 2) + 4) = 2^24 + 14
+    assert oracle.row_sumsq(row([1] * 9 + [4096] + [1] * 6), dtype)[0] == np.float32(16777230.0)
+
+
 def test_row_sumsq_sample_mask_zeroes_dropped_samples():
     rng = np.random.default_rng(6)
     a = rng.standard_normal((12, 64)).astype(np.float32)
