@@ -305,6 +305,9 @@ def main():
                          "up's is o's, o's is the G of V, K and Q, Q's is the next block's down's), every layer is told "
                          "which samples the one above kept and leaves the rows of dropped samples unwritten; only the top "
                          "layer's G is an input")
+    ap.add_argument("--sweep-norms", action="store_true",
+                    help="with --chained: every layer sweeps its G for the row norms, as independent layers must, instead "
+                         "of taking them from the block sums of squares the dgrad above has left (the same bits)")
     ap.add_argument("--xsq-cached", action="store_true",
                     help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
                          "pass would, vcas_row_norms over every row) and handed to the weight halves; not the default, "
@@ -393,20 +396,26 @@ def main():
                 l.xsq_forward = torch.empty(l.spec.R, dtype=torch.float32, device="cuda")
                 vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
         entries, prev = [], None
+        fused_norms = args.chained and not args.sweep_norms
         for l in layers:
             sib = not args.no_siblings and _is_sibling(l.spec.name)
-            G, above = l.G, None
+            G, above, g_blocks = l.G, None, None
+            # chained: every dgrad also leaves the sums of squares of its dX by blocks of 32 columns, from
+            # which the entry below takes the norms of its G instead of sweeping it
+            l.sq_blocks = (torch.empty(((l.spec.K_in + 31) // 32, l.spec.R), dtype=torch.float32, device="cuda")
+                           if fused_norms else None)
             if args.chained and prev is not None:
                 # a sibling takes what its elder sibling took; everybody else the dX of the entry before
-                G, above = (prev_G, prev_above) if _is_sibling(l.spec.name) else (prev.dX, prev.plan.maskA)
+                G, above, g_blocks = ((prev_G, prev_above, prev_blocks) if _is_sibling(l.spec.name)
+                                      else (prev.dX, prev.plan.maskA, prev.sq_blocks))
                 assert G.shape == l.G.shape, (l.spec.name, G.shape, l.G.shape)
                 l.G = G
             entries.append(vb.layer_args(l.shape, G, l.X, l.W, l.spec.rho, l.spec.nu,
                                          vb.Rng(l.spec.seed, l.spec.layer, 0, draw_counter.data_ptr()), True,
                                          l.plan, l.dX, l.dW, l.ws, l.xsq_forward, sibling=sib,
                                          kept_above=above, leave_dropped_rows=args.chained,
-                                         wgrad_fill=args.wgrad_fill))
-            prev, prev_G, prev_above = l, G, above
+                                         wgrad_fill=args.wgrad_fill, dx_sq_blocks=l.sq_blocks, g_sq_blocks=g_blocks))
+            prev, prev_G, prev_above, prev_blocks = l, G, above, g_blocks
         stack = vb.make_stack(entries)
         s2, s3 = torch.cuda.Stream(), torch.cuda.Stream()
 
@@ -575,8 +584,9 @@ def main():
         "launch": (f"vcas_backward_stack from the host, groups of {args.stack} layers, SampleW and dW on two side streams"
                    + ("" if args.no_siblings else ", data halves of V, K, Q of a block in shared launches")
                    + f", weight gradients sliced for {args.wgrad_fill or 384} workgroups"
-                   + (", layers chained (each dX buffer is the next G, dropped samples stay dropped and unwritten)"
-                      if args.chained else "")
+                   + (", layers chained (each dX buffer is the next G, dropped samples stay dropped and unwritten"
+                      + (", row norms of G swept" if args.sweep_norms else ", row norms of G from the dgrad above")
+                      + ")" if args.chained else "")
                    + (", row norms of X cached before the timed region" if args.xsq_cached else "")
                    if stack is not None else
                    ("eager" if args.eager else "hip_graph") +

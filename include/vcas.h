@@ -181,6 +181,32 @@ vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const
                                    void *stream);
 
 /*
+ * The norms of a layer's incoming gradient from the launch that produced it.  In a
+ * stack of layers the G of a layer is the dX the layer above has just written
+ * (Sec. 4: samplers at every layer), and Sec. 4.1 needs ||G_i||_F of it; a second
+ * pass over HBM for those norms is avoided by letting the dgrad epilogue add up the
+ * squares of what it stores.
+ * vcas_sampled_dgrad_norms: vcas_sampled_dgrad_jac (J may be null: no Jacobian)
+ * that also writes, for every row r of a kept sample and every block b of 32
+ * columns, sq_blocks[b * R + r] = sum of squares of dX[r, 32 b .. 32 b + 31] as
+ * stored (after the rounding to bf16), b < nb = ceil(K_in / 32), block-major so
+ * that both sides touch neighbouring addresses; pairwise, neighbours first, i.e.
+ * the 32-column subtrees of the order vcas_row_norms uses.  Rows of dropped
+ * samples are not written there.  bf16 only (VCAS_EDTYPE otherwise).
+ * vcas_row_norms_from_blocks: sq[r] = the nb block sums of row r added pairwise,
+ * neighbours first (zero-padded to a power of two): bit for bit what
+ * vcas_row_norms computes from the stored matrix itself.  K = row length of that
+ * matrix; sample_mask (N bytes, null: all): rows of samples with mask 0 are not
+ * read and get 0 (pass the producing layer's maskA).  norm (null: skip): the
+ * per-sample Frobenius norms, as vcas_row_norms' gnorm.
+ */
+vcas_status vcas_sampled_dgrad_norms(const vcas_shape *shape, const void *G, const void *W, const float *p,
+                                     const int32_t *idxA, const int32_t *cntA, const void *J, void *dX,
+                                     float *sq_blocks, void *stream);
+vcas_status vcas_row_norms_from_blocks(int32_t N, int32_t T, int32_t K, const float *sq_blocks,
+                                       const uint8_t *sample_mask, float *sq, float *norm, void *stream);
+
+/*
  * Sampled weight gradient (Sec. 4.2, grad_W = Gtilde^T X):
  *   dW[o,k] = sum over the *cntW rows t = idxW[.] of row_scale[t] G[t,o] X[t,k].
  * dW [K_out,K_in] fp32 is overwritten.  Needs the workspace (split-K partial
@@ -268,6 +294,14 @@ typedef struct {
                            step shorter.  The number of slices fixes the order of a weight gradient's sums:
                            dW is the same bits for the same value of this field, and within rounding
                            (fp32 sums in another order) across values. */
+    /* The norms of G from the launch that wrote G (see vcas_sampled_dgrad_norms), for entries that feed
+       each other; bf16 only, both optional. */
+    float *dx_sq_blocks;       /* [ceil(K_in/32) * R] (block-major), device: this entry's dgrad also leaves the block sums of
+                                  squares of its dX here (rows of kept samples only); needs dX */
+    const float *g_sq_blocks;  /* [ceil(K_out/32) * R], device: block sums of squares of this entry's G, as the
+                                  entry that wrote G left them; the pass over G is replaced by a pass over
+                                  them (the same bits).  Needs kept_above: rows of samples dropped above have
+                                  no block sums */
 } vcas_layer_args;
 
 /*

@@ -100,13 +100,34 @@ def uniform(seed: int, layer: int, stream: int, draw: int, row: int) -> float:
 
 
 def row_sumsq(A: np.ndarray, dtype: int, T: int = 1, sample_keep: np.ndarray | None = None) -> np.ndarray:
-    """fp32 squared row norms of A[R,K] in the written-down lane order."""
+    """fp32 squared row norms of A[R,K] in the written-down order (pairwise, neighbours first)."""
     A = _check(A, dtype)
     R, K = A.shape
     out = np.empty(R, np.float32)
     keep = None if sample_keep is None else np.ascontiguousarray(sample_keep, dtype=np.uint8)
     _L().orc_row_sumsq(_p(A), C.c_int(dtype), C.c_int64(R), C.c_int(K), C.c_int(T),
                        None if keep is None else _p(keep), _p(out))
+    return out
+
+
+def block_sumsq(A: np.ndarray, dtype: int) -> np.ndarray:
+    """Sums of squares of A[R,K] by blocks of 32 columns, [R, ceil(K/32)] fp32: the 32-column subtrees of the
+    pairwise order of row_sumsq (what the dgrad of the layer above leaves for a layer inside a stack, Sec. 4)."""
+    A = _check(A, dtype)
+    R, K = A.shape
+    out = np.empty((R, (K + 31) // 32), np.float32)
+    _L().orc_block_sumsq(_p(A), C.c_int(dtype), C.c_int64(R), C.c_int(K), _p(out))
+    return out
+
+
+def rows_from_blocks(blocks: np.ndarray, T: int = 1, sample_keep: np.ndarray | None = None) -> np.ndarray:
+    """Row sums from their block sums, pairwise, neighbours first; rows of dropped samples get 0."""
+    blocks = np.ascontiguousarray(blocks, dtype=np.float32)
+    R, nb = blocks.shape
+    out = np.empty(R, np.float32)
+    keep = None if sample_keep is None else np.ascontiguousarray(sample_keep, dtype=np.uint8)
+    _L().orc_rows_from_blocks(_p(blocks), C.c_int64(R), C.c_int(nb), C.c_int(T), None if keep is None else _p(keep),
+                              _p(out))
     return out
 
 

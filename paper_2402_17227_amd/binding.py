@@ -20,7 +20,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
-    "vcas_static_scratch_bytes", "vcas_sampled_wgrad_static",
+    "vcas_static_scratch_bytes", "vcas_sampled_wgrad_static", "vcas_sampled_dgrad_norms", "vcas_row_norms_from_blocks",
     "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_backward_weight_cached",
     "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
@@ -51,7 +51,7 @@ class LayerArgs(C.Structure):
                 ("nu", C.c_double), ("rng", Rng), ("token_sampling", C.c_int32), ("plan", PlanPtrs),
                 ("dX", C.c_void_p), ("dW", C.c_void_p), ("workspace", C.c_void_p), ("xsq_forward", C.c_void_p), ("sibling", C.c_int32),
                 ("J", C.c_void_p), ("kept_above", C.c_void_p), ("leave_dropped_rows", C.c_int32),
-                ("wgrad_fill", C.c_int32)]
+                ("wgrad_fill", C.c_int32), ("dx_sq_blocks", C.c_void_p), ("g_sq_blocks", C.c_void_p)]
 
 
 _lib = None
@@ -195,6 +195,17 @@ def vcas_sampled_dgrad_jac(shape: Shape, G, W, p, idxA, cntA, J, dX):
                                         _ptr(dX), _stream()), "vcas_sampled_dgrad_jac")
 
 
+def vcas_sampled_dgrad_norms(shape: Shape, G, W, p, idxA, cntA, J, dX, sq_blocks):
+    _check(lib().vcas_sampled_dgrad_norms(C.byref(shape), _ptr(G), _ptr(W), _ptr(p), _ptr(idxA), _ptr(cntA), _ptr(J),
+                                          _ptr(dX), _ptr(sq_blocks), _stream()), "vcas_sampled_dgrad_norms")
+
+
+def vcas_row_norms_from_blocks(N: int, T: int, K: int, sq_blocks, sample_mask, sq, norm):
+    _check(lib().vcas_row_norms_from_blocks(C.c_int32(N), C.c_int32(T), C.c_int32(K), _ptr(sq_blocks),
+                                            _ptr(sample_mask), _ptr(sq), _ptr(norm), _stream()),
+           "vcas_row_norms_from_blocks")
+
+
 def vcas_sampled_wgrad(shape: Shape, G, X, row_scale, idxW, cntW, dW, workspace):
     _check(lib().vcas_sampled_wgrad(C.byref(shape), _ptr(G), _ptr(X), _ptr(row_scale), _ptr(idxW), _ptr(cntW),
                                     _ptr(dW), _ptr(workspace), _stream()), "vcas_sampled_wgrad")
@@ -223,7 +234,7 @@ def vcas_linear_backward(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng,
 
 def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sampling: bool, plan: Plan, dX, dW,
                workspace, xsq_forward=None, sibling=False, J=None, kept_above=None,
-               leave_dropped_rows=False, wgrad_fill=0) -> LayerArgs:
+               leave_dropped_rows=False, wgrad_fill=0, dx_sq_blocks=None, g_sq_blocks=None) -> LayerArgs:
     """One entry of the array vcas_backward_stack takes (the tensors must stay alive while it is used)."""
     a = LayerArgs()
     a.shape = shape
@@ -238,6 +249,7 @@ def layer_args(shape: Shape, G, X, W, rho: float, nu: float, rng: Rng, token_sam
     a.J, a.kept_above = _ptr(J), _ptr(kept_above)
     a.leave_dropped_rows = 1 if leave_dropped_rows else 0
     a.wgrad_fill = wgrad_fill
+    a.dx_sq_blocks, a.g_sq_blocks = _ptr(dx_sq_blocks), _ptr(g_sq_blocks)
     return a
 
 

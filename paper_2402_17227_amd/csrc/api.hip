@@ -54,7 +54,9 @@ int wgrad_tiles_bf16(int K_out, int K_in, int tile);
 int wgrad_tiles_f32(int K_out, int K_in);
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
-                       const InlineSampleA *sample_a, hipStream_t st);
+                       const InlineSampleA *sample_a, float *sq_blocks, hipStream_t st);
+vcas_status rows_from_blocks(const float *blocks, int64_t R, int K, int T, const uint8_t *keep, float *const *outs,
+                             int n_out, hipStream_t st);
 vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
                              hipStream_t st);
 vcas_status wgrad_bf16_batch(const WgradItem *items, int n, int tile, hipStream_t st);
@@ -150,12 +152,13 @@ __global__ __launch_bounds__(64) void sq_diff_final_kernel(const double *__restr
 
 // J: elementwise Jacobian [R, K_in] in the layer dtype, multiplied into dX (null: none);
 // fill: write zero rows for the samples that are not kept
+// sq_blocks (bf16 only, else null): also write the sums of squares of dX by blocks of 32 columns
 static vcas_status dispatch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
                                   const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
-                                  int64_t expected_rows, hipStream_t st)
+                                  int64_t expected_rows, hipStream_t st, float *sq_blocks = nullptr)
 {
-    return s.dtype == VCAS_BF16 ? dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, fill, expected_rows, nullptr, st)
-                                : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, fill, st);
+    if (s.dtype == VCAS_BF16) return dgrad_bf16(s, G, W, p, idxA, cntA, dX, J, fill, expected_rows, nullptr, sq_blocks, st);
+    return sq_blocks ? VCAS_EDTYPE : dgrad_f32(s, G, W, p, idxA, cntA, dX, J, fill, st);
 }
 
 // Tile edge and split-K slices of bf16 weight gradients.  `fill` = the workgroups a launch should
@@ -305,6 +308,8 @@ struct ChainArgs {
     const void *J = nullptr;              // elementwise Jacobian multiplied into dX
     const uint8_t *kept_above = nullptr;  // samples whose rows of G exist at all (the others count as zero)
     bool fill = true;                     // write zero rows of dX for the samples that are not kept
+    const float *g_sq_blocks = nullptr;   // block sums of squares of G from the dgrad that wrote it: no sweep over G
+    float *dx_sq_blocks = nullptr;        // where this layer's dgrad leaves the block sums of squares of its dX
 };
 
 // Where the norms of X are taken: with those of G, before SampleA (one launch fewer, every row
@@ -326,7 +331,11 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
     // together: the square roots SampleW needs travel in the plan's score and q arrays until
     // SampleW overwrites them with their final contents
-    if (together_for(s, xnorms))
+    if (chain.g_sq_blocks) {
+        // the norms of G come from the launch that wrote G; those of X are left to the weight half
+        float *outs[1] = {pl.gsq};
+        VCAS_TRY(rows_from_blocks(chain.g_sq_blocks, R, s.K_out, s.T, chain.kept_above, outs, 1, st));
+    } else if (together_for(s, xnorms))
         VCAS_TRY(row_sumsq_pair(G, s.K_out, pl.gsq, X, s.K_in, pl.xsq, s.dtype, R, rng, 1u, uw, pl.score, pl.q, s.T,
                                 chain.kept_above, st));
     else
@@ -350,10 +359,12 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
         sa.maskA = pl.maskA;
         sa.idxA = pl.idxA;
         sa.cntA = pl.cntA;
-        return dgrad_bf16(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, &sa, st);
+        return dgrad_bf16(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, &sa, chain.dx_sq_blocks, st);
     }
     VCAS_TRY(sampler_a(pl.gsq, s.N, s.T, (double)s.N * rho, rng, pl.gnorm, pl.p, pl.maskA, pl.idxA, pl.cntA, st));
-    if (dX) VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, st));
+    if (dX)
+        VCAS_TRY(dispatch_dgrad(s, G, W, pl.p, pl.idxA, pl.cntA, dX, chain.J, chain.fill, rows_expected, st,
+                                chain.dx_sq_blocks));
     return VCAS_OK;
 }
 
@@ -394,7 +405,7 @@ static bool shares_data_half(const vcas_layer_args &a, const vcas_layer_args &b)
 {
     const vcas_shape &s = a.shape;
     return b.sibling != 0 && same_shape(s, b.shape) && s.dtype == VCAS_BF16 && s.N <= 1024 && a.dX && b.dX &&
-           (a.leave_dropped_rows != 0) == (b.leave_dropped_rows != 0);
+           (a.leave_dropped_rows != 0) == (b.leave_dropped_rows != 0) && (a.g_sq_blocks != nullptr) == (b.g_sq_blocks != nullptr);
 }
 
 // Data halves of n sibling layers (shares_data_half): the row norms of every G in one launch,
@@ -438,9 +449,23 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         q.J = static_cast<const uint16_t *>(a.J);
         q.sa = sa;
         if (!in_dgrad) q.sa.gsq = nullptr;
+        q.sq_blocks = a.dx_sq_blocks;
         if (a.rho > rho_max) rho_max = a.rho;
     }
-    VCAS_TRY(row_sumsq_group(norms, n, s.dtype, R, s.K_out, s.T, st));
+    if (layers[0].g_sq_blocks) {
+        // norms of G from the launch that wrote it: one pass over the block sums serves every
+        // sibling that was handed the same G; the others take a pass of their own
+        for (int i = 0; i < n;) {
+            float *outs[kMaxSiblings];
+            int m = 0;
+            for (; i + m < n && layers[i + m].g_sq_blocks == layers[i].g_sq_blocks &&
+                   layers[i + m].kept_above == layers[i].kept_above; ++m)
+                outs[m] = layers[i + m].plan.gsq;
+            VCAS_TRY(rows_from_blocks(layers[i].g_sq_blocks, R, s.K_out, s.T, layers[i].kept_above, outs, m, st));
+            i += m;
+        }
+    } else
+        VCAS_TRY(row_sumsq_group(norms, n, s.dtype, R, s.K_out, s.T, st));
     if (!in_dgrad) VCAS_TRY(sampler_a_group(samplers, n, s.N, s.T, st));
     return dgrad_bf16_group(s, probs, n, layers[0].leave_dropped_rows == 0, (int64_t)((double)R * rho_max + 0.5), st);
 }
@@ -691,6 +716,29 @@ vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const
     return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, J, true, 0, as_stream(stream));
 }
 
+vcas_status vcas_sampled_dgrad_norms(const vcas_shape *shape, const void *G, const void *W, const float *p,
+                                     const int32_t *idxA, const int32_t *cntA, const void *J, void *dX,
+                                     float *sq_blocks, void *stream)
+{
+    VCAS_TRY(check_shape(shape));
+    VCAS_TRY(check_gemm_limits(shape));
+    if (shape->dtype != VCAS_BF16) return VCAS_EDTYPE;
+    if (!G || !W || !p || !idxA || !cntA || !dX || !sq_blocks) return VCAS_ENULL;
+    if (!aligned16(G) || !aligned16(W) || (J && !aligned16(J)) || !aligned16(dX)) return VCAS_EINVAL;
+    return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, J, true, 0, as_stream(stream), sq_blocks);
+}
+
+vcas_status vcas_row_norms_from_blocks(int32_t N, int32_t T, int32_t K, const float *sq_blocks,
+                                       const uint8_t *sample_mask, float *sq, float *norm, void *stream)
+{
+    if (N <= 0 || T <= 0 || K <= 0 || (int64_t)N * T > (int64_t)1 << 30) return VCAS_EINVAL;
+    if (!sq_blocks || !sq) return VCAS_ENULL;
+    float *outs[1] = {sq};
+    VCAS_TRY(rows_from_blocks(sq_blocks, (int64_t)N * T, K, T, sample_mask, outs, 1, as_stream(stream)));
+    if (norm) VCAS_TRY(sample_norms(sq, N, T, norm, as_stream(stream)));
+    return VCAS_OK;
+}
+
 vcas_status vcas_sampled_wgrad(const vcas_shape *shape, const void *G, const void *X, const float *row_scale_,
                                const int32_t *idxW, const int32_t *cntW, float *dW, void *workspace, void *stream)
 {
@@ -757,6 +805,9 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if (a.wgrad_fill < 0) return VCAS_EINVAL;
         if (a.J && !a.dX) return VCAS_ENULL;
         if (a.J && !aligned16(a.J)) return VCAS_EINVAL;
+        if ((a.g_sq_blocks || a.dx_sq_blocks) && a.shape.dtype != VCAS_BF16) return VCAS_EDTYPE;
+        if (a.dx_sq_blocks && !a.dX) return VCAS_ENULL;
+        if (a.g_sq_blocks && !a.kept_above) return VCAS_ENULL;
         if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
             (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
             return VCAS_EINVAL;
@@ -801,8 +852,11 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
                 chain.J = a.J;
                 chain.kept_above = a.kept_above;
                 chain.fill = a.leave_dropped_rows == 0;
+                chain.g_sq_blocks = a.g_sq_blocks;
+                chain.dx_sq_blocks = a.dx_sq_blocks;
                 VCAS_TRY(data_half(a.shape, a.G, a.X, a.W, a.rho, a.rng, a.token_sampling, a.plan, a.dX, chain,
-                                   a.workspace, st, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default, true));
+                                   a.workspace, st,
+                                   a.xsq_forward || a.g_sq_blocks ? kXNormsAfterSampleA : xnorms_default, true));
             }
             l += n;
         }
@@ -821,7 +875,8 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
                 VCAS_TRY(weight_half_siblings(layers + l, n, s2));
             else
                 VCAS_TRY(weight_half(a.shape, a.G, a.X, a.rho, a.nu, a.rng, a.token_sampling, a.plan, nullptr,
-                                     a.workspace, s2, a.xsq_forward ? kXNormsAfterSampleA : xnorms_default,
+                                     a.workspace, s2,
+                                     a.xsq_forward || a.g_sq_blocks ? kXNormsAfterSampleA : xnorms_default,
                                      a.xsq_forward));
             l += n;
         }

@@ -61,7 +61,7 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
                                                 const int32_t *__restrict__ cntA, uint16_t *__restrict__ dX, int N,
                                                 int T, int K_in, int K_out, int tiles_n,
                                                 const uint16_t *__restrict__ J, int fill_dropped,
-                                                const InlineSampleA &sa)
+                                                const InlineSampleA &sa, float *__restrict__ sq_blocks)
 {
     constexpr int NW = WM * WN, NT = NW * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -303,6 +303,17 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
     }
     wait_loads_outstanding<0>();
 
+    // Sums of squares of the stored dX by blocks of 32 columns (sq_blocks, optional).  Level 1, the
+    // two columns a lane stores, is formed beside the store; the 16 lane values of a block (even
+    // lanes hold one row, odd lanes the next) are then added by ONE lane, which reads them back from
+    // LDS: the operand stages are free by now, every wavefront gets ITEMS x 64 floats of them, an
+    // item = the 64 lane values of one (row pair, column block), its 16-byte slots XOR-ed with the
+    // item number so that the readers spread over the banks.
+    constexpr int ITEMS = TM * 8 * TN;
+    static_assert(ITEMS * 256 * NW <= NS * STAGE, "the block sums are staged in the operand stages");
+    float *sq_lds = reinterpret_cast<float *>(smem) + wave * (ITEMS * 64);
+    if (sq_blocks) __syncthreads();   // every wavefront is done with the stages
+
     // Each MFMA lane holds one column of 16 rows; neighbouring lanes swap every second value so
     // that a lane owns two adjacent columns of one row and stores them as one dword.
     const bool odd = lane & 1;
@@ -321,16 +332,54 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
                 const float recv = dpp_move<0xB1>(send);
                 float lo = odd ? recv : mine_e, hi = odd ? mine_o : recv;
                 const int col = n0 + wn0 + j * 32 + (lane & 30);
+                uint32_t stored = 0u;
                 if (dst >= 0 && col < K_in) {
                     if (J) {   // elementwise Jacobian of the layer below (App. E, proof of unbiasedness), same layout as dX
                         const uint32_t jw = *reinterpret_cast<const uint32_t *>(J + (int64_t)dst * K_in + col);
                         lo = lo * bf16_lo(jw);
                         hi = hi * bf16_hi(jw);
                     }
-                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = pack_bf16(lo, hi);
+                    stored = pack_bf16(lo, hi);
+                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = stored;
+                }
+                if (sq_blocks) {
+                    // level 1 of the block's sum of squares: the two columns of this lane, as stored
+                    const float e0 = bf16_lo(stored), e1 = bf16_hi(stored);
+                    const int it = (i * 8 + (v >> 1)) * TN + j;
+                    sq_lds[it * 64 + (((lane >> 2) ^ (it & 7)) << 2) + (lane & 3)] = e0 * e0 + e1 * e1;
                 }
             }
         }
+    if (sq_blocks && lane < TM * 16) {
+        // lane = (i, q, h, w): the row pair wm0 + 32 i + 8 q + 4 h + 2 w (+0, +1), i.e. consecutive
+        // lanes take consecutive row pairs, and the results go out as runs of consecutive rows of
+        // sq_blocks [block][row].  Pairwise, neighbours first: the 16 column pairs of a row in order.
+        const int i = lane >> 4, q = (lane >> 2) & 3, h = (lane >> 1) & 1, w = lane & 1;
+        const int r_even = wm0 + i * 32 + q * 8 + h * 4 + w * 2;
+        const int32_t dst_e = row_of[r_even], dst_o = row_of[r_even + 1];
+        const int nb = (K_in + 31) >> 5;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int it = (i * 8 + q * 2 + w) * TN + j;
+            float4 f[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                f[k] = *reinterpret_cast<const float4 *>(sq_lds + it * 64 + ((h * 8 + (k ^ (it & 7))) << 2));
+            float ev[8], od[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                ev[k] = f[k].x + f[k].z;
+                od[k] = f[k].y + f[k].w;
+            }
+            const float even_total = ((ev[0] + ev[1]) + (ev[2] + ev[3])) + ((ev[4] + ev[5]) + (ev[6] + ev[7]));
+            const float odd_total = ((od[0] + od[1]) + (od[2] + od[3])) + ((od[4] + od[5]) + (od[6] + od[7]));
+            const int blk32 = (n0 + wn0 + j * 32) >> 5;
+            if (blk32 < nb) {
+                if (dst_e >= 0) sq_blocks[(int64_t)blk32 * R + dst_e] = even_total;
+                if (dst_o >= 0) sq_blocks[(int64_t)blk32 * R + dst_o] = odd_total;
+            }
+        }
+    }
 }
 
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
@@ -342,9 +391,10 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_kernel(const uint
                                                                   uint16_t *__restrict__ dX, int N, int T, int K_in,
                                                                   int K_out, int tiles_n,
                                                                   const uint16_t *__restrict__ J, int fill_dropped,
-                                                                  InlineSampleA sa)
+                                                                  InlineSampleA sa, float *__restrict__ sq_blocks)
 {
-    dgrad_bf16_body<BM, BN, WM, WN, NS, SPQ>(G, W, p, idxA, cntA, dX, N, T, K_in, K_out, tiles_n, J, fill_dropped, sa);
+    dgrad_bf16_body<BM, BN, WM, WN, NS, SPQ>(G, W, p, idxA, cntA, dX, N, T, K_in, K_out, tiles_n, J, fill_dropped, sa,
+                                             sq_blocks);
 }
 
 // Several layers of one shape whose upstream gradients do not depend on each other (the Q, K and V
@@ -356,7 +406,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_group_kernel(Dgra
 {
     const DgradProblem &q = grp.prob[blockIdx.y];
     dgrad_bf16_body<BM, BN, WM, WN, NS, SPQ>(q.G, q.W, q.p, q.idxA, q.cntA, q.dX, N, T, K_in, K_out, tiles_n, q.J,
-                                             fill_dropped, q.sa);
+                                             fill_dropped, q.sa, q.sq_blocks);
 }
 
 // ---------------------------------------------------------- host launchers
@@ -364,7 +414,7 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void dgrad_bf16_group_kernel(Dgra
 template <int BM, int BN, int WM, int WN, int NS, int OCC, int SPQ>
 static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *W, const float *p,
                                 const int32_t *idxA, const int32_t *cntA, void *dX, const void *J, bool fill,
-                                const InlineSampleA &sa, hipStream_t st)
+                                const InlineSampleA &sa, float *sq_blocks, hipStream_t st)
 {
     const int64_t R = (int64_t)s.N * s.T;
     const int tiles_n = (s.K_in + BN - 1) / BN;
@@ -380,7 +430,7 @@ static vcas_status launch_dgrad(const vcas_shape &s, const void *G, const void *
     }
     launch_timed(0, kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, st, static_cast<const uint16_t *>(G),
                  static_cast<const uint16_t *>(W), p, idxA, cntA, static_cast<uint16_t *>(dX), s.N, s.T, s.K_in,
-                 s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0, sa);
+                 s.K_out, tiles_n, static_cast<const uint16_t *>(J), fill ? 1 : 0, sa, sq_blocks);
     return launch_status();
 }
 
@@ -434,7 +484,7 @@ vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int
 // it itself from the row norms and writes the plan's SampleA fields; N <= 64 only.
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
-                       const InlineSampleA *sample_a, hipStream_t st)
+                       const InlineSampleA *sample_a, float *sq_blocks, hipStream_t st)
 {
     InlineSampleA sa = {};
     sa.gsq = nullptr;
@@ -457,11 +507,11 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     // without an expectation (the kept count is known on the device only) the tiles of ALL rows are counted, and a
     // kernel picked for them may find half of them empty: the larger tile then needs more of them to pay
     if (tiles256 >= (expected_rows > 0 ? 128 : 192))
-        return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
-    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+        return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
+    if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
-    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
-    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, st);
+    if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
+    return launch_dgrad<64, 128, 2, 2, 4, 1, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
 }
 
 }  // namespace vcas

@@ -148,6 +148,64 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
     }
 }
 
+// Row sums of squares from the sums of squares of their 32-column blocks (what the dgrad epilogue
+// emits for the dX it has just written): blocks[b * R + row], b < nb, added pairwise, neighbours
+// first, the upper levels of the same tree a sweep over the row forms.  Neighbouring threads take
+// neighbouring rows, so their reads are neighbours; rows of samples whose sample_keep byte is 0 are
+// not read and get 0.  Up to kMaxSiblings outputs receive the same values (sibling layers share their G).
+struct RowsFromBlocks {
+    float *out[kMaxSiblings];
+};
+
+__global__ __launch_bounds__(256) void rows_from_blocks_kernel(const float *__restrict__ blocks, int64_t R, int nb,
+                                                               int T, const uint8_t *__restrict__ sample_keep,
+                                                               RowsFromBlocks outs, int n_out)
+{
+    // 32 rows per workgroup, eight threads per row: thread (row, part) adds an aligned run of
+    // P/8 blocks (P = nb padded to a power of two), i.e. one subtree of the row's tree, with eight
+    // loads in flight; the eight subtree sums meet in LDS and are added as the top three levels.
+    __shared__ float part_sum[8][32];
+    const int r_local = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int64_t row = (int64_t)blockIdx.x * 32 + r_local;
+    int P = 1;
+    while (P < nb) P *= 2;
+    const int chunk = P >= 8 ? P / 8 : 1;
+    const bool live = row < R && (!sample_keep || sample_keep[row / T] != 0);
+    float acc = 0.0f;
+    if (live) {
+        const int b0 = part * chunk, b1 = min(nb, b0 + chunk);
+        PairwiseStream<9> leaves;
+        for (int b = b0; b < b1; b += 8) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? blocks[(int64_t)(b + k) * R + row] : 0.0f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (b + k < b1) leaves.push(v[k]);
+        }
+        acc = leaves.finish();
+    }
+    part_sum[part][r_local] = acc;
+    __syncthreads();
+    if (part == 0 && row < R) {
+        const float total = ((part_sum[0][r_local] + part_sum[1][r_local]) + (part_sum[2][r_local] + part_sum[3][r_local])) +
+                            ((part_sum[4][r_local] + part_sum[5][r_local]) + (part_sum[6][r_local] + part_sum[7][r_local]));
+        for (int k = 0; k < n_out; ++k) outs.out[k][row] = live ? total : 0.0f;
+    }
+}
+
+// outs: n_out <= kMaxSiblings arrays of R floats
+vcas_status rows_from_blocks(const float *blocks, int64_t R, int K, int T, const uint8_t *keep, float *const *outs,
+                             int n_out, hipStream_t st)
+{
+    if (n_out < 1 || n_out > kMaxSiblings) return VCAS_EINVAL;
+    RowsFromBlocks o = {};
+    for (int k = 0; k < n_out; ++k) o.out[k] = outs[k];
+    hipLaunchKernelGGL(rows_from_blocks_kernel, dim3((unsigned)((R + 31) / 32)), dim3(256), 0, st, blocks, R,
+                       (K + 31) / 32, T, keep, o, n_out);
+    return launch_status();
+}
+
 // ||G_i||_F: value t of a sample belongs to lane t mod 64, plain fp32 adds in
 // ascending t, exchange steps, correctly rounded sqrt.  One wavefront per sample.
 __global__ __launch_bounds__(256) void sample_norm_kernel(const float *__restrict__ gsq, int N, int T,

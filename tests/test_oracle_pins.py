@@ -99,6 +99,38 @@ def test_row_sumsq_adds_neighbours_first(dtype):
     assert oracle.row_sumsq(row([1] * 9 + [4096] + [1] * 6), dtype)[0] == np.float32(16777230.0)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("K", [8, 40, 136, 768, 1000, 4096])
+def test_block_sums_are_subtrees_of_the_row_sum(dtype, K):
+    """Row norms in two stages (32-column block sums, then the blocks pairwise) give the bits of the one-stage
+    row sum, ragged last block and non-power-of-two block counts included; each block sum is the row sum of
+    the block taken as a row of its own; and the definition in fp64 pins both."""
+    rng = np.random.default_rng(K)
+    a = (rng.standard_normal((7, K)) * np.exp(rng.standard_normal((7, 1)))).astype(np.float32)
+    A = workloads.f32_to_bf16_bits(a) if dtype == BF16 else a
+    blocks = oracle.block_sumsq(A, dtype)
+    assert blocks.shape == (7, (K + 31) // 32)
+    whole = oracle.row_sumsq(A, dtype)
+    assert np.array_equal(oracle.rows_from_blocks(blocks).view(np.uint32), whole.view(np.uint32))
+    for b in range(blocks.shape[1]):
+        piece = np.ascontiguousarray(A[:, 32 * b:32 * b + 32])
+        assert np.array_equal(oracle.row_sumsq(piece, dtype).view(np.uint32), blocks[:, b].view(np.uint32))
+    np.testing.assert_allclose(blocks.astype(np.float64).sum(axis=1), oracle.row_sumsq_f64(A, dtype), rtol=1e-6)
+    # dropped samples: zero, whatever their block sums hold
+    keep = np.array([1, 0, 1, 1, 0, 1, 1], np.uint8)
+    poisoned = blocks.copy()
+    poisoned[keep == 0] = np.nan
+    got = oracle.rows_from_blocks(poisoned, 1, keep)
+    assert np.array_equal(got[keep == 1].view(np.uint32), whole[keep == 1].view(np.uint32)) and np.all(got[keep == 0] == 0)
+
+
+def test_rows_from_blocks_worked_example():
+    """Five block sums (padded to eight): 2^24, 1, 1, 1, 1 -> pairs 2^24 (the 1 is lost to the tie), 2, 1 | fours
+    2^24 + 2, 1 | 2^24 + 2 + 1 = 2^24 + 3 -> rounds to 2^24 + 4 (tie to even)."""
+    blocks = np.array([[16777216.0, 1, 1, 1, 1]], np.float32)
+    assert oracle.rows_from_blocks(blocks)[0] == np.float32(16777220.0)
+
+
 def test_row_sumsq_sample_mask_zeroes_dropped_samples():
     rng = np.random.default_rng(6)
     a = rng.standard_normal((12, 64)).astype(np.float32)
