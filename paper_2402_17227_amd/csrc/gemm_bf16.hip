@@ -8,6 +8,8 @@
 // registers: buffer loads write straight into LDS; W, which lies "the wrong way" for an MFMA
 // lane (the contraction index is its slow dimension), stays as it is in memory, [64 k][columns],
 // and ds_read_b64_tr_b16 transposes it on the way out.  The per-row 1/p goes into the epilogue.
+#include <type_traits>
+
 #include "mfma_bf16.hpp"
 
 namespace vcas {
@@ -303,81 +305,117 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
     }
     wait_loads_outstanding<0>();
 
-    // Sums of squares of the stored dX by blocks of 32 columns (sq_blocks, optional).  Level 1, the
-    // two columns a lane stores, is formed beside the store; the 16 lane values of a block (even
-    // lanes hold one row, odd lanes the next) are then added by ONE lane, which reads them back from
-    // LDS: the operand stages are free by now, every wavefront gets ITEMS x 64 floats of them, an
-    // item = the 64 lane values of one (row pair, column block), its 16-byte slots XOR-ed with the
-    // item number so that the readers spread over the banks.
-    constexpr int ITEMS = TM * 8 * TN;
-    static_assert(ITEMS * 256 * NW <= NS * STAGE, "the block sums are staged in the operand stages");
-    float *sq_lds = reinterpret_cast<float *>(smem) + wave * (ITEMS * 64);
-    if (sq_blocks) __syncthreads();   // every wavefront is done with the stages
-
-    // Each MFMA lane holds one column of 16 rows; neighbouring lanes swap every second value so
-    // that a lane owns two adjacent columns of one row and stores them as one dword.
+    // Epilogue.  An MFMA lane holds one column of 16 rows, so stores straight from the
+    // accumulators would be 64-byte pieces, 64 instructions per wavefront.  Instead every wavefront
+    // passes its (TM*32) x 64 sub-tile through LDS (the operand stages are free by now): rounded
+    // values in, 128-byte rows (whole cache lines) out, 16 bytes per lane.  Row `row` of the strip
+    // keeps logical 16-byte slot s at slot s ^ esw(row), so that the two rows a write instruction
+    // touches per half-wavefront fall into different banks.
+    static_assert(TN == 2, "a staged row is 64 columns = 128 bytes");
+    static_assert(NW * TM * 4096 <= NS * STAGE, "the output strips are staged in the operand stages");
+    __syncthreads();   // every wavefront is done with the stages
+    unsigned char *strip = smem + wave * (TM * 4096);
+    auto esw = [](int row) { return (row & 1) << 2; };
+    if (J) {
+        // Elementwise Jacobian of the layer below (App. E, proof of unbiasedness), same layout as
+        // dX: its sub-tile is fetched into the strip first (zeros for rows and columns that are not
+        // stored), in the layout the results will have; each lane then picks up the values at its
+        // own column and multiplies before the one rounding.
+        const i32x4 descJ = raw_descriptor(J, (uint32_t)(R * K_in * 2));
+        const uint32_t strip_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * (TM * 4096));
+#pragma unroll
+        for (int q = 0; q < TM * 4; ++q) {
+            const int row = q * 8 + (lane >> 3);
+            const int32_t dst = row_of[wm0 + row];
+            const int col = n0 + wn0 + (((lane & 7) ^ esw(row)) << 3);
+            const uint32_t off = dst >= 0 && col < K_in ? ((uint32_t)dst * (uint32_t)K_in + (uint32_t)col) * 2u : kOutside;
+            lds_direct_load16(descJ, strip_lds + q * 1024, off, 0u);
+        }
+        wait_loads_outstanding<0>();
+        asm volatile("" ::: "memory");
+    }
+    // A lane rounds its column's values of two neighbouring rows into one dword; neighbouring lanes
+    // then trade halves (one DPP move, one byte permute) so that each owns two adjacent columns of
+    // one row.  A dropped row has scale 0 and a column past K_in met zero columns of W, so what is
+    // not stored arrives as zero and counts as zero in the block sums.  All LDS reads of a group
+    // of cells come before its writes: the compiler cannot tell the strip from the row tables.
     const bool odd = lane & 1;
+    const uint32_t halves = odd ? 0x03020706u : 0x05040100u;   // even: (mine.lo, other.lo); odd: (other.hi, mine.hi)
+    auto fill_strip = [&](auto with_jacobian) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            float4 sc[4];
 #pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-            const int r_even = wm0 + i * 32 + acc_row(v);
-            const int r = r_even + (odd ? 1 : 0);
-            const int32_t dst = row_of[r];
-            const float sc_e = scale_of[r_even], sc_o = scale_of[r_even + 1];
+            for (int g = 0; g < 4; ++g)
+                sc[g] = *reinterpret_cast<const float4 *>(scale_of + wm0 + i * 32 + g * 8 + (lane >> 5) * 4);
+            uint16_t jw[16][TN];
+            if (with_jacobian) {
+                // the Jacobian's values at this lane's own column, rows acc_row(v)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
-                const float send = odd ? mine_e : mine_o;
-                const float recv = dpp_move<0xB1>(send);
-                float lo = odd ? recv : mine_e, hi = odd ? mine_o : recv;
-                const int col = n0 + wn0 + j * 32 + (lane & 30);
-                uint32_t stored = 0u;
-                if (dst >= 0 && col < K_in) {
-                    if (J) {   // elementwise Jacobian of the layer below (App. E, proof of unbiasedness), same layout as dX
-                        const uint32_t jw = *reinterpret_cast<const uint32_t *>(J + (int64_t)dst * K_in + col);
-                        lo = lo * bf16_lo(jw);
-                        hi = hi * bf16_hi(jw);
+                for (int v = 0; v < 16; ++v)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int row = i * 32 + acc_row(v);
+                        const int slot = j * 4 + ((lane & 31) >> 3);
+                        jw[v][j] = *reinterpret_cast<const uint16_t *>(strip + row * 128 + ((slot ^ esw(row)) << 4) +
+                                                                      (lane & 7) * 2);
                     }
-                    stored = pack_bf16(lo, hi);
-                    *reinterpret_cast<uint32_t *>(dX + (int64_t)dst * K_in + col) = stored;
-                }
-                if (sq_blocks) {
-                    // level 1 of the block's sum of squares: the two columns of this lane, as stored
-                    const float e0 = bf16_lo(stored), e1 = bf16_hi(stored);
-                    const int it = (i * 8 + (v >> 1)) * TN + j;
-                    sq_lds[it * 64 + (((lane >> 2) ^ (it & 7)) << 2) + (lane & 3)] = e0 * e0 + e1 * e1;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const int row = i * 32 + acc_row(v) + (odd ? 1 : 0);
+                const float sc_e = (v & 2) ? sc[v >> 2].z : sc[v >> 2].x, sc_o = (v & 2) ? sc[v >> 2].w : sc[v >> 2].y;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float mine_e = acc[i][j][v] * sc_e, mine_o = acc[i][j][v + 1] * sc_o;
+                    if (with_jacobian) {
+                        mine_e = mine_e * __uint_as_float((uint32_t)jw[v][j] << 16);
+                        mine_o = mine_o * __uint_as_float((uint32_t)jw[v + 1][j] << 16);
+                    }
+                    const uint32_t mine = pack_bf16(mine_e, mine_o);
+                    const uint32_t other = __float_as_uint(dpp_move<0xB1>(__uint_as_float(mine)));
+                    const int slot = j * 4 + ((lane & 31) >> 3);
+                    *reinterpret_cast<uint32_t *>(strip + row * 128 + ((slot ^ esw(row)) << 4) + ((lane >> 1) & 3) * 4) =
+                        __builtin_amdgcn_perm(other, mine, halves);
                 }
             }
         }
-    if (sq_blocks && lane < TM * 16) {
-        // lane = (i, q, h, w): the row pair wm0 + 32 i + 8 q + 4 h + 2 w (+0, +1), i.e. consecutive
-        // lanes take consecutive row pairs, and the results go out as runs of consecutive rows of
-        // sq_blocks [block][row].  Pairwise, neighbours first: the 16 column pairs of a row in order.
-        const int i = lane >> 4, q = (lane >> 2) & 3, h = (lane >> 1) & 1, w = lane & 1;
-        const int r_even = wm0 + i * 32 + q * 8 + h * 4 + w * 2;
-        const int32_t dst_e = row_of[r_even], dst_o = row_of[r_even + 1];
-        const int nb = (K_in + 31) >> 5;
+    };
+    if (J) fill_strip(std::true_type{});
+    else fill_strip(std::false_type{});
+    __builtin_amdgcn_wave_barrier();   // the strip is this wavefront's own: its LDS accesses execute in order
+    const int nb = (K_in + 31) >> 5;
+    int32_t dst_of[TM * 4];
+    uint4 val[TM * 4];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int it = (i * 8 + q * 2 + w) * TN + j;
-            float4 f[8];
+    for (int q = 0; q < TM * 4; ++q) {
+        const int row = q * 8 + (lane >> 3);
+        dst_of[q] = row_of[wm0 + row];
+        val[q] = *reinterpret_cast<const uint4 *>(strip + row * 128 + ((lane & 7) << 4));
+    }
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                f[k] = *reinterpret_cast<const float4 *>(sq_lds + it * 64 + ((h * 8 + (k ^ (it & 7))) << 2));
-            float ev[8], od[8];
+    for (int q = 0; q < TM * 4; ++q) {
+        const int row = q * 8 + (lane >> 3);
+        const int col = n0 + wn0 + (((lane & 7) ^ esw(row)) << 3);
+        if (dst_of[q] >= 0 && col < K_in) *reinterpret_cast<uint4 *>(dX + (int64_t)dst_of[q] * K_in + col) = val[q];
+    }
+    if (sq_blocks) {
+        // Sums of squares of the stored values by blocks of 32 columns, pairwise with neighbours
+        // first: a lane adds its eight columns (three levels), the four lanes of a block the rest.
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                ev[k] = f[k].x + f[k].z;
-                od[k] = f[k].y + f[k].w;
-            }
-            const float even_total = ((ev[0] + ev[1]) + (ev[2] + ev[3])) + ((ev[4] + ev[5]) + (ev[6] + ev[7]));
-            const float odd_total = ((od[0] + od[1]) + (od[2] + od[3])) + ((od[4] + od[5]) + (od[6] + od[7]));
-            const int blk32 = (n0 + wn0 + j * 32) >> 5;
-            if (blk32 < nb) {
-                if (dst_e >= 0) sq_blocks[(int64_t)blk32 * R + dst_e] = even_total;
-                if (dst_o >= 0) sq_blocks[(int64_t)blk32 * R + dst_o] = odd_total;
-            }
+        for (int q = 0; q < TM * 4; ++q) {
+            const int row = q * 8 + (lane >> 3);
+            const int col = n0 + wn0 + (((lane & 7) ^ esw(row)) << 3);
+            const uint4 w = val[q];
+            const float q0 = bf16_lo(w.x) * bf16_lo(w.x), q1 = bf16_hi(w.x) * bf16_hi(w.x);
+            const float q2 = bf16_lo(w.y) * bf16_lo(w.y), q3 = bf16_hi(w.y) * bf16_hi(w.y);
+            const float q4 = bf16_lo(w.z) * bf16_lo(w.z), q5 = bf16_hi(w.z) * bf16_hi(w.z);
+            const float q6 = bf16_lo(w.w) * bf16_lo(w.w), q7 = bf16_hi(w.w) * bf16_hi(w.w);
+            float t = ((q0 + q1) + (q2 + q3)) + ((q4 + q5) + (q6 + q7));
+            t = t + dpp_move<0xB1>(t);   // slots (0,1) and (2,3) of the block
+            t = t + dpp_move<0x4E>(t);   // the two halves
+            const int blk32 = col >> 5;
+            if ((lane & 3) == 0 && dst_of[q] >= 0 && blk32 < nb) sq_blocks[(int64_t)blk32 * R + dst_of[q]] = t;
         }
     }
 }
