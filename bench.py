@@ -93,6 +93,21 @@ def _is_sibling(name):
     return name.endswith((".k", ".q"))
 
 
+def _chainable(specs):
+    """Can the layers feed each other in this order?  A layer's dX [R, K_in] must be the G [R, K_out] of the
+    next one; a sibling takes what its elder sibling took."""
+    prev = None
+    for sp in specs:
+        if prev is not None:
+            if _is_sibling(sp.name):
+                if (sp.K_in, sp.K_out) != (prev.K_in, prev.K_out):
+                    return False
+            elif sp.K_out != prev.K_in or (sp.N, sp.T, sp.dtype) != (prev.N, prev.T, prev.dtype):
+                return False
+        prev = sp
+    return True
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary of this workload
     (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size); None
@@ -300,13 +315,16 @@ def main():
     ap.add_argument("--wgrad-fill", type=int, default=64, metavar="WORKGROUPS",
                     help="stack launch: workgroups a weight-gradient launch should have before it stops cutting the "
                          "contraction into split-K slices (vcas_layer_args.wgrad_fill; 0 or 384 = what a stand-alone call uses)")
-    ap.add_argument("--chained", action="store_true",
-                    help="stack launch: the layers feed each other as in a real backward pass (down's dX buffer is up's G, "
-                         "up's is o's, o's is the G of V, K and Q, Q's is the next block's down's), every layer is told "
-                         "which samples the one above kept and leaves the rows of dropped samples unwritten; only the top "
-                         "layer's G is an input")
+    ap.add_argument("--independent", action="store_true",
+                    help="stack launch: every layer keeps the upstream gradient it was generated with, as if other kernels "
+                         "had produced it.  The default is the chain of a backward pass (Sec. 4: SampleA sits between the "
+                         "layers, the gradient grows sparser on its way down): down's dX buffer is up's G, up's is o's, o's "
+                         "is the G of V, K and Q, Q's is the next block's down's; every layer is told which samples the one "
+                         "above kept, leaves the rows of dropped samples unwritten, and takes the row norms of its G from "
+                         "the block sums the dgrad above left beside its dX; only the top layer's G is an input")
+    ap.add_argument("--chained", action="store_true", help="the default since the chain became the timed form; accepted and ignored")
     ap.add_argument("--sweep-norms", action="store_true",
-                    help="with --chained: every layer sweeps its G for the row norms, as independent layers must, instead "
+                    help="chained stack: every layer sweeps its G for the row norms, as independent layers must, instead "
                          "of taking them from the block sums of squares the dgrad above has left (the same bits)")
     ap.add_argument("--xsq-cached", action="store_true",
                     help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
@@ -380,15 +398,18 @@ def main():
     sides = [] if args.one_stream else [torch.cuda.Stream() for _ in range(args.side_streams)]
 
     stack = None
+    fused_norms = False
     if args.stack is None:
         # a group of layers = the stretch between two cross-stream waits: half a block ([down, up, o], [V, K, Q]) where
         # a layer is a few microseconds of work and the side streams must not fall behind, a whole block where
         # layers are long enough to hide that (bert_base 2.29 vs 2.32 ms, bert_large 15.2 vs 14.7 ms)
         args.stack = 3 if specs[0].R <= 4096 else 6
+    args.chained = not args.independent and _chainable(specs)   # a fused Q/K/V layer breaks the chain of shapes
     if args.graph or args.eager or args.one_stream:
         args.stack = 0
-        if args.xsq_cached or args.chained:
-            sys.exit("bench.py: --xsq-cached and --chained go with the stack launch only")
+        args.chained = False                      # per-layer calls: independent layers
+        if args.xsq_cached:
+            sys.exit("bench.py: --xsq-cached goes with the stack launch only")
     if args.stack > 0:
         for l in layers:
             l.xsq_forward = None
@@ -396,7 +417,7 @@ def main():
                 l.xsq_forward = torch.empty(l.spec.R, dtype=torch.float32, device="cuda")
                 vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
         entries, prev = [], None
-        fused_norms = args.chained and not args.sweep_norms
+        fused_norms = args.chained and not args.sweep_norms and specs[0].dtype == workloads.BF16
         for l in layers:
             sib = not args.no_siblings and _is_sibling(l.spec.name)
             G, above, g_blocks = l.G, None, None
@@ -482,9 +503,15 @@ def main():
     bf16 = specs[0].dtype == workloads.BF16
     e = 2 if bf16 else 4
     sfx = "bf16" if bf16 else "f32"
-    # algorithmic HBM bytes per launch: kept operand rows once, W resp. dW once, all of dX (zeros included)
+    # algorithmic HBM bytes per launch: kept operand rows once, W resp. dW once, and dX: all of it (zeros
+    # included) for independent layers, the kept rows and their block sums of squares in the chain
+    def dx_bytes(l):
+        if not args.chained:
+            return l.spec.R * l.spec.K_in * e
+        kept = int(l.plan.cntA.item()) * l.spec.T
+        return kept * l.spec.K_in * e + (kept * ((l.spec.K_in + 31) // 32) * 4 if l.sq_blocks is not None else 0)
     dg_bytes = sum(int(l.plan.cntA.item()) * l.spec.T * l.spec.K_out * e + l.spec.K_in * l.spec.K_out * e
-                   + l.spec.R * l.spec.K_in * e for l in layers) / len(layers)
+                   + dx_bytes(l) for l in layers) / len(layers)
     wg_bytes = sum(int(l.plan.cntW.item()) * (l.spec.K_out + l.spec.K_in) * e + 4 * l.spec.K_in * l.spec.K_out
                    for l in layers) / len(layers)
     # a launch may cover several layers (siblings): flops and bytes per launch follow the launch count
@@ -585,13 +612,13 @@ def main():
                    + ("" if args.no_siblings else ", data halves of V, K, Q of a block in shared launches")
                    + f", weight gradients sliced for {args.wgrad_fill or 384} workgroups"
                    + (", layers chained (each dX buffer is the next G, dropped samples stay dropped and unwritten"
-                      + (", row norms of G swept" if args.sweep_norms else ", row norms of G from the dgrad above")
-                      + ")" if args.chained else "")
+                      + (", row norms of G from the dgrad above" if fused_norms else ", row norms of G swept")
+                      + ")" if args.chained else ", independent layers (every G an input, swept for its row norms)")
                    + (", row norms of X cached before the timed region" if args.xsq_cached else "")
                    if stack is not None else
                    ("eager" if args.eager else "hip_graph") +
                    (", one stream" if args.one_stream else f", dW halves on {args.side_streams} side streams")),
-        "config": {"workload": args.workload, "layers": len(layers), "N": specs[0].N, "T": specs[0].T,
+        "config": {"workload": args.workload, "layers": len(layers), "chained": bool(args.chained), "N": specs[0].N, "T": specs[0].T,
                    "rho": [min(s.rho for s in specs), max(s.rho for s in specs)], "nu": specs[0].nu},
         "kept_flop_fraction": kept_fraction,
         "dense_ms_per_step": dict(dense_ms, note=dense_note),

@@ -237,12 +237,14 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
     double w[E];
     double part = 0.0;
     int cnt = 0;   // per wavefront, from ballots (scalar work, beside the vector sums)
+    float open_max = 0.0f;   // largest score of this thread that is still open
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const bool pos = a[j] > 0.0f;
         w[j] = pos ? (double)a[j] : 0.0;
         part += w[j];
         cnt += ballot_count(pos);
+        open_max = pos && a[j] > open_max ? a[j] : open_max;
     }
     double S;
     int nonzero;
@@ -262,14 +264,23 @@ __device__ void keep_probs_regs(const float (&a)[E], double budget, float (&prob
             break;
         }
         c = rem / S;
-        part = 0.0;
         cnt = 0;
+        // The product is monotone in the score, rounding included: a thread whose largest open score
+        // stays below one has nothing to fix, and its partial sum, the same additions over the same
+        // values, is the one it already holds.  A wavefront without any thread that fixes something
+        // skips the round's arithmetic (in the later rounds that is most of them).
+        if (__ballot(c * (double)open_max >= 1.0) != 0ull) {
+            part = 0.0;
+            open_max = 0.0f;
 #pragma unroll
-        for (int j = 0; j < E; ++j) {
-            const bool cap = c * w[j] >= 1.0;
-            w[j] = cap ? 0.0 : w[j];
-            part += w[j];
-            cnt += ballot_count(cap);
+            for (int j = 0; j < E; ++j) {
+                const bool cap = c * w[j] >= 1.0;
+                w[j] = cap ? 0.0 : w[j];
+                part += w[j];
+                cnt += ballot_count(cap);
+                const float still = (float)w[j];   // exact: a score, or zero
+                open_max = still > open_max ? still : open_max;
+            }
         }
         double S_next;
         int newly;

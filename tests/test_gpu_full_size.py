@@ -183,13 +183,19 @@ def test_full_size_sibling_layers_in_shared_launches(vb, workload):
         _check_against_oracle(spec, G, X, W, plan, dX, dW, 2)
 
 
-def test_full_size_block_in_the_chained_launch(vb):
-    """bench.py --chained at full size, one attention block of bert_base: the out-projection, then V, K, Q as
+@pytest.mark.parametrize("workload,block,fused", [("bert_base", "b5", False), ("bert_large", "b11", True)])
+def test_full_size_block_in_the_chained_launch(vb, workload, block, fused):
+    """The chained launch of bench.py at full size, one attention block: the out-projection, then V, K, Q as
     siblings that take its dX as their G, know which samples it kept (kept_above) and leave the rows of the
     samples they drop unwritten.  The oracle computes the out-projection on its own and hands its dX (bf16) to
-    V, K, Q; the GPU gets the same tensor with NaN in the rows of dropped samples, in one stack call."""
+    V, K, Q; the GPU gets the same tensor with NaN in the rows of dropped samples, in one stack call.
+    fused (the benchmark's default form): the out-projection's dgrad also leaves the block sums of squares of
+    its dX, and V, K, Q take the row norms of their G from block sums instead of sweeping it.  Data flows from
+    the oracle to the GPU only: the block sums handed to V, K, Q are the oracle's, of the oracle's dX; what the
+    GPU's dgrad emitted is checked against those within the tolerance of dX, and bit for bit against a sweep of
+    the dX it wrote."""
     from tests.gpu_util import to_device, from_device, plan_to_numpy, compare_plan, rel_l2, rel_l2_rows, rel_l2_tiles
-    specs = {s.name.split(".")[2]: s for s in workloads.config("bert_base") if s.name.split(".")[1] == "b5"}
+    specs = {s.name.split(".")[2]: s for s in workloads.config(workload) if s.name.split(".")[1] == block}
     o = specs["o"]
     G, X, W = workloads.make_layer(o)
     want_o, dX_o, _ = oracle.linear_backward(G, X, W, o.dtype, o.N, o.T, o.rho, o.nu, o.seed, o.layer, 1)
@@ -199,6 +205,14 @@ def test_full_size_block_in_the_chained_launch(vb):
     g2 = to_device(G2, BF16)
     g2.view(o.N, o.T, -1)[torch.from_numpy(~kept).cuda()] = float("nan")
     above = torch.from_numpy(want_o.maskA.astype(np.uint8)).cuda()
+    nb = (o.K_in + 31) // 32
+    blocks_o = torch.full((nb, o.R), float("nan"), device="cuda") if fused else None
+    want_blocks = g2_blocks = None
+    if fused:
+        want_blocks = oracle.block_sumsq(G2, BF16)                       # [R, nb]
+        poisoned = want_blocks.copy()
+        poisoned[np.repeat(~kept, o.T)] = np.nan                         # rows of dropped samples are never read
+        g2_blocks = torch.from_numpy(np.ascontiguousarray(poisoned.T)).cuda()
     entries, outs, keep, host = [], [], [], []
     for k, name in enumerate(["o", "v", "k", "q"]):
         sp = specs[name]
@@ -212,7 +226,9 @@ def test_full_size_block_in_the_chained_launch(vb):
         dW = torch.full((sp.K_out, sp.K_in), float("nan"), dtype=torch.float32, device="cuda")
         entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 1), True, plan, dX, dW, ws,
                                      sibling=name in "kq", kept_above=None if name == "o" else above,
-                                     leave_dropped_rows=True, wgrad_fill=64))
+                                     leave_dropped_rows=True, wgrad_fill=64,
+                                     dx_sq_blocks=blocks_o if name == "o" else None,
+                                     g_sq_blocks=None if name == "o" else g2_blocks))
         outs.append((sp, plan, dX, dW))
         keep.append((g, x, w, ws))
         host.append((G if name == "o" else G2, Xs, Ws))
@@ -234,6 +250,22 @@ def test_full_size_block_in_the_chained_launch(vb):
         assert np.isnan(got_dX[~rows]).all() and np.isfinite(got_dX[rows]).all()
         assert rel_l2_rows(got_dX[rows], want_dX[rows]) <= 1e-2
         assert rel_l2_tiles(from_device(dW), want_dW) <= 1e-2
+    if fused:
+        rows = np.repeat(kept, o.T)
+        got_blocks = blocks_o.cpu().numpy().T
+        assert np.isnan(got_blocks[~rows]).all() and np.isfinite(got_blocks[rows]).all()
+        num = np.abs(got_blocks[rows].astype(np.float64) - want_blocks[rows]).sum(axis=1)
+        den = want_blocks[rows].astype(np.float64).sum(axis=1)
+        assert (num[den > 0] / den[den > 0]).max() <= 4e-2               # squares: twice the tolerance of dX
+        # the same tree as a sweep over the dX this launch wrote (dropped rows zeroed for the sweep, which reads them)
+        dX_o = outs[0][2].clone()
+        dX_o.view(o.N, o.T, -1)[torch.from_numpy(~kept).cuda()] = 0.0
+        sq_blocks = torch.full((o.R,), float("nan"), device="cuda")
+        sq_sweep = torch.full((o.R,), float("nan"), device="cuda")
+        vb.vcas_row_norms_from_blocks(o.N, o.T, o.K_in, blocks_o, above, sq_blocks, None)
+        vb.vcas_row_norms(vb.shape_of(o.N, o.T, 8, o.K_in, BF16), dX_o, None, None, sq_sweep, None, None)
+        torch.cuda.synchronize()
+        assert torch.equal(sq_blocks.view(torch.int32), sq_sweep.view(torch.int32))
 
 
 def test_variance_probe_at_vit_size_with_eight_draws(vb):

@@ -676,7 +676,10 @@ def test_stack_of_layers_equals_layer_by_layer_calls(vb, group, streams):
              workloads.LayerSpec("st1", F32, 6, 50, 72, 136, 0.6, 0.4, layer=1, seed=4, gen_seed=2, token_sigma=0.5),
              workloads.LayerSpec("st2", BF16, 12, 300, 4096, 64, 0.5, 0.5, layer=2, seed=4, gen_seed=3, token_sigma=0.5),
              workloads.LayerSpec("st3", BF16, 9, 33, 136, 200, 0.7, 0.5, layer=3, seed=4, gen_seed=4, token_sigma=0.5),
-             workloads.LayerSpec("st4", BF16, 16, 64, 256, 768, 1.0, 1.0, layer=4, seed=4, gen_seed=5, token_sigma=0.5)]
+             workloads.LayerSpec("st4", BF16, 16, 64, 256, 768, 1.0, 1.0, layer=4, seed=4, gen_seed=5, token_sigma=0.5),
+             # long vectors: sample norms from the tail of the pass over G, SampleA inside dgrad (ragged T, wide rows)
+             workloads.LayerSpec("st5", BF16, 33, 131, 136, 264, 0.6, 0.5, layer=5, seed=4, gen_seed=6, token_sigma=0.5),
+             workloads.LayerSpec("st6", BF16, 9, 500, 72, 4104, 0.4, 0.5, layer=6, seed=4, gen_seed=7, token_sigma=0.5)]
     host, dev, refs, entries, outs = [], [], [], [], []
     for sp in specs:
         G, X, W = workloads.make_layer(sp)
@@ -712,11 +715,12 @@ def test_stack_of_layers_equals_layer_by_layer_calls(vb, group, streams):
         assert torch.equal(dX.view(torch.int16) if dX.dtype == torch.bfloat16 else dX.view(torch.int32),
                            dX_r.view(torch.int16) if dX_r.dtype == torch.bfloat16 else dX_r.view(torch.int32)), sp.name
         assert torch.equal(dW.view(torch.int32), dW_r.view(torch.int32)), sp.name
-    sp = specs[2]
-    G, X, W = host[2]
-    want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 1)
-    compare_plan(plan_to_numpy(outs[2][0]), want)
-    assert rel_l2_rows(from_device(outs[2][1]), want_dX) <= TOL[BF16] and rel_l2_tiles(from_device(outs[2][2]), want_dW) <= TOL[BF16]
+    for k in (2, 5):
+        sp = specs[k]
+        G, X, W = host[k]
+        want, want_dX, want_dW = oracle.linear_backward(G, X, W, sp.dtype, sp.N, sp.T, sp.rho, sp.nu, sp.seed, sp.layer, 1)
+        compare_plan(plan_to_numpy(outs[k][0]), want)
+        assert rel_l2_rows(from_device(outs[k][1]), want_dX) <= TOL[BF16] and rel_l2_tiles(from_device(outs[k][2]), want_dW) <= TOL[BF16]
 
 
 @pytest.mark.parametrize("group", [2, 8])
@@ -790,11 +794,14 @@ def test_sibling_layers_share_launches_and_keep_their_bits(vb, group):
         assert rel_l2_rows(from_device(outs[k][1]), want_dX) <= TOL[BF16] and rel_l2_tiles(from_device(outs[k][2]), want_dW) <= TOL[BF16]
 
 
-def test_sibling_layers_inside_a_sparse_chain(vb):
+@pytest.mark.parametrize("N,T", [(20, 64), (37, 117), (64, 70)])
+def test_sibling_layers_inside_a_sparse_chain(vb, N, T):
     """Siblings with the additions of the chained data call: a mask of samples dropped above, an elementwise
-    Jacobian each, dropped rows left unwritten.  One stack call against per-layer chained calls, bit for bit."""
+    Jacobian each, dropped rows left unwritten.  One stack call against per-layer chained calls, bit for bit.
+    With more than 4096 rows the stack takes the sample norms in the tail of the pass over G (rows counted per
+    sample across workgroups; T = 117 and 70 make workgroups straddle samples) and SampleA inside dgrad."""
     from tests.gpu_util import to_device, plan_to_numpy
-    N, T, K_in, K_out = 20, 64, 136, 264
+    K_in, K_out = 136, 264
     rng_np = np.random.default_rng(41)
     above = torch.from_numpy((rng_np.uniform(size=N) < 0.7).astype(np.uint8)).cuda()
     entries, outs, refs, keep = [], [], [], []
