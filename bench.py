@@ -421,10 +421,9 @@ def main():
         for l in layers:
             sib = not args.no_siblings and _is_sibling(l.spec.name)
             G, above, g_blocks = l.G, None, None
-            # chained: every dgrad also leaves the sums of squares of its dX by blocks of 32 columns, from
+            # chained: every dgrad also leaves the sums of squares of its dX by blocks of 64 columns, from
             # which the entry below takes the norms of its G instead of sweeping it
-            l.sq_blocks = (torch.empty(((l.spec.K_in + 31) // 32, l.spec.R), dtype=torch.float32, device="cuda")
-                           if fused_norms else None)
+            l.sq_blocks = vb.make_sq_blocks(l.spec.R, l.spec.K_in) if fused_norms else None
             if args.chained and prev is not None:
                 # a sibling takes what its elder sibling took; everybody else the dX of the entry before
                 G, above, g_blocks = ((prev_G, prev_above, prev_blocks) if _is_sibling(l.spec.name)
@@ -509,7 +508,7 @@ def main():
         if not args.chained:
             return l.spec.R * l.spec.K_in * e
         kept = int(l.plan.cntA.item()) * l.spec.T
-        return kept * l.spec.K_in * e + (kept * ((l.spec.K_in + 31) // 32) * 4 if l.sq_blocks is not None else 0)
+        return kept * l.spec.K_in * e + (kept * ((l.spec.K_in + 63) // 64) * 4 if l.sq_blocks is not None else 0)
     dg_bytes = sum(int(l.plan.cntA.item()) * l.spec.T * l.spec.K_out * e + l.spec.K_in * l.spec.K_out * e
                    + dx_bytes(l) for l in layers) / len(layers)
     wg_bytes = sum(int(l.plan.cntW.item()) * (l.spec.K_out + l.spec.K_in) * e + 4 * l.spec.K_in * l.spec.K_out

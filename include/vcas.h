@@ -187,19 +187,26 @@ vcas_status vcas_sampled_dgrad_jac(const vcas_shape *shape, const void *G, const
  * pass over HBM for those norms is avoided by letting the dgrad epilogue add up the
  * squares of what it stores.
  * vcas_sampled_dgrad_norms: vcas_sampled_dgrad_jac (J may be null: no Jacobian)
- * that also writes, for every row r of a kept sample and every block b of 32
- * columns, sq_blocks[b * R + r] = sum of squares of dX[r, 32 b .. 32 b + 31] as
- * stored (after the rounding to bf16), b < nb = ceil(K_in / 32), block-major so
- * that both sides touch neighbouring addresses; pairwise, neighbours first, i.e.
- * the 32-column subtrees of the order vcas_row_norms uses.  Rows of dropped
- * samples are not written there.  bf16 only (VCAS_EDTYPE otherwise).
+ * that also writes, for every row r of a kept sample and every block b of 64
+ * columns, the sum of squares of dX[r, 64 b .. 64 b + 63] as stored (after the
+ * rounding to bf16), b < nb = ceil(K_in / 64); pairwise, neighbours first, i.e.
+ * the 64-column subtrees of the order vcas_row_norms uses.  Layout: four
+ * neighbouring blocks of a row side by side,
+ *   sq_blocks[((b / 4) * R + r) * 4 + b % 4],
+ * so that both sides move 16 bytes per row and neighbouring rows touch
+ * neighbouring addresses; vcas_sq_blocks_bytes gives the size.  Slots with
+ * b >= nb and rows of dropped samples are not written.  bf16 only (VCAS_EDTYPE
+ * otherwise).  sq_blocks 16-byte aligned.
  * vcas_row_norms_from_blocks: sq[r] = the nb block sums of row r added pairwise,
  * neighbours first (zero-padded to a power of two): bit for bit what
  * vcas_row_norms computes from the stored matrix itself.  K = row length of that
  * matrix; sample_mask (N bytes, null: all): rows of samples with mask 0 are not
  * read and get 0 (pass the producing layer's maskA).  norm (null: skip): the
  * per-sample Frobenius norms, as vcas_row_norms' gnorm.
+ * vcas_sq_blocks_bytes (host query): bytes of the block sums of a matrix of R
+ * rows and K columns, 16 R ceil(ceil(K / 64) / 4); 0 on bad sizes.
  */
+size_t vcas_sq_blocks_bytes(int64_t R, int32_t K);
 vcas_status vcas_sampled_dgrad_norms(const vcas_shape *shape, const void *G, const void *W, const float *p,
                                      const int32_t *idxA, const int32_t *cntA, const void *J, void *dX,
                                      float *sq_blocks, void *stream);
@@ -296,12 +303,13 @@ typedef struct {
                            (fp32 sums in another order) across values. */
     /* The norms of G from the launch that wrote G (see vcas_sampled_dgrad_norms), for entries that feed
        each other; bf16 only, both optional. */
-    float *dx_sq_blocks;       /* [ceil(K_in/32) * R] (block-major), device: this entry's dgrad also leaves the block sums of
+    float *dx_sq_blocks;       /* vcas_sq_blocks_bytes(R, K_in) bytes, device: this entry's dgrad also leaves the block sums of
                                   squares of its dX here (rows of kept samples only); needs dX */
-    const float *g_sq_blocks;  /* [ceil(K_out/32) * R], device: block sums of squares of this entry's G, as the
-                                  entry that wrote G left them; the pass over G is replaced by a pass over
-                                  them (the same bits).  Needs kept_above: rows of samples dropped above have
-                                  no block sums */
+    const float *g_sq_blocks;  /* vcas_sq_blocks_bytes(R, K_out) bytes, device: block sums of squares of this entry's G, as
+                                  the entry that wrote G left them; the pass over G is replaced by a pass over
+                                  them (the same bits), which for N <= 64 and T <= 1024 also leaves the sample
+                                  norms, so that dgrad decides SampleA itself and no launch of its own does.
+                                  Needs kept_above: rows of samples dropped above have no block sums */
 } vcas_layer_args;
 
 /*

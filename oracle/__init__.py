@@ -110,13 +110,14 @@ def row_sumsq(A: np.ndarray, dtype: int, T: int = 1, sample_keep: np.ndarray | N
     return out
 
 
-def block_sumsq(A: np.ndarray, dtype: int) -> np.ndarray:
-    """Sums of squares of A[R,K] by blocks of 32 columns, [R, ceil(K/32)] fp32: the 32-column subtrees of the
-    pairwise order of row_sumsq (what the dgrad of the layer above leaves for a layer inside a stack, Sec. 4)."""
+def block_sumsq(A: np.ndarray, dtype: int, width: int = 64) -> np.ndarray:
+    """Sums of squares of A[R,K] by blocks of `width` columns (a power of two), [R, ceil(K/width)] fp32: subtrees
+    of the pairwise order of row_sumsq (what the dgrad of the layer above leaves for a layer inside a stack, Sec. 4)."""
     A = _check(A, dtype)
     R, K = A.shape
-    out = np.empty((R, (K + 31) // 32), np.float32)
-    _L().orc_block_sumsq(_p(A), C.c_int(dtype), C.c_int64(R), C.c_int(K), _p(out))
+    assert width >= 1 and width & (width - 1) == 0
+    out = np.empty((R, (K + width - 1) // width), np.float32)
+    _L().orc_block_sumsq(_p(A), C.c_int(dtype), C.c_int64(R), C.c_int(K), C.c_int(width), _p(out))
     return out
 
 

@@ -196,24 +196,26 @@ void orc_row_sumsq(const void *A, int dtype, int64_t R, int K, int T,
  * The same row sums in two stages, the way a layer inside a stack gets them
  * from the launch that wrote the matrix (Sec. 4: a sampler at every layer needs
  * the norms of the gradient the layer above has just produced): first the sum of
- * squares of every block of 32 consecutive columns (pairwise, neighbours first;
- * a last, shorter block is padded with +0), blocks[t * nb + b], nb = ceil(K/32);
- * then, per row, the nb block sums pairwise, neighbours first.  Both stages are
- * subtrees of the one tree orc_row_sumsq forms, so the results are its bits.
+ * squares of every block of `width` consecutive columns (width a power of two;
+ * pairwise, neighbours first; a last, shorter block is padded with +0),
+ * blocks[t * nb + b], nb = ceil(K/width); then, per row, the nb block sums
+ * pairwise, neighbours first.  Both stages are subtrees of the one tree
+ * orc_row_sumsq forms, so the results are its bits, whatever the width.
  */
-void orc_block_sumsq(const void *A, int dtype, int64_t R, int K, float *blocks)
+void orc_block_sumsq(const void *A, int dtype, int64_t R, int K, int width, float *blocks)
 {
-    int nb = (K + 31) / 32;
-    float sq[32];
+    int nb = (K + width - 1) / width;
+    float *sq = (float *)malloc((size_t)width * sizeof(float));
     for (int64_t t = 0; t < R; ++t)
         for (int b = 0; b < nb; ++b) {
-            int n = K - 32 * b < 32 ? K - 32 * b : 32;
+            int n = K - width * b < width ? K - width * b : width;
             for (int k = 0; k < n; ++k) {
-                float v = elem(A, dtype, (size_t)t * K + 32 * b + k);
+                float v = elem(A, dtype, (size_t)t * K + (size_t)width * b + k);
                 sq[k] = v * v;
             }
             blocks[t * nb + b] = pairwise_sum_f32(sq, n);
         }
+    free(sq);
 }
 
 void orc_rows_from_blocks(const float *blocks, int64_t R, int nb, int T, const uint8_t *sample_keep, float *out)

@@ -20,7 +20,7 @@ STATUS = {0: "VCAS_OK", 1: "VCAS_EINVAL", 2: "VCAS_ENULL", 3: "VCAS_EDTYPE", 4: 
 EXPORTS = [
     "vcas_status_string", "vcas_workspace_bytes", "vcas_workspace_init", "vcas_row_norms", "vcas_keep_probs",
     "vcas_sample_compact", "vcas_leverage_scores", "vcas_row_scale", "vcas_sampled_dgrad", "vcas_sampled_dgrad_jac", "vcas_sampled_wgrad",
-    "vcas_static_scratch_bytes", "vcas_sampled_wgrad_static", "vcas_sampled_dgrad_norms", "vcas_row_norms_from_blocks",
+    "vcas_static_scratch_bytes", "vcas_sampled_wgrad_static", "vcas_sampled_dgrad_norms", "vcas_row_norms_from_blocks", "vcas_sq_blocks_bytes",
     "vcas_linear_backward", "vcas_backward_stack", "vcas_backward_data", "vcas_backward_data_chained", "vcas_backward_weight", "vcas_backward_weight_cached",
     "vcas_variance_probe", "vcas_sparsity_ratio", "vcas_grad_stats_update", "vcas_grad_stats_variance",
     "vcas_sq_diff_strided", "vcas_controller_update", "vcas_profile_begin", "vcas_profile_end",
@@ -198,6 +198,21 @@ def vcas_sampled_dgrad_jac(shape: Shape, G, W, p, idxA, cntA, J, dX):
 def vcas_sampled_dgrad_norms(shape: Shape, G, W, p, idxA, cntA, J, dX, sq_blocks):
     _check(lib().vcas_sampled_dgrad_norms(C.byref(shape), _ptr(G), _ptr(W), _ptr(p), _ptr(idxA), _ptr(cntA), _ptr(J),
                                           _ptr(dX), _ptr(sq_blocks), _stream()), "vcas_sampled_dgrad_norms")
+
+
+def vcas_sq_blocks_bytes(R: int, K: int) -> int:
+    f = lib().vcas_sq_blocks_bytes
+    f.restype = C.c_size_t
+    return int(f(C.c_int64(R), C.c_int32(K)))
+
+
+def make_sq_blocks(R: int, K: int, fill=None, device="cuda") -> torch.Tensor:
+    """Device buffer for the block sums of squares of an [R, K] matrix, viewed [groups, R, 4] (see include/vcas.h)."""
+    n = vcas_sq_blocks_bytes(R, K) // 4
+    if n == 0:
+        raise VcasError("bad sizes")
+    t = torch.empty(n, dtype=torch.float32, device=device) if fill is None else torch.full((n,), fill, dtype=torch.float32, device=device)
+    return t.view(-1, R, 4)
 
 
 def vcas_row_norms_from_blocks(N: int, T: int, K: int, sq_blocks, sample_mask, sq, norm):

@@ -57,6 +57,9 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
                        const InlineSampleA *sample_a, float *sq_blocks, hipStream_t st);
 vcas_status rows_from_blocks(const float *blocks, int64_t R, int K, int T, const uint8_t *keep, float *const *outs,
                              int n_out, hipStream_t st);
+bool sample_norms_from_blocks_fits(int N, int T);
+vcas_status sample_norms_from_blocks(const float *blocks, int N, int T, int K, const uint8_t *keep, float *const *outs,
+                                     float *const *gnorms, int n_out, hipStream_t st);
 vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int n, bool fill, int64_t expected_rows,
                              hipStream_t st);
 vcas_status wgrad_bf16_batch(const WgradItem *items, int n, int tile, hipStream_t st);
@@ -331,7 +334,15 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
     float *uw = token_sampling ? uniforms_of(s, workspace) : nullptr;
     // together: the square roots SampleW needs travel in the plan's score and q arrays until
     // SampleW overwrites them with their final contents
-    if (chain.g_sq_blocks) {
+    // Inside a stack, with the block sums of G at hand: one workgroup per sample adds them to row
+    // sums and the sample's norm, and the dgrad workgroups decide SampleA themselves from the N
+    // norms, so that the chain row norms -> SampleA -> dX is two launches instead of three.
+    const bool norms_for_dgrad = sample_a_in_dgrad && chain.g_sq_blocks && dX && s.dtype == VCAS_BF16 && s.N <= 64 &&
+                                 sample_norms_from_blocks_fits(s.N, s.T);
+    if (norms_for_dgrad) {
+        float *outs[1] = {pl.gsq}, *gnorms[1] = {pl.gnorm};
+        VCAS_TRY(sample_norms_from_blocks(chain.g_sq_blocks, s.N, s.T, s.K_out, chain.kept_above, outs, gnorms, 1, st));
+    } else if (chain.g_sq_blocks) {
         // the norms of G come from the launch that wrote G; those of X are left to the weight half
         float *outs[1] = {pl.gsq};
         VCAS_TRY(rows_from_blocks(chain.g_sq_blocks, R, s.K_out, s.T, chain.kept_above, outs, 1, st));
@@ -342,13 +353,14 @@ static vcas_status data_half(const vcas_shape &s, const void *G, const void *X, 
         VCAS_TRY(row_sumsq(G, s.dtype, R, s.K_out, s.T, chain.kept_above, pl.gsq, st));
     // SampleA keeps about N*rho samples (Sec. 4.1): the row count the dgrad tile choice plans for
     const int64_t rows_expected = (int64_t)((double)R * rho + 0.5);
-    if (sample_a_in_dgrad && dX && s.dtype == VCAS_BF16 && s.N <= 64 && R <= 4096) {
+    if (norms_for_dgrad || (sample_a_in_dgrad && dX && s.dtype == VCAS_BF16 && s.N <= 64 && R <= 4096)) {
         // one launch and its gap less on the chain row norms -> SampleA -> dX: the dgrad workgroups
         // decide SampleA themselves.  Worth it only while the vector of row norms is short: every
         // workgroup reads all of it (BERT-base, R = 4096: step 2.78 -> 2.70 ms; ViT, N = 64,
         // R = 12608: 3.93 -> 4.44 ms)
-        InlineSampleA sa;
-        sa.gsq = pl.gsq;
+        InlineSampleA sa = {};
+        if (norms_for_dgrad) sa.norms = pl.gnorm;
+        else sa.gsq = pl.gsq;
         sa.budget = (double)s.N * rho;
         sa.seed = rng.seed;
         sa.layer = rng.layer;
@@ -417,6 +429,8 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
     const vcas_shape &s = layers[0].shape;
     const int64_t R = (int64_t)s.N * s.T;
     const bool in_dgrad = s.N <= 64 && R <= 4096;
+    // with the block sums of G at hand the sample norms come with the row sums and dgrad decides from those (see data_half)
+    const bool norms_for_dgrad = layers[0].g_sq_blocks && s.N <= 64 && sample_norms_from_blocks_fits(s.N, s.T);
     RowNormGroup norms = {};
     SampleAGroup samplers = {};
     DgradProblem probs[kMaxSiblings];
@@ -426,7 +440,7 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         norms.A[i] = static_cast<const uint4 *>(a.G);
         norms.out[i] = a.plan.gsq;
         norms.keep[i] = a.kept_above;
-        InlineSampleA sa;
+        InlineSampleA sa = {};
         sa.gsq = a.plan.gsq;
         sa.budget = (double)s.N * a.rho;
         sa.seed = a.rng.seed;
@@ -448,7 +462,8 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         q.dX = static_cast<uint16_t *>(a.dX);
         q.J = static_cast<const uint16_t *>(a.J);
         q.sa = sa;
-        if (!in_dgrad) q.sa.gsq = nullptr;
+        if (!in_dgrad || norms_for_dgrad) q.sa.gsq = nullptr;
+        if (norms_for_dgrad) q.sa.norms = a.plan.gnorm;
         q.sq_blocks = a.dx_sq_blocks;
         if (a.rho > rho_max) rho_max = a.rho;
     }
@@ -456,17 +471,23 @@ static vcas_status data_half_siblings(const vcas_layer_args *layers, int n, hipS
         // norms of G from the launch that wrote it: one pass over the block sums serves every
         // sibling that was handed the same G; the others take a pass of their own
         for (int i = 0; i < n;) {
-            float *outs[kMaxSiblings];
+            float *outs[kMaxSiblings], *gnorms[kMaxSiblings];
             int m = 0;
             for (; i + m < n && layers[i + m].g_sq_blocks == layers[i].g_sq_blocks &&
-                   layers[i + m].kept_above == layers[i].kept_above; ++m)
+                   layers[i + m].kept_above == layers[i].kept_above; ++m) {
                 outs[m] = layers[i + m].plan.gsq;
-            VCAS_TRY(rows_from_blocks(layers[i].g_sq_blocks, R, s.K_out, s.T, layers[i].kept_above, outs, m, st));
+                gnorms[m] = layers[i + m].plan.gnorm;
+            }
+            if (norms_for_dgrad)
+                VCAS_TRY(sample_norms_from_blocks(layers[i].g_sq_blocks, s.N, s.T, s.K_out, layers[i].kept_above, outs,
+                                                  gnorms, m, st));
+            else
+                VCAS_TRY(rows_from_blocks(layers[i].g_sq_blocks, R, s.K_out, s.T, layers[i].kept_above, outs, m, st));
             i += m;
         }
     } else
         VCAS_TRY(row_sumsq_group(norms, n, s.dtype, R, s.K_out, s.T, st));
-    if (!in_dgrad) VCAS_TRY(sampler_a_group(samplers, n, s.N, s.T, st));
+    if (!in_dgrad && !norms_for_dgrad) VCAS_TRY(sampler_a_group(samplers, n, s.N, s.T, st));
     return dgrad_bf16_group(s, probs, n, layers[0].leave_dropped_rows == 0, (int64_t)((double)R * rho_max + 0.5), st);
 }
 
@@ -724,8 +745,14 @@ vcas_status vcas_sampled_dgrad_norms(const vcas_shape *shape, const void *G, con
     VCAS_TRY(check_gemm_limits(shape));
     if (shape->dtype != VCAS_BF16) return VCAS_EDTYPE;
     if (!G || !W || !p || !idxA || !cntA || !dX || !sq_blocks) return VCAS_ENULL;
-    if (!aligned16(G) || !aligned16(W) || (J && !aligned16(J)) || !aligned16(dX)) return VCAS_EINVAL;
+    if (!aligned16(G) || !aligned16(W) || (J && !aligned16(J)) || !aligned16(dX) || !aligned16(sq_blocks)) return VCAS_EINVAL;
     return dispatch_dgrad(*shape, G, W, p, idxA, cntA, dX, J, true, 0, as_stream(stream), sq_blocks);
+}
+
+size_t vcas_sq_blocks_bytes(int64_t R, int32_t K)
+{
+    if (R <= 0 || K <= 0) return 0;
+    return (size_t)16 * (size_t)R * (size_t)(((K + 63) / 64 + 3) / 4);
 }
 
 vcas_status vcas_row_norms_from_blocks(int32_t N, int32_t T, int32_t K, const float *sq_blocks,
@@ -733,6 +760,7 @@ vcas_status vcas_row_norms_from_blocks(int32_t N, int32_t T, int32_t K, const fl
 {
     if (N <= 0 || T <= 0 || K <= 0 || (int64_t)N * T > (int64_t)1 << 30) return VCAS_EINVAL;
     if (!sq_blocks || !sq) return VCAS_ENULL;
+    if (!aligned16(sq_blocks)) return VCAS_EINVAL;
     float *outs[1] = {sq};
     VCAS_TRY(rows_from_blocks(sq_blocks, (int64_t)N * T, K, T, sample_mask, outs, 1, as_stream(stream)));
     if (norm) VCAS_TRY(sample_norms(sq, N, T, norm, as_stream(stream)));
@@ -808,6 +836,7 @@ vcas_status vcas_backward_stack(const vcas_layer_args *layers, int32_t L, int32_
         if ((a.g_sq_blocks || a.dx_sq_blocks) && a.shape.dtype != VCAS_BF16) return VCAS_EDTYPE;
         if (a.dx_sq_blocks && !a.dX) return VCAS_ENULL;
         if (a.g_sq_blocks && !a.kept_above) return VCAS_ENULL;
+        if (!aligned16(a.g_sq_blocks) || !aligned16(a.dx_sq_blocks)) return VCAS_EINVAL;
         if (!aligned16(a.G) || !aligned16(a.X) || (a.W && !aligned16(a.W)) || (a.dX && !aligned16(a.dX)) ||
             (a.dW && !aligned16(a.dW)) || !aligned16(a.workspace))
             return VCAS_EINVAL;

@@ -83,24 +83,28 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
     __shared__ float sa_norm[64], sa_p[64];
     __shared__ int sa_count;
     int cnt;
-    if (sa.gsq != nullptr) {
+    if (sa.gsq != nullptr || sa.norms != nullptr) {
         // SampleA decided here, by every workgroup for itself (N <= 64: a few microseconds of one
-        // wavefront's work on 4 N T bytes that sit in L2), instead of by a launch of its own in
-        // front of this one; the first workgroup writes the plan's fields for everybody else.
+        // wavefront's work), instead of by a launch of its own in front of this one; the first
+        // workgroup writes the plan's fields for everybody else.  The sample norms are either given
+        // or taken here from the row sums (4 N T bytes that sit in L2: short vectors only).
         const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
         const uint32_t draw = sa.draw + (sa.draw_offset ? *sa.draw_offset : 0u);   // fetched beside the norms
-        if (T <= 128) sample_norms_batched<8, 2>(sa.gsq, wave_, NW, N, T, sa_norm);
-        else sample_norms_batched<4, 8>(sa.gsq, wave_, NW, N, T, sa_norm);
-        __syncthreads();
+        const bool given = sa.norms != nullptr;
+        if (!given) {
+            if (T <= 128) sample_norms_batched<8, 2>(sa.gsq, wave_, NW, N, T, sa_norm);
+            else sample_norms_batched<4, 8>(sa.gsq, wave_, NW, N, T, sa_norm);
+            __syncthreads();
+        }
         if (wave_ == 0) {
-            const float a = lane_ < N ? sa_norm[lane_] : 0.0f;
+            const float a = lane_ < N ? (given ? sa.norms[lane_] : sa_norm[lane_]) : 0.0f;
             const SampleADecision d = sample_a_wave(a, N, sa.budget, sa.seed, sa.layer, draw);
             if (lane_ < N) sa_p[lane_] = d.pr;
             if (d.keep) idx_staged[d.below] = lane_;
             if (lane_ == 0) sa_count = d.count;
             if (blockIdx.x == 0) {
                 if (lane_ < N) {
-                    sa.gnorm[lane_] = a;
+                    if (!given) sa.gnorm[lane_] = a;
                     sa.p[lane_] = d.pr;
                     sa.maskA[lane_] = d.keep ? 1 : 0;
                 }
@@ -384,7 +388,6 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
     if (J) fill_strip(std::true_type{});
     else fill_strip(std::false_type{});
     __builtin_amdgcn_wave_barrier();   // the strip is this wavefront's own: its LDS accesses execute in order
-    const int nb = (K_in + 31) >> 5;
     int32_t dst_of[TM * 4];
     uint4 val[TM * 4];
 #pragma unroll
@@ -400,22 +403,25 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
         if (dst_of[q] >= 0 && col < K_in) *reinterpret_cast<uint4 *>(dX + (int64_t)dst_of[q] * K_in + col) = val[q];
     }
     if (sq_blocks) {
-        // Sums of squares of the stored values by blocks of 32 columns, pairwise with neighbours
-        // first: a lane adds its eight columns (three levels), the four lanes of a block the rest.
+        // Sums of squares of the stored values by blocks of 64 columns (this wavefront's strip is
+        // exactly one), pairwise with neighbours first: a lane adds its eight columns (three levels),
+        // the eight lanes of a row the rest.  Four neighbouring blocks of a row lie side by side:
+        // sq_blocks[((blk / 4) * R + row) * 4 + blk % 4].
+        const int blk = (n0 + wn0) >> 6;
+        const int nb = (K_in + 63) >> 6;
 #pragma unroll
         for (int q = 0; q < TM * 4; ++q) {
-            const int row = q * 8 + (lane >> 3);
-            const int col = n0 + wn0 + (((lane & 7) ^ esw(row)) << 3);
             const uint4 w = val[q];
             const float q0 = bf16_lo(w.x) * bf16_lo(w.x), q1 = bf16_hi(w.x) * bf16_hi(w.x);
             const float q2 = bf16_lo(w.y) * bf16_lo(w.y), q3 = bf16_hi(w.y) * bf16_hi(w.y);
             const float q4 = bf16_lo(w.z) * bf16_lo(w.z), q5 = bf16_hi(w.z) * bf16_hi(w.z);
             const float q6 = bf16_lo(w.w) * bf16_lo(w.w), q7 = bf16_hi(w.w) * bf16_hi(w.w);
             float t = ((q0 + q1) + (q2 + q3)) + ((q4 + q5) + (q6 + q7));
-            t = t + dpp_move<0xB1>(t);   // slots (0,1) and (2,3) of the block
-            t = t + dpp_move<0x4E>(t);   // the two halves
-            const int blk32 = col >> 5;
-            if ((lane & 3) == 0 && dst_of[q] >= 0 && blk32 < nb) sq_blocks[(int64_t)blk32 * R + dst_of[q]] = t;
+            t = t + dpp_move<0xB1>(t);    // slots (0,1), (2,3), (4,5), (6,7)
+            t = t + dpp_move<0x4E>(t);    // the two halves of each 32 columns
+            t = t + dpp_move<0x141>(t);   // the two 32-column halves (the other quad of the row's eight lanes)
+            if ((lane & 7) == 0 && dst_of[q] >= 0 && blk < nb)
+                sq_blocks[((int64_t)(blk >> 2) * R + dst_of[q]) * 4 + (blk & 3)] = t;
         }
     }
 }
@@ -500,7 +506,7 @@ vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int
     if (n < 1 || n > kMaxSiblings) return VCAS_EINVAL;
     DgradGroup grp = {};
     for (int i = 0; i < n; ++i) {
-        if (probs[i].sa.gsq && s.N > 64) return VCAS_EINVAL;
+        if ((probs[i].sa.gsq || probs[i].sa.norms) && s.N > 64) return VCAS_EINVAL;
         grp.prob[i] = probs[i];
     }
     const int64_t R = (int64_t)s.N * s.T;
@@ -519,7 +525,7 @@ vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int
 // J: elementwise Jacobian [R, K_in] multiplied into dX, or null.  fill: write the zero rows of
 // dropped samples (false: leave them as they are).
 // sample_a (null: SampleA has been decided, p / idxA / cntA hold its outcome): the kernel decides
-// it itself from the row norms and writes the plan's SampleA fields; N <= 64 only.
+// it itself from the row sums or the sample norms and writes the plan's SampleA fields; N <= 64 only.
 vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const float *p, const int32_t *idxA,
                        const int32_t *cntA, void *dX, const void *J, bool fill, int64_t expected_rows,
                        const InlineSampleA *sample_a, float *sq_blocks, hipStream_t st)

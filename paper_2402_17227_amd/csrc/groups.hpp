@@ -20,7 +20,7 @@ struct DgradProblem {
     uint16_t *dX;
     const uint16_t *J;   // null: no Jacobian
     InlineSampleA sa;    // sa.gsq null: SampleA has been decided, p / idxA / cntA hold its outcome
-    float *sq_blocks;    // null, or [R][ceil(K_in/32)]: sums of squares of the written dX by blocks of 32 columns
+    float *sq_blocks;    // null, or the sums of squares of the written dX by blocks of 64 columns (layout: rows_from_blocks)
 };
 struct DgradGroup {
     DgradProblem prob[kMaxSiblings];

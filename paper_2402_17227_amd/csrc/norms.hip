@@ -148,49 +148,115 @@ __global__ __launch_bounds__(256) void row_sumsq_pair_kernel(const uint4 *__rest
     }
 }
 
-// Row sums of squares from the sums of squares of their 32-column blocks (what the dgrad epilogue
-// emits for the dX it has just written): blocks[b * R + row], b < nb, added pairwise, neighbours
-// first, the upper levels of the same tree a sweep over the row forms.  Neighbouring threads take
-// neighbouring rows, so their reads are neighbours; rows of samples whose sample_keep byte is 0 are
-// not read and get 0.  Up to kMaxSiblings outputs receive the same values (sibling layers share their G).
+// Row sums of squares from the sums of squares of their 64-column blocks (what the dgrad epilogue
+// emits for the dX it has just written), added pairwise, neighbours first: the upper levels of the
+// same tree a sweep over the row forms.  Layout: four neighbouring blocks of a row lie side by
+// side, blocks[((b / 4) * R + row) * 4 + b % 4], b < nb = ceil(K/64), so that a thread fetches
+// 16 bytes at a time and neighbouring threads (neighbouring rows) fetch neighbouring 16 bytes; the
+// slots b >= nb of the last group are never written and never used.  Rows of samples whose
+// sample_keep byte is 0 are not read and get 0.  Up to kMaxSiblings outputs receive the same values
+// (sibling layers share their G).
 struct RowsFromBlocks {
     float *out[kMaxSiblings];
+    float *gnorm[kMaxSiblings];   // sample norms too (sample_norms_from_blocks_kernel only)
 };
 
-__global__ __launch_bounds__(256) void rows_from_blocks_kernel(const float *__restrict__ blocks, int64_t R, int nb,
+// The leaves first + 4 * g0 .. of one row, groups g0 <= g < g1, pushed in order (eight loads in flight).
+__device__ __forceinline__ float block_subtree(const float4 *__restrict__ blocks4, int64_t R, int64_t row, int g0, int g1,
+                                               int nb)
+{
+    PairwiseStream<12> leaves;
+    for (int g = g0; g < g1; g += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            v[k] = g + k < g1 ? blocks4[(int64_t)(g + k) * R + row] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int b = 4 * (g + k);
+            if (g + k < g1) {
+                leaves.push(v[k].x);
+                if (b + 1 < nb) leaves.push(v[k].y);
+                if (b + 2 < nb) leaves.push(v[k].z);
+                if (b + 3 < nb) leaves.push(v[k].w);
+            }
+        }
+    }
+    return leaves.finish();
+}
+
+__global__ __launch_bounds__(256) void rows_from_blocks_kernel(const float4 *__restrict__ blocks4, int64_t R, int nb,
                                                                int T, const uint8_t *__restrict__ sample_keep,
                                                                RowsFromBlocks outs, int n_out)
 {
     // 32 rows per workgroup, eight threads per row: thread (row, part) adds an aligned run of
-    // P/8 blocks (P = nb padded to a power of two), i.e. one subtree of the row's tree, with eight
-    // loads in flight; the eight subtree sums meet in LDS and are added as the top three levels.
+    // groups (a power of two of them), i.e. one subtree of the row's tree; the eight subtree sums
+    // meet in LDS and are added as the top three levels.
     __shared__ float part_sum[8][32];
     const int r_local = threadIdx.x & 31, part = threadIdx.x >> 5;
     const int64_t row = (int64_t)blockIdx.x * 32 + r_local;
-    int P = 1;
-    while (P < nb) P *= 2;
-    const int chunk = P >= 8 ? P / 8 : 1;
+    const int groups = (nb + 3) >> 2;
+    int Gp = 1;
+    while (Gp < groups) Gp *= 2;
+    const int chunk = Gp >= 8 ? Gp / 8 : 1;
     const bool live = row < R && (!sample_keep || sample_keep[row / T] != 0);
     float acc = 0.0f;
-    if (live) {
-        const int b0 = part * chunk, b1 = min(nb, b0 + chunk);
-        PairwiseStream<9> leaves;
-        for (int b = b0; b < b1; b += 8) {
-            float v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? blocks[(int64_t)(b + k) * R + row] : 0.0f;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (b + k < b1) leaves.push(v[k]);
-        }
-        acc = leaves.finish();
-    }
+    if (live && part * chunk < groups) acc = block_subtree(blocks4, R, row, part * chunk, min(groups, (part + 1) * chunk), nb);
     part_sum[part][r_local] = acc;
     __syncthreads();
     if (part == 0 && row < R) {
         const float total = ((part_sum[0][r_local] + part_sum[1][r_local]) + (part_sum[2][r_local] + part_sum[3][r_local])) +
                             ((part_sum[4][r_local] + part_sum[5][r_local]) + (part_sum[6][r_local] + part_sum[7][r_local]));
         for (int k = 0; k < n_out; ++k) outs.out[k][row] = live ? total : 0.0f;
+    }
+}
+
+// The same, and the sample norms ||G_i||_F = sqrt(sum of the sample's row sums) (Sec. 4.1) behind
+// them: one workgroup of 1024 threads per sample (T <= 1024 rows), `parts` threads per row.  The
+// row sums stay in LDS for the norm, which one wavefront adds in the order of sample_norm_wave
+// (value t on lane t mod 64, ascending t, exchange tree).  The chain row norms -> SampleA -> dX of
+// a layer inside a stack is then this launch and a dgrad that decides SampleA itself.
+__global__ __launch_bounds__(1024) void sample_norms_from_blocks_kernel(const float4 *__restrict__ blocks4, int64_t R, int nb,
+                                                                        int T, const uint8_t *__restrict__ sample_keep,
+                                                                        RowsFromBlocks outs, int n_out)
+{
+    __shared__ float part_sum[1024];
+    __shared__ float row_total[1024];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const bool live = !sample_keep || sample_keep[i] != 0;
+    const int groups = (nb + 3) >> 2;
+    int Gp = 1;
+    while (Gp < groups) Gp *= 2;
+    int parts = 1;
+    while (parts < 16 && parts * 2 * T <= 1024 && parts * 2 <= Gp) parts *= 2;
+    const int chunk = Gp / parts;
+    const int r = tid % T, part = tid / T;
+    const int64_t row = (int64_t)i * T + r;
+    float acc = 0.0f;
+    if (live && part < parts && part * chunk < groups)
+        acc = block_subtree(blocks4, R, row, part * chunk, min(groups, (part + 1) * chunk), nb);
+    part_sum[tid] = acc;
+    __syncthreads();
+    if (part == 0) {
+        // the parts of a row, pairwise (parts is a power of two, at most 16 with Gp >= parts)
+        float v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = k < parts ? part_sum[r + k * T] : 0.0f;
+#pragma unroll
+        for (int n = 16; n > 1; n /= 2)
+#pragma unroll
+            for (int k = 0; k < n / 2; ++k) v[k] = v[2 * k] + v[2 * k + 1];
+        const float total = live ? v[0] : 0.0f;
+        row_total[r] = total;
+        for (int k = 0; k < n_out; ++k) outs.out[k][row] = total;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        float sum = 0.0f;
+        for (int t = tid; t < T; t += 64) sum = sum + row_total[t];
+        const float norm = __builtin_sqrtf(wave_exchange_sum(sum));
+        if (tid == 0)
+            for (int k = 0; k < n_out; ++k) outs.gnorm[k][i] = norm;
     }
 }
 
@@ -201,8 +267,26 @@ vcas_status rows_from_blocks(const float *blocks, int64_t R, int K, int T, const
     if (n_out < 1 || n_out > kMaxSiblings) return VCAS_EINVAL;
     RowsFromBlocks o = {};
     for (int k = 0; k < n_out; ++k) o.out[k] = outs[k];
-    hipLaunchKernelGGL(rows_from_blocks_kernel, dim3((unsigned)((R + 31) / 32)), dim3(256), 0, st, blocks, R,
-                       (K + 31) / 32, T, keep, o, n_out);
+    hipLaunchKernelGGL(rows_from_blocks_kernel, dim3((unsigned)((R + 31) / 32)), dim3(256), 0, st,
+                       reinterpret_cast<const float4 *>(blocks), R, (K + 63) / 64, T, keep, o, n_out);
+    return launch_status();
+}
+
+// True where sample_norms_from_blocks applies.
+bool sample_norms_from_blocks_fits(int N, int T) { return T <= 1024 && N >= 1; }
+
+// Row sums (outs) and sample norms (gnorms) of N samples of T <= 1024 rows from the block sums.
+vcas_status sample_norms_from_blocks(const float *blocks, int N, int T, int K, const uint8_t *keep, float *const *outs,
+                                     float *const *gnorms, int n_out, hipStream_t st)
+{
+    if (n_out < 1 || n_out > kMaxSiblings || !sample_norms_from_blocks_fits(N, T)) return VCAS_EINVAL;
+    RowsFromBlocks o = {};
+    for (int k = 0; k < n_out; ++k) {
+        o.out[k] = outs[k];
+        o.gnorm[k] = gnorms[k];
+    }
+    hipLaunchKernelGGL(sample_norms_from_blocks_kernel, dim3((unsigned)N), dim3(1024), 0, st,
+                       reinterpret_cast<const float4 *>(blocks), (int64_t)N * T, (K + 63) / 64, T, keep, o, n_out);
     return launch_status();
 }
 

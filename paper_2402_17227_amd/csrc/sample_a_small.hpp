@@ -116,7 +116,8 @@ __device__ __forceinline__ SampleADecision sample_a_wave(float a, int N, double 
 // SampleA decided inside another kernel: where the row norms of G are, the budget N rho, the
 // random stream, and where the plan's SampleA fields go (written by one workgroup).
 struct InlineSampleA {
-    const float *gsq;   // null: off
+    const float *gsq;     // row sums of squares of G: the sample norms are taken here too
+    const float *norms;   // or the sample norms ||G_i||_F themselves; both null: off
     double budget;
     uint64_t seed;
     uint32_t layer, draw;

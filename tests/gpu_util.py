@@ -91,3 +91,19 @@ def compare_plan(got: dict, want) -> None:
         assert np.array_equal(got[name], getattr(want, name)), name
     assert got["cntA"] == want.idxA.size and got["cntW"] == want.idxW.size
     assert np.array_equal(got["idxA"], want.idxA) and np.array_equal(got["idxW"], want.idxW)
+
+
+def blocks_to_device_layout(blocks, fill=np.nan):
+    """[R, nb] block sums (the oracle's) -> the library's layout [ceil(nb/4), R, 4]: four neighbouring blocks of
+    a row side by side; the unused slots of the last group get `fill` (nobody may read them)."""
+    R, nb = blocks.shape
+    out = np.full(((nb + 3) // 4, R, 4), fill, np.float32)
+    for b in range(nb):
+        out[b // 4, :, b % 4] = blocks[:, b]
+    return out
+
+
+def blocks_from_device_layout(dev, nb):
+    """The inverse: [groups, R, 4] -> [R, nb]."""
+    a = dev.cpu().numpy() if hasattr(dev, "cpu") else np.asarray(dev)
+    return np.stack([a[b // 4, :, b % 4] for b in range(nb)], axis=1)

@@ -205,14 +205,15 @@ def test_full_size_block_in_the_chained_launch(vb, workload, block, fused):
     g2 = to_device(G2, BF16)
     g2.view(o.N, o.T, -1)[torch.from_numpy(~kept).cuda()] = float("nan")
     above = torch.from_numpy(want_o.maskA.astype(np.uint8)).cuda()
-    nb = (o.K_in + 31) // 32
-    blocks_o = torch.full((nb, o.R), float("nan"), device="cuda") if fused else None
+    from tests.gpu_util import blocks_to_device_layout, blocks_from_device_layout
+    nb = (o.K_in + 63) // 64
+    blocks_o = vb.make_sq_blocks(o.R, o.K_in, float("nan")) if fused else None
     want_blocks = g2_blocks = None
     if fused:
         want_blocks = oracle.block_sumsq(G2, BF16)                       # [R, nb]
         poisoned = want_blocks.copy()
         poisoned[np.repeat(~kept, o.T)] = np.nan                         # rows of dropped samples are never read
-        g2_blocks = torch.from_numpy(np.ascontiguousarray(poisoned.T)).cuda()
+        g2_blocks = torch.from_numpy(blocks_to_device_layout(poisoned)).cuda()
     entries, outs, keep, host = [], [], [], []
     for k, name in enumerate(["o", "v", "k", "q"]):
         sp = specs[name]
@@ -252,7 +253,7 @@ def test_full_size_block_in_the_chained_launch(vb, workload, block, fused):
         assert rel_l2_tiles(from_device(dW), want_dW) <= 1e-2
     if fused:
         rows = np.repeat(kept, o.T)
-        got_blocks = blocks_o.cpu().numpy().T
+        got_blocks = blocks_from_device_layout(blocks_o, nb)
         assert np.isnan(got_blocks[~rows]).all() and np.isfinite(got_blocks[rows]).all()
         num = np.abs(got_blocks[rows].astype(np.float64) - want_blocks[rows]).sum(axis=1)
         den = want_blocks[rows].astype(np.float64).sum(axis=1)

@@ -1,7 +1,8 @@
 """The norms of a layer's incoming gradient from the launch that produced it (Sec. 4: a sampler at every
 layer; Sec. 4.1: p_i ~ ||G_i||_F).  Inside a stack a layer's G is the dX the layer above has just written, so
-its dgrad epilogue adds up the squares of what it stores, by blocks of 32 columns, and the layer below adds the
-block sums instead of sweeping G again.  The summation order (pairwise, neighbours first) makes the two routes
+its dgrad epilogue adds up the squares of what it stores, by blocks of 64 columns, and the layer below adds the
+block sums instead of sweeping G again (and, inside a stack, takes the sample norms in the same launch and
+lets its dgrad decide SampleA).  The summation order (pairwise, neighbours first) makes the two routes
 agree bit for bit.
 
 Data flows from the oracle to the GPU only: the consumer is checked against the oracle on the oracle's own
@@ -39,6 +40,7 @@ def test_rows_from_blocks_bit_exact(vb, N, T, K):
     rng = np.random.default_rng(K + N)
     a = (rng.standard_normal((N * T, K)) * np.exp(rng.standard_normal((N * T, 1)))).astype(np.float32)
     A = workloads.f32_to_bf16_bits(a)
+    from tests.gpu_util import blocks_to_device_layout
     blocks = oracle.block_sumsq(A, BF16)
     keep = (rng.uniform(size=N) < 0.7).astype(np.uint8)
     keep[0] = 1
@@ -47,7 +49,7 @@ def test_rows_from_blocks_bit_exact(vb, N, T, K):
     for mask, src in ((None, blocks), (keep, poisoned)):
         sq = torch.full((N * T,), float("nan"), device="cuda")
         norm = torch.full((N,), float("nan"), device="cuda")
-        vb.vcas_row_norms_from_blocks(N, T, K, _dev(np.ascontiguousarray(src.T)), None if mask is None else _dev(mask), sq, norm)
+        vb.vcas_row_norms_from_blocks(N, T, K, _dev(blocks_to_device_layout(src)), None if mask is None else _dev(mask), sq, norm)
         torch.cuda.synchronize()
         want = oracle.row_sumsq(A, BF16, T, mask)
         assert np.array_equal(sq.cpu().numpy().view(np.uint32), want.view(np.uint32))
@@ -60,9 +62,9 @@ def test_rows_from_blocks_bit_exact(vb, N, T, K):
                                                     (33, 125, 3080, 200, 0.5, False),
                                                     (17, 128, 1024, 72, 1.0, True),      # 64x128 tiles, two stages
                                                     (6, 50, 264, 136, 0.7, False),       # 64x128 tiles, four stages
-                                                    (9, 64, 40, 72, 0.8, True)])         # one ragged block of 32 columns... and a bit
+                                                    (9, 64, 40, 72, 0.8, True)])         # less than one block of 64 columns
 def test_dgrad_block_sums(vb, N, T, kin, kout, frac, jac):
-    from tests.gpu_util import from_device, rel_l2_rows
+    from tests.gpu_util import from_device, rel_l2_rows, blocks_from_device_layout
     rng = np.random.default_rng(N * 1000 + kin)
     R = N * T
     G = workloads.f32_to_bf16_bits(rng.standard_normal((R, kout)).astype(np.float32))
@@ -75,11 +77,11 @@ def test_dgrad_block_sums(vb, N, T, kin, kout, frac, jac):
     idx_buf = np.full(N, -1, np.int32)
     idx_buf[:idxA.size] = idxA
     shape = vb.shape_of(N, T, kin, kout, BF16)
-    nb = (kin + 31) // 32
+    nb = (kin + 63) // 64
     g, w, pd, ix, cn = _dev(G, BF16), _dev(W, BF16), _dev(p), _dev(idx_buf), _dev(np.array([idxA.size], np.int32))
     jd = _dev(J, BF16) if jac else None
     dX = torch.full((R, kin), float("nan"), dtype=torch.bfloat16, device="cuda")
-    blocks = torch.full((nb, R), float("nan"), device="cuda")        # block-major
+    blocks = vb.make_sq_blocks(R, kin, float("nan"))
     vb.vcas_sampled_dgrad_norms(shape, g, w, pd, ix, cn, jd, dX, blocks)
     # the same dX as the call without the block sums
     ref = torch.full((R, kin), float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -92,7 +94,8 @@ def test_dgrad_block_sums(vb, N, T, kin, kout, frac, jac):
     want_dX = oracle.dgrad_jacobian(G, W, J, BF16, N, T, p, maskA) if jac else oracle.dgrad(G, W, BF16, N, T, p, maskA)
     assert rel_l2_rows(from_device(dX), want_dX) <= 1e-2
     kept_rows = np.repeat(maskA == 1, T)
-    got_blocks = blocks.cpu().numpy().T
+    got_blocks = blocks_from_device_layout(blocks, nb)
+    assert np.isnan(blocks.cpu().numpy().reshape(-1, R, 4)[-1][:, nb - 4 * ((nb - 1) // 4):]).all()   # unused slots untouched
     # rows of dropped samples are not written
     assert np.isnan(got_blocks[~kept_rows]).all() and np.isfinite(got_blocks[kept_rows]).all()
     # within the tolerance of dX of the oracle's block sums of its own dX (squares: twice the relative error)
@@ -112,13 +115,15 @@ def test_dgrad_block_sums(vb, N, T, kin, kout, frac, jac):
     assert torch.equal(sq_a.view(torch.int32), sq_b.view(torch.int32))
 
 
-def test_stack_takes_norms_from_the_layer_above(vb):
+@pytest.mark.parametrize("N,T", [(24, 64), (5, 300), (3, 1024), (70, 20), (2, 1100)])
+def test_stack_takes_norms_from_the_layer_above(vb, N, T):
     """A chain down -> up -> o -> (v, k, q): every entry's dX buffer is the next entry's G, the entries know
     which samples the one above kept and leave dropped rows unwritten.  With the block sums handed down the
     sweeps over G disappear for every entry but the first; plans, dX and dW must be the bits of the same stack
-    with the sweeps."""
+    with the sweeps.  Up to 64 samples of up to 1024 rows the pass over the block sums also leaves the sample
+    norms and dgrad decides SampleA (one workgroup per sample, 1 to 16 threads per row); beyond (the last two
+    cases) the row sums go through the SampleA launch as before."""
     from tests.gpu_util import to_device, plan_to_numpy
-    N, T = 24, 64
     # G of an entry is [R, K_out]; its dX is [R, K_in] and is the next entry's G: K_in(above) == K_out(below)
     chain = [("down", 264, 136), ("up", 136, 264), ("o", 136, 136), ("v", 200, 136), ("k", 200, 136), ("q", 200, 136)]
     runs = []
@@ -145,7 +150,7 @@ def test_stack_takes_norms_from_the_layer_above(vb):
             plan, ws = vb.Plan.allocate(N, T), vb.make_workspace(shape)
             dX = torch.full((N * T, kin), float("nan"), dtype=torch.bfloat16, device="cuda")
             dW = torch.full((kout, kin), float("nan"), dtype=torch.float32, device="cuda")
-            blocks = torch.full(((kin + 31) // 32, N * T), float("nan"), device="cuda") if fused else None
+            blocks = vb.make_sq_blocks(N * T, kin, float("nan")) if fused else None
             entries.append(vb.layer_args(shape, g, x, w, sp.rho, sp.nu, vb.Rng(sp.seed, sp.layer, 2), True, plan, dX, dW, ws,
                                          sibling=sib, kept_above=above, leave_dropped_rows=True,
                                          dx_sq_blocks=blocks, g_sq_blocks=gblocks))

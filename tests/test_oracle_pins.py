@@ -101,19 +101,20 @@ def test_row_sumsq_adds_neighbours_first(dtype):
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("K", [8, 40, 136, 768, 1000, 4096])
-def test_block_sums_are_subtrees_of_the_row_sum(dtype, K):
-    """Row norms in two stages (32-column block sums, then the blocks pairwise) give the bits of the one-stage
-    row sum, ragged last block and non-power-of-two block counts included; each block sum is the row sum of
-    the block taken as a row of its own; and the definition in fp64 pins both."""
+@pytest.mark.parametrize("width", [32, 64, 256])
+def test_block_sums_are_subtrees_of_the_row_sum(dtype, K, width):
+    """Row norms in two stages (sums over blocks of `width` columns, then the blocks pairwise) give the bits of
+    the one-stage row sum, ragged last block and non-power-of-two block counts included, whatever the width;
+    each block sum is the row sum of the block taken as a row of its own; and the definition in fp64 pins both."""
     rng = np.random.default_rng(K)
     a = (rng.standard_normal((7, K)) * np.exp(rng.standard_normal((7, 1)))).astype(np.float32)
     A = workloads.f32_to_bf16_bits(a) if dtype == BF16 else a
-    blocks = oracle.block_sumsq(A, dtype)
-    assert blocks.shape == (7, (K + 31) // 32)
+    blocks = oracle.block_sumsq(A, dtype, width)
+    assert blocks.shape == (7, (K + width - 1) // width)
     whole = oracle.row_sumsq(A, dtype)
     assert np.array_equal(oracle.rows_from_blocks(blocks).view(np.uint32), whole.view(np.uint32))
     for b in range(blocks.shape[1]):
-        piece = np.ascontiguousarray(A[:, 32 * b:32 * b + 32])
+        piece = np.ascontiguousarray(A[:, width * b:width * b + width])
         assert np.array_equal(oracle.row_sumsq(piece, dtype).view(np.uint32), blocks[:, b].view(np.uint32))
     np.testing.assert_allclose(blocks.astype(np.float64).sum(axis=1), oracle.row_sumsq_f64(A, dtype), rtol=1e-6)
     # dropped samples: zero, whatever their block sums hold
