@@ -320,12 +320,14 @@ def main():
                          "had produced it.  The default is the chain of a backward pass (Sec. 4: SampleA sits between the "
                          "layers, the gradient grows sparser on its way down): down's dX buffer is up's G, up's is o's, o's "
                          "is the G of V, K and Q, Q's is the next block's down's; every layer is told which samples the one "
-                         "above kept, leaves the rows of dropped samples unwritten, and takes the row norms of its G from "
-                         "the block sums the dgrad above left beside its dX; only the top layer's G is an input")
+                         "above kept, sweeps the rows of its G that exist for their norms and leaves the rows of dropped "
+                         "samples unwritten; only the top layer's G is an input")
     ap.add_argument("--chained", action="store_true", help="the default since the chain became the timed form; accepted and ignored")
-    ap.add_argument("--sweep-norms", action="store_true",
-                    help="chained stack: every layer sweeps its G for the row norms, as independent layers must, instead "
-                         "of taking them from the block sums of squares the dgrad above has left (the same bits)")
+    ap.add_argument("--fused-norms", action="store_true",
+                    help="chained stack: every dgrad also leaves the sums of squares of its dX by blocks of 64 columns; the "
+                         "entry below adds them to row sums and sample norms in one launch and its dgrad decides SampleA "
+                         "itself, instead of sweeping G and launching SampleA (the same bits; bf16 only)")
+    ap.add_argument("--sweep-norms", action="store_true", help="the default; accepted and ignored")
     ap.add_argument("--xsq-cached", action="store_true",
                     help="stack launch only: the squared row norms of X are taken before the timed region (as a forward "
                          "pass would, vcas_row_norms over every row) and handed to the weight halves; not the default, "
@@ -417,7 +419,7 @@ def main():
                 l.xsq_forward = torch.empty(l.spec.R, dtype=torch.float32, device="cuda")
                 vb.vcas_row_norms(l.shape, None, l.X, None, None, l.xsq_forward, None)
         entries, prev = [], None
-        fused_norms = args.chained and not args.sweep_norms and specs[0].dtype == workloads.BF16
+        fused_norms = args.chained and args.fused_norms and specs[0].dtype == workloads.BF16
         for l in layers:
             sib = not args.no_siblings and _is_sibling(l.spec.name)
             G, above, g_blocks = l.G, None, None

@@ -189,7 +189,7 @@ def test_full_size_block_in_the_chained_launch(vb, workload, block, fused):
     siblings that take its dX as their G, know which samples it kept (kept_above) and leave the rows of the
     samples they drop unwritten.  The oracle computes the out-projection on its own and hands its dX (bf16) to
     V, K, Q; the GPU gets the same tensor with NaN in the rows of dropped samples, in one stack call.
-    fused (the benchmark's default form): the out-projection's dgrad also leaves the block sums of squares of
+    fused (bench.py --fused-norms): the out-projection's dgrad also leaves the block sums of squares of
     its dX, and V, K, Q take the row norms of their G from block sums instead of sweeping it.  Data flows from
     the oracle to the GPU only: the block sums handed to V, K, Q are the oracle's, of the oracle's dX; what the
     GPU's dgrad emitted is checked against those within the tolerance of dX, and bit for bit against a sweep of
