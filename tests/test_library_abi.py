@@ -38,6 +38,15 @@ def test_workspace_bytes_and_status_strings(vb):
     assert b"null" in vb.lib().vcas_status_string(2)
 
 
+def test_block_sum_buffer_size(vb):
+    """Four neighbouring 64-column blocks of a row share 16 bytes: ceil(ceil(K/64)/4) groups of R x 16 bytes."""
+    assert vb.vcas_sq_blocks_bytes(16384, 1024) == 16384 * 16 * 4
+    assert vb.vcas_sq_blocks_bytes(16384, 4096) == 16384 * 16 * 16
+    assert vb.vcas_sq_blocks_bytes(100, 8) == 100 * 16            # less than one block
+    assert vb.vcas_sq_blocks_bytes(100, 264) == 100 * 16 * 2      # five blocks: two groups
+    assert vb.vcas_sq_blocks_bytes(0, 64) == 0 and vb.vcas_sq_blocks_bytes(64, 0) == 0
+
+
 def test_bad_arguments_are_rejected_on_the_host(vb):
     lib = vb.lib()
     null = C.c_void_p(0)
