@@ -115,7 +115,7 @@ def test_dgrad_block_sums(vb, N, T, kin, kout, frac, jac):
     assert torch.equal(sq_a.view(torch.int32), sq_b.view(torch.int32))
 
 
-@pytest.mark.parametrize("N,T", [(24, 64), (5, 300), (3, 1024), (70, 20), (2, 1100)])
+@pytest.mark.parametrize("N,T", [(24, 64), (5, 300), (3, 1024), (6, 1), (64, 16), (70, 20), (2, 1100)])
 def test_stack_takes_norms_from_the_layer_above(vb, N, T):
     """A chain down -> up -> o -> (v, k, q): every entry's dX buffer is the next entry's G, the entries know
     which samples the one above kept and leave dropped rows unwritten.  With the block sums handed down the
