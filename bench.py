@@ -529,7 +529,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                 "frac": achieved / peak, "traffic": traffic,
                 "traffic_source": (f"{traffic_src}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --counters-pass`, "
-                                   "taken with the build that file names, not measured in this run") if traffic_src else None,
+                                   "taken with the build of the commit that last changed that file, not measured in this run") if traffic_src else None,
                 "algorithmic_bytes": alg_bytes, "avg_launch_us": avg_ms * 1e3,
                 "launches_per_step": dg_per_step if name.startswith("dgrad") else wg_per_step,
                 "dgrad_ms_per_step": dg_total, "wgrad_ms_per_step": wg_total}
