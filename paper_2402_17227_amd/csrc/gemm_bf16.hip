@@ -55,8 +55,12 @@ constexpr int kIdxStaged = 1024;   // kept-sample indices a workgroup stages in 
 // grid: 1-D, tiles_n * (ceil(R/BM) + 1) + 8 workgroups.  The first ceil8(compute
 // tiles) ids compute (spread over the XCDs in contiguous runs), the following
 // ones write the zero rows of dropped samples, the rest exit.
-// SPQ: the loads of the next step are spread over the MFMAs of the first SPQ
-// quarters of the current one (0: all issued right after the barrier).
+// SPQ >= 0: one barrier at the top of every step; the loads of the next step are spread over the
+// MFMAs of the first SPQ quarters of the current one (0: all issued right after the barrier).
+// SPQ < 0 (two stages only): the barrier sits ahead of the step's LAST k-slice, the loads of the
+// step after next go out one per -SPQ MFMAs from there, and the next step's first fragments are
+// read under the last slice's MFMAs (256x256, one workgroup per CU: nothing else covers the
+// wait for LDS behind a barrier there).
 template <int BM, int BN, int WM, int WN, int NS, int SPQ>
 __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, const uint16_t *__restrict__ W,
                                                 const float *__restrict__ p, const int32_t *__restrict__ idxA,
@@ -242,7 +246,7 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
 
     const int r32 = lane & 31, h = lane >> 5;
     const int blk = lane >> 4, sl = lane & 15;    // 16-lane block and lane within it
-    constexpr int KS = BK / 16, MM = TM * TN, SPAN = KS * MM * SPQ / 4;
+    constexpr int KS = BK / 16, MM = TM * TN, SPAN = KS * MM * (SPQ > 0 ? SPQ : 0) / 4;
     // One contraction step on stage `stage`; the loads of step `nstep` go to stage `nstage`.
     // Fragments of two k-slices are read ahead; load d goes out after MFMA number d*SPAN/LOADS.
     auto step_body = [&](int stage, int nstage, int nstep) {
@@ -296,16 +300,86 @@ __device__ __forceinline__ void dgrad_bf16_body(const uint16_t *__restrict__ G, 
         }
     };
 
-    for (int s = 0; s < steps; ++s) {
-        // the NS-2 younger steps may stay in flight; step s must have landed
-        wait_loads_outstanding<(NS - 2) * LOADS>();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        const int nxt = s + NS - 1;
-        __builtin_amdgcn_sched_barrier(0);
-        step_body(s % NS, nxt % NS, nxt < steps ? nxt : steps + 64);
-        __builtin_amdgcn_sched_barrier(0);
+    if constexpr (SPQ < 0) {
+        // Two stages, the barrier ahead of the step's LAST k-slice.  By then every wavefront holds that
+        // slice's fragments in registers, so the stage is free: the loads of step s+2 start there (one
+        // per -SPQ MFMAs, running on into the next step's slices), and the first fragments of step s+1
+        // are read under the last slice's MFMAs, so that no wavefront sits behind the barrier waiting for LDS.
+        constexpr int EVERY = -SPQ;
+        static_assert(NS == 2 && KS >= 2 && KS % 2 == 0, "two fragment sets alternate over an even number of slices");
+        static_assert(LOADS * EVERY <= KS * MM, "a step's loads are all issued before its barrier");
+        constexpr int AT_ONCE = MM / EVERY < LOADS ? MM / EVERY : LOADS;   // loads that go out during a last slice
+        bf16x8 a[2][TM], b[2][TN];
+        auto read_frags = [&](int stage, int ks, bf16x8(&fa)[TM], bf16x8(&fb)[TN]) {
+            const unsigned char *tileA = smem + stage * STAGE;
+            const unsigned char *tileB = tileA + B_AT;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(tileA + lds_off(wm0 + i * 32 + r32, ks * 2 + h));
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                bf16x4 half[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int k = ks * 16 + (blk >> 1) * 8 + e * 4 + (sl >> 2);
+                    const int col = wn0 + i * 32 + (blk & 1) * 16 + (sl & 3) * 4;
+                    const unsigned char *src = tileB + k * B_PITCH + (((col >> 3) ^ wswz(k)) << 4) + (col & 7) * 2;
+                    half[e] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4 *)(src));
+                }
+                fb[i] = __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        };
+        wait_loads_outstanding<0>();
+        __syncthreads();                           // step 0 has landed
+#pragma unroll
+        for (int d = 0; d < AT_ONCE; ++d) issue_nth(d, 1, 1 < steps ? 1 : steps + 64);
+        read_frags(0, 0, a[0], b[0]);
+        for (int s = 0; s < steps; ++s) {
+            const int cur = s & 1;
+            const int after = s + 1 < steps ? s + 1 : steps + 64, after2 = s + 2 < steps ? s + 2 : steps + 64;
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(cur, 1, a[1], b[1]);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    wait_loads_outstanding<0>();   // step s+1: all of its loads have been issued by now
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and this stage has been read
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_sched_barrier(0);
+                    read_frags(cur ^ 1, 0, a[0], b[0]);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+                        // MFMAs counted from the start of a last slice: that slice, then the slices of the next step
+                        const int m = (ks == KS - 1 ? 0 : (ks + 1) * MM) + i * TN + j;
+                        if (m % EVERY == 0 && m / EVERY < LOADS) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (ks == KS - 1) issue_nth(m / EVERY, cur, after2);
+                            else issue_nth(m / EVERY, cur ^ 1, after);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                if (ks + 2 < KS) read_frags(cur, ks + 2, a[ks & 1], b[ks & 1]);
+            }
+        }
+    } else {
+        for (int s = 0; s < steps; ++s) {
+            // the NS-2 younger steps may stay in flight; step s must have landed
+            wait_loads_outstanding<(NS - 2) * LOADS>();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int nxt = s + NS - 1;
+            __builtin_amdgcn_sched_barrier(0);
+            step_body(s % NS, nxt % NS, nxt < steps ? nxt : steps + 64);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     wait_loads_outstanding<0>();
 
@@ -513,7 +587,7 @@ vcas_status dgrad_bf16_group(const vcas_shape &s, const DgradProblem *probs, int
     const int64_t rows = expected_rows > 0 && expected_rows < R ? expected_rows : R;
     const int64_t tiles256 = n * ((rows + 255) / 256) * ((s.K_in + 255) / 256);
     const int64_t tiles128 = n * ((rows + 127) / 128) * ((s.K_in + 127) / 128);
-    if (tiles256 >= 128) return launch_dgrad_group<256, 256, 2, 4, 2, 1, 2>(s, grp, n, fill, st);
+    if (tiles256 >= 128) return launch_dgrad_group<256, 256, 2, 4, 2, 1, -1>(s, grp, n, fill, st);
     if (tiles128 > 256) return launch_dgrad_group<128, 128, 2, 2, 2, 2, 4>(s, grp, n, fill, st);
     const int64_t tiles64 = n * ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad_group<64, 128, 2, 2, 2, 2, 0>(s, grp, n, fill, st);
@@ -551,7 +625,7 @@ vcas_status dgrad_bf16(const vcas_shape &s, const void *G, const void *W, const 
     // without an expectation (the kept count is known on the device only) the tiles of ALL rows are counted, and a
     // kernel picked for them may find half of them empty: the larger tile then needs more of them to pay
     if (tiles256 >= (expected_rows > 0 ? 128 : 192))
-        return launch_dgrad<256, 256, 2, 4, 2, 1, 2>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
+        return launch_dgrad<256, 256, 2, 4, 2, 1, -1>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
     if (tiles128 > 256) return launch_dgrad<128, 128, 2, 2, 2, 2, 4>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
     const int64_t tiles64 = ((rows + 63) / 64) * ((s.K_in + 127) / 128);
     if (tiles64 > 256) return launch_dgrad<64, 128, 2, 2, 2, 2, 0>(s, G, W, p, idxA, cntA, dX, J, fill, sa, sq_blocks, st);
