@@ -202,6 +202,10 @@ def test_dgrad_never_reads_rows_of_dropped_samples(vb, dtype, N, T, kin, kout):
                                                 (17, 128, 2040, 136, 0.6),
                                                 (33, 125, 3080, 200, 1.0),     # 256x256 tiles, ragged rows and columns
                                                 (33, 125, 3080, 200, 0.5),
+                                                (33, 125, 3080, 8, 1.0),       # 256x256 tiles, a single ragged contraction step
+                                                (33, 125, 3080, 64, 1.0),      # ... exactly one step
+                                                (33, 125, 3080, 72, 0.5),      # ... two steps, the second ragged
+                                                (33, 125, 3080, 192, 1.0),     # ... three steps
                                                 (17, 128, 1024, 72, 1.0),      # 64x128 tiles, two stages
                                                 (1100, 4, 264, 72, 0.7)])     # more kept samples than are staged in LDS
 def test_dgrad_bf16_tile_variants(vb, N, T, kin, kout, frac):
